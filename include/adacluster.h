@@ -1,0 +1,193 @@
+/*
+ * adacluster.h -- C ABI of the MI355X (gfx950) clustered sparse-attention library.
+ *
+ * The library implements the attention-layer replacement of AdaCluster
+ * (Algorithm 3 of the paper): queries are clustered on the unit sphere, keys by
+ * the multi-stage threshold-adaptive k-means of Algorithm 1, critical key
+ * clusters are chosen per query cluster from centroid-level scores (Eq. 1 / Eq. 2,
+ * Algorithm 2) and attention runs only over the selected clusters.
+ *
+ * General conventions
+ *   - Every pointer named in a signature is a DEVICE pointer unless the comment
+ *     says "host".  Tensors are contiguous, row-major.  Q, K, V, O are [H,N,d] in
+ *     the dtype named by params.dtype; d is 64 or 128; N is arbitrary (>= 1).
+ *   - The caller owns every buffer.  The library allocates no device memory: all
+ *     scratch lives in the caller's workspace `ws` of at least
+ *     adacluster_workspace_bytes() bytes, 256-byte aligned.  Workspace contents
+ *     are undefined after a call.  Output buffers are fully overwritten.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream).  Calls are asynchronous except adacluster_kcluster and
+ *     adacluster_attn, which synchronise the stream once per clustering stage to
+ *     read a few integers back (the stage loop of Algorithm 1 has a data-dependent
+ *     trip count).
+ *   - Every function returns 0 on success or a negative ADACLUSTER_E_* code.  On
+ *     an argument error nothing is launched.  adacluster_last_error() returns a
+ *     message for the calling thread's last failure.  No function throws, aborts
+ *     or prints.
+ *   - Calls that share a workspace must not overlap in time.
+ */
+#ifndef ADACLUSTER_H
+#define ADACLUSTER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ADACLUSTER_OK             0
+#define ADACLUSTER_E_BADARG      -1   /* NULL pointer or value out of range          */
+#define ADACLUSTER_E_BADSHAPE    -2   /* H, N, d or a cluster count is not supported */
+#define ADACLUSTER_E_BADDTYPE    -3
+#define ADACLUSTER_E_WORKSPACE   -4   /* workspace NULL, misaligned or too small     */
+#define ADACLUSTER_E_UNSUPPORTED -5
+#define ADACLUSTER_E_INTERNAL    -6   /* a HIP runtime call failed                   */
+
+#define ADACLUSTER_F32  0
+#define ADACLUSTER_BF16 1
+
+#define ADACLUSTER_SCORE_TQ  0   /* Alg. 2 on centroids: Q+ (K+)^T + Q- (K-)^T            */
+#define ADACLUSTER_SCORE_BOX 1   /* Eq. 1 on each cluster's per-dimension min/max box      */
+#define ADACLUSTER_SCORE_DOT 2   /* plain centroid dot product (the "w/o Quest" ablation)  */
+
+#define ADACLUSTER_SELECT_TOPK 0 /* Alg. 3 line 8 */
+#define ADACLUSTER_SELECT_TOPP 1 /* smallest set of clusters holding a share top_p of the
+                                    size-weighted softmax mass of the centroid scores     */
+
+#define ADACLUSTER_MAX_STAGES 16
+
+/* Problem and method parameters (Alg. 3 inputs: tau, topk, N_max; Sec. 4.1 settings). */
+typedef struct adacluster_params {
+  int32_t H, N, d;              /* heads, tokens, head width (64 or 128)                       */
+  int32_t dtype;                /* ADACLUSTER_F32 or ADACLUSTER_BF16 (Q,K,V,O)                  */
+  int32_t q_clusters;           /* number of query clusters (paper: 65); 1 <= q_clusters <= N   */
+  int32_t q_iters;              /* assignment passes of the query k-means (>= 1)                */
+  int32_t k_iters;              /* assignment passes of each key k-means stage (>= 1)           */
+  int32_t q_init_mode;          /* 0: strided sample of the queries; 1: q_centroids passed in   */
+  int32_t k_m0;                 /* key centres of the first stage ("Initial K", paper: 100)     */
+  int32_t k_m_min;              /* floor for the centre count of later stages                   */
+  int32_t k_max_clusters;       /* N_max of Alg. 1.  Centre buffers hold cap = N_max + k_m0 rows */
+  int32_t k_max_stages;         /* at most this many stages (<= ADACLUSTER_MAX_STAGES)          */
+  float   tau_abs;              /* > 0: absolute distance threshold tau                         */
+  float   tau_factor;           /* used when tau_abs <= 0: tau = factor x mean first-stage
+                                   token-to-centre distance over all heads (paper: 1.5)        */
+  float   min_unassigned_frac;  /* stop staging once |U| <= floor(frac*N); 0 = Alg. 1 literally */
+  int32_t score_mode;           /* ADACLUSTER_SCORE_*                                           */
+  int32_t select_mode;          /* ADACLUSTER_SELECT_*                                          */
+  int32_t topk;                 /* clusters kept per query cluster (top-k mode), >= 1           */
+  float   top_p;                /* mass share (top-p mode), in (0,1]                            */
+  float   softmax_scale;        /* <= 0 means 1/sqrt(d)                                         */
+} adacluster_params;
+
+/* rows of every per-head key-centre buffer: k_max_clusters + k_m0 */
+int adacluster_centroid_capacity(const adacluster_params* p);
+
+/* Bytes of workspace any entry point needs for these parameters (host pointer out). */
+int adacluster_workspace_bytes(const adacluster_params* p, size_t* bytes);
+
+/* Copies the calling thread's last error message into buf (host), NUL-terminated. */
+int adacluster_last_error(char* buf, size_t buf_bytes);
+
+/*
+ * Query clustering: KMeans(Normalize(Q)), Alg. 3 line 1 / Sec. 3.1.
+ *   Q                  [H,N,d]   in
+ *   q_labels           [H,N]     out  cluster of every query (arg-max cosine to q_assign_centroids)
+ *   q_centroids        [H,Cq,d]  in (q_init_mode 1: initial centres) / out: unit-norm member means
+ *                                under q_labels (empty cluster: previous centre)
+ *   q_assign_centroids [H,Cq,d]  out  centres the last assignment pass used, as fp32 holding
+ *                                values representable in the I/O dtype
+ *   q_sizes            [H,Cq]    out  members per cluster
+ *   q_mean_norm        [H,Cq]    out  mean ||q|| of the members (0 for an empty cluster)
+ */
+int adacluster_qcluster(const adacluster_params* p, const void* Q,
+                        int32_t* q_labels, float* q_centroids, float* q_assign_centroids,
+                        int32_t* q_sizes, float* q_mean_norm,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Key clustering: MultiStageClustering(K, tau, N_max), Algorithm 1.  cap = capacity above.
+ *   K                  [H,N,d]    in
+ *   k_labels           [H,N]      out  nearest centre among all stage centres (Alg. 1 last step)
+ *   k_centroids        [H,cap,d]  out  member means under k_labels (rows >= k_count undefined;
+ *                                 empty cluster: its stage centre)
+ *   k_assign_centroids [H,cap,d]  out  the stage centres, in stage order (what k_labels is the
+ *                                 arg-min of), fp32 holding I/O-dtype-representable values
+ *   k_box_min,k_box_max[H,cap,d]  out  per-dimension member extremes; both may be NULL
+ *   k_sizes            [H,cap]    out  members per cluster (0 beyond k_count)
+ *   k_count            [H]        out  number of centres |C|
+ *   full_flag          [H]        out  1 iff staging stopped on |C| >= N_max with tokens left (F)
+ *   k_stage_offs       [H,ADACLUSTER_MAX_STAGES+1] out  running centre count after each stage,
+ *                                 unused entries = k_count; may be NULL
+ *   k_stage_of         [H,N]      out  stage at which a token fell within tau (-1: never); may be NULL
+ *   tau_used           [1]        out  the threshold applied (tau_abs, or the derived value)
+ */
+int adacluster_kcluster(const adacluster_params* p, const void* K,
+                        int32_t* k_labels, float* k_centroids, float* k_assign_centroids,
+                        float* k_box_min, float* k_box_max,
+                        int32_t* k_sizes, int32_t* k_count, int32_t* full_flag,
+                        int32_t* k_stage_offs, int32_t* k_stage_of, float* tau_used,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Critical-cluster selection: centroid scores (Eq. 1 / Eq. 2, Alg. 2) and arg-top-k (Alg. 3
+ * line 8) or the top-p budget.  Scores are evaluated in fp64 with the contraction summed in
+ * ascending dimension order, so the index sets are reproducible bit for bit.
+ *   q_centroids [H,Cq,d], q_mean_norm [H,Cq]              in (outputs of adacluster_qcluster)
+ *   k_centroids, k_box_min, k_box_max [H,cap,d]           in (boxes only read in BOX mode)
+ *   k_sizes [H,cap], k_count [H], full_flag [H]           in
+ *   sel_idx [H,Cq,cap]  out  ascending key-cluster ids per query cluster (first sel_cnt entries)
+ *   sel_cnt [H,Cq]      out
+ * Empty key clusters are never selected; a head with full_flag set selects every non-empty one.
+ */
+int adacluster_select(const adacluster_params* p,
+                      const float* q_centroids, const float* q_mean_norm,
+                      const float* k_centroids, const float* k_box_min, const float* k_box_max,
+                      const int32_t* k_sizes, const int32_t* k_count, const int32_t* full_flag,
+                      int32_t* sel_idx, int32_t* sel_cnt,
+                      void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Attention over the selected clusters (Alg. 3 lines 9-10): for a query n in query cluster i,
+ *   O_n = sum over keys m whose cluster is in sel(i) of softmax_m(scale * q_n . k_m) v_m,
+ * with the raw (un-normalised) query.  A query cluster with an empty selection yields zeros.
+ *   Q,K,V [H,N,d] in;  q_labels,k_labels [H,N] in (values in [0,Cq) and [0,k_count[h]));
+ *   k_count [H] in;  sel_idx [H,Cq,cap], sel_cnt [H,Cq] in (ascending, distinct);
+ *   O [H,N,d] out, original token order.
+ */
+int adacluster_sparse_attn(const adacluster_params* p,
+                           const void* Q, const void* K, const void* V,
+                           const int32_t* q_labels, const int32_t* k_labels, const int32_t* k_count,
+                           const int32_t* sel_idx, const int32_t* sel_cnt,
+                           void* O, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * The whole of Algorithm 3 in one call: query clustering, Algorithm 1, selection, attention
+ * (heads whose flag F is set attend to every key).  Cluster outputs may each be NULL when the
+ * caller does not need them (they then live in the workspace); shapes as above.
+ */
+typedef struct adacluster_outputs {
+  int32_t* q_labels;  float* q_centroids;  float* q_assign_centroids;
+  int32_t* q_sizes;   float* q_mean_norm;
+  int32_t* k_labels;  float* k_centroids;  float* k_assign_centroids;
+  float* k_box_min;   float* k_box_max;
+  int32_t* k_sizes;   int32_t* k_count;    int32_t* full_flag;
+  int32_t* k_stage_offs; int32_t* k_stage_of; float* tau_used;
+  int32_t* sel_idx;   int32_t* sel_cnt;
+} adacluster_outputs;
+
+int adacluster_attn(const adacluster_params* p,
+                    const void* Q, const void* K, const void* V, void* O,
+                    const adacluster_outputs* outs /* host struct of device pointers, may be NULL */,
+                    void* ws, size_t ws_bytes, void* stream);
+
+/* Dense softmax attention on the same attention kernel (the F = True branch of Alg. 3 and the
+ * timing baseline): every query attends to every key. */
+int adacluster_dense_attn(const adacluster_params* p,
+                          const void* Q, const void* K, const void* V, void* O,
+                          void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADACLUSTER_H */

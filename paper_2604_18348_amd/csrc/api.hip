@@ -1,0 +1,417 @@
+// C ABI of the clustered sparse-attention library: argument checks, workspace layout and the
+// order in which the kernels of Algorithm 3 are enqueued.  No device memory is allocated here.
+#include "common.h"
+#include "launch.h"
+
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+using namespace adac;
+
+namespace {
+
+thread_local char g_err[256] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int check_params(const adacluster_params* p) {
+  if (!p) return fail(ADACLUSTER_E_BADARG, "params is NULL");
+  if (p->H < 1 || p->N < 1) return fail(ADACLUSTER_E_BADSHAPE, "H and N must be >= 1 (H=%d N=%d)", p->H, p->N);
+  if (p->H > 65535) return fail(ADACLUSTER_E_BADSHAPE, "H must be <= 65535");
+  if (p->d != 64 && p->d != 128) return fail(ADACLUSTER_E_BADSHAPE, "d must be 64 or 128 (d=%d)", p->d);
+  if (p->dtype != ADACLUSTER_F32 && p->dtype != ADACLUSTER_BF16) return fail(ADACLUSTER_E_BADDTYPE, "unknown dtype %d", p->dtype);
+  if ((long long)p->N * p->d * 4 >= (1ll << 40)) return fail(ADACLUSTER_E_BADSHAPE, "N too large");
+  if (p->q_clusters < 1 || p->q_clusters > p->N) return fail(ADACLUSTER_E_BADSHAPE, "q_clusters must be in [1,N]");
+  if (p->q_clusters > 4096) return fail(ADACLUSTER_E_BADSHAPE, "q_clusters must be <= 4096");
+  if (p->q_iters < 1 || p->k_iters < 1) return fail(ADACLUSTER_E_BADARG, "q_iters and k_iters must be >= 1");
+  if (p->q_init_mode != 0 && p->q_init_mode != 1) return fail(ADACLUSTER_E_BADARG, "q_init_mode must be 0 or 1");
+  if (p->k_m0 < 1 || p->k_m0 > p->N) return fail(ADACLUSTER_E_BADSHAPE, "k_m0 must be in [1,N]");
+  if (p->k_m_min < 1 || p->k_m_min > p->k_m0) return fail(ADACLUSTER_E_BADARG, "k_m_min must be in [1,k_m0]");
+  if (p->k_max_clusters < 1) return fail(ADACLUSTER_E_BADARG, "k_max_clusters must be >= 1");
+  if (p->k_m0 > p->k_max_clusters) return fail(ADACLUSTER_E_BADARG, "k_m0 must not exceed k_max_clusters");
+  if ((long long)p->k_max_clusters + p->k_m0 > 7168) return fail(ADACLUSTER_E_BADSHAPE, "k_max_clusters + k_m0 must be <= 7168");
+  if (p->k_max_stages < 1 || p->k_max_stages > ADACLUSTER_MAX_STAGES) return fail(ADACLUSTER_E_BADARG, "k_max_stages must be in [1,%d]", ADACLUSTER_MAX_STAGES);
+  if (!(p->tau_abs > 0.f) && !(p->tau_factor > 0.f)) return fail(ADACLUSTER_E_BADARG, "tau_abs or tau_factor must be > 0");
+  if (!(p->min_unassigned_frac >= 0.f) || p->min_unassigned_frac > 1.f) return fail(ADACLUSTER_E_BADARG, "min_unassigned_frac must be in [0,1]");
+  if (p->score_mode < 0 || p->score_mode > 2) return fail(ADACLUSTER_E_BADARG, "unknown score_mode %d", p->score_mode);
+  if (p->select_mode < 0 || p->select_mode > 1) return fail(ADACLUSTER_E_BADARG, "unknown select_mode %d", p->select_mode);
+  if (p->topk < 1) return fail(ADACLUSTER_E_BADARG, "topk must be >= 1");
+  if (!(p->top_p > 0.f) || p->top_p > 1.f) return fail(ADACLUSTER_E_BADARG, "top_p must be in (0,1]");
+  return 0;
+}
+
+inline int capacity(const adacluster_params* p) { return p->k_max_clusters + p->k_m0; }
+inline size_t esize(const adacluster_params* p) { return p->dtype == ADACLUSTER_BF16 ? 2 : 4; }
+inline int parts_for(int n, int m) {
+  long long P = ((long long)n + (long long)m * 128 - 1) / ((long long)m * 128);
+  return (int)(P < 1 ? 1 : (P > 32 ? 32 : P));
+}
+
+// ---- workspace layout ----------------------------------------------------------------------
+struct Layout {
+  size_t total = 0;
+  size_t take(size_t bytes) { size_t o = total; total += align_up(bytes, 256); return o; }
+};
+
+struct WS {
+  unsigned char* base;
+  KState* kstate; int32_t* summary; float* tau; int32_t* u_prev;
+  void* cent_lp; float* bias; float* master;
+  int32_t* labels_tmp; float* dist2; int32_t* ulist[2]; int32_t* blockcnt; double* tau_part;
+  SortScratch sort; int32_t* perm_tmp; int32_t* offs_tmp;
+  float* psum; float* pnorm; float* pmin; float* pmax;
+  int32_t* perm_q; int32_t* offs_q; int32_t* perm_k; int32_t* offs_k;
+  void* Kp; void* Vp;
+  int32_t* rng_start; int32_t* rng_pre; int32_t* rng_cnt; int32_t* tiles; int32_t* ntiles;
+  // homes for outputs of the fused call the caller did not ask for
+  int32_t* q_labels; float* q_centroids; float* q_assign; int32_t* q_sizes; float* q_mean_norm;
+  int32_t* k_labels; float* k_centroids; float* k_assign; float* k_bmin; float* k_bmax;
+  int32_t* k_sizes; int32_t* k_count; int32_t* full_flag; int32_t* sel_idx; int32_t* sel_cnt;
+  int32_t* one_count;   // [H] constant key-cluster count for the dense plan
+};
+
+struct Dims {
+  int H, N, d, Cq, cap, capmax, nblk, nseg, maxtiles, maxr, prow, BM;
+};
+
+Dims dims_of(const adacluster_params* p) {
+  Dims D;
+  D.H = p->H; D.N = p->N; D.d = p->d; D.Cq = p->q_clusters; D.cap = capacity(p);
+  D.capmax = D.cap > D.Cq ? D.cap : D.Cq;
+  D.nblk = (p->N + 1023) / 1024;
+  D.nseg = (p->N + 1023) / 1024;
+  D.BM = attn_block_rows(p->dtype, p->d);
+  D.maxtiles = p->N / D.BM + D.Cq + 1;
+  D.maxr = D.cap;
+  D.prow = p->N / 128 + D.capmax + 34;
+  return D;
+}
+
+size_t layout(const adacluster_params* p, WS* w, unsigned char* base) {
+  const Dims D = dims_of(p);
+  const size_t H = D.H, N = D.N, d = D.d, es = esize(p);
+  Layout L;
+#define TAKE(field, type, bytes) { size_t o_ = L.take(bytes); if (w) w->field = (type)(base + o_); }
+  TAKE(kstate, KState*, H * sizeof(KState));
+  TAKE(summary, int32_t*, 64);
+  TAKE(tau, float*, 64);
+  TAKE(u_prev, int32_t*, H * 4);
+  TAKE(cent_lp, void*, H * D.capmax * d * es);
+  TAKE(bias, float*, H * D.capmax * 4);
+  TAKE(master, float*, H * (size_t)(p->k_m0 > D.Cq ? p->k_m0 : D.Cq) * d * 4);
+  TAKE(labels_tmp, int32_t*, H * N * 4);
+  TAKE(dist2, float*, H * N * 4);
+  TAKE(ulist[0], int32_t*, H * N * 4);
+  TAKE(ulist[1], int32_t*, H * N * 4);
+  TAKE(blockcnt, int32_t*, H * D.nblk * 4);
+  TAKE(tau_part, double*, H * D.nblk * 8);
+  TAKE(sort.hist, int32_t*, H * D.nseg * 128 * 4);
+  TAKE(sort.lab_a, int32_t*, H * N * 4);
+  TAKE(sort.val_a, int32_t*, H * N * 4);
+  TAKE(sort.lab_b, int32_t*, H * N * 4);
+  TAKE(perm_tmp, int32_t*, H * N * 4);
+  TAKE(offs_tmp, int32_t*, H * (size_t)(D.capmax + 1) * 4);
+  TAKE(psum, float*, H * (size_t)D.prow * d * 4);
+  TAKE(pnorm, float*, H * (size_t)D.prow * 4);
+  TAKE(pmin, float*, H * (size_t)D.prow * d * 4);
+  TAKE(pmax, float*, H * (size_t)D.prow * d * 4);
+  TAKE(perm_q, int32_t*, H * N * 4);
+  TAKE(offs_q, int32_t*, H * (size_t)(D.Cq + 1) * 4);
+  TAKE(perm_k, int32_t*, H * N * 4);
+  TAKE(offs_k, int32_t*, H * (size_t)(D.cap + 1) * 4);
+  TAKE(Kp, void*, H * N * d * es);
+  TAKE(Vp, void*, H * N * d * es);
+  TAKE(rng_start, int32_t*, H * (size_t)D.Cq * D.maxr * 4);
+  TAKE(rng_pre, int32_t*, H * (size_t)D.Cq * (D.maxr + 1) * 4);
+  TAKE(rng_cnt, int32_t*, H * (size_t)D.Cq * 4);
+  TAKE(tiles, int32_t*, H * (size_t)D.maxtiles * 3 * 4);
+  TAKE(ntiles, int32_t*, H * 4);
+  TAKE(q_labels, int32_t*, H * N * 4);
+  TAKE(q_centroids, float*, H * (size_t)D.Cq * d * 4);
+  TAKE(q_assign, float*, H * (size_t)D.Cq * d * 4);
+  TAKE(q_sizes, int32_t*, H * (size_t)D.Cq * 4);
+  TAKE(q_mean_norm, float*, H * (size_t)D.Cq * 4);
+  TAKE(k_labels, int32_t*, H * N * 4);
+  TAKE(k_centroids, float*, H * (size_t)D.cap * d * 4);
+  TAKE(k_assign, float*, H * (size_t)D.cap * d * 4);
+  TAKE(k_bmin, float*, H * (size_t)D.cap * d * 4);
+  TAKE(k_bmax, float*, H * (size_t)D.cap * d * 4);
+  TAKE(k_sizes, int32_t*, H * (size_t)D.cap * 4);
+  TAKE(k_count, int32_t*, H * 4);
+  TAKE(full_flag, int32_t*, H * 4);
+  TAKE(sel_idx, int32_t*, H * (size_t)D.Cq * D.cap * 4);
+  TAKE(sel_cnt, int32_t*, H * (size_t)D.Cq * 4);
+  TAKE(one_count, int32_t*, H * 4);
+#undef TAKE
+  if (w) w->base = base;
+  return L.total;
+}
+
+int check_ws(const adacluster_params* p, void* ws, size_t ws_bytes, WS* w) {
+  if (!ws) return fail(ADACLUSTER_E_WORKSPACE, "workspace is NULL");
+  if (((uintptr_t)ws) & 255) return fail(ADACLUSTER_E_WORKSPACE, "workspace must be 256-byte aligned");
+  const size_t need = layout(p, nullptr, nullptr);
+  if (ws_bytes < need) return fail(ADACLUSTER_E_WORKSPACE, "workspace too small: %zu < %zu bytes", ws_bytes, need);
+  layout(p, w, (unsigned char*)ws);
+  return 0;
+}
+
+#define RET_IF(expr) { int rc_ = (expr); if (rc_ != 0) return rc_ == ADACLUSTER_E_INTERNAL ? fail(rc_, "HIP launch failed: %s", hipGetErrorString(hipGetLastError())) : rc_; }
+
+// ---- query clustering ----------------------------------------------------------------------
+int run_qcluster(const adacluster_params* p, const WS& w, hipStream_t st, const void* Q, int32_t* q_labels,
+                 float* q_centroids, float* q_assign, int32_t* q_sizes, float* q_mean_norm) {
+  const Dims D = dims_of(p);
+  const int P = parts_for(D.N, D.Cq);
+  RET_IF(launch_init_centroids(st, p->dtype, D.d, D.H, D.N, 0, D.Cq, D.Cq, nullptr, nullptr, 1, p->q_init_mode,
+                               D.Cq, D.Cq, Q, q_centroids, w.cent_lp, q_assign, w.bias));
+  for (int it = 0; it < p->q_iters; ++it) {
+    RET_IF(launch_assign(st, p->dtype, D.d, D.H, D.N, D.N, 0, D.Cq, D.Cq, nullptr, nullptr, Q, w.cent_lp, w.bias,
+                         q_labels, nullptr));
+    RET_IF(launch_sort(st, D.H, D.N, D.N, D.Cq, q_labels, nullptr, nullptr, 0, nullptr, 0, nullptr, 0, w.perm_q,
+                       w.offs_q, D.Cq + 1, w.sort));
+    RET_IF(launch_seg_reduce(st, p->dtype, D.d, D.H, D.N, 0, D.Cq, D.Cq, P, nullptr, 1, 0, Q, w.perm_q, w.offs_q,
+                             D.Cq + 1, w.psum, w.pnorm, w.pmin, w.pmax));
+    const bool last = it == p->q_iters - 1;
+    if (!last) {
+      RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 0, D.Cq, D.Cq, P, D.Cq, D.Cq, nullptr, 1, 1, 0, w.offs_q,
+                             D.Cq + 1, w.psum, w.pnorm, w.pmin, w.pmax, q_centroids, w.cent_lp, q_assign, w.bias,
+                             nullptr, nullptr, nullptr, nullptr, nullptr, nullptr));
+    } else {
+      RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 0, D.Cq, D.Cq, P, D.Cq, D.Cq, nullptr, 1, 0, 0, w.offs_q,
+                             D.Cq + 1, w.psum, w.pnorm, w.pmin, w.pmax, nullptr, nullptr, nullptr, nullptr,
+                             q_centroids, nullptr, q_sizes, q_mean_norm, nullptr, nullptr));
+    }
+  }
+  return 0;
+}
+
+// ---- Algorithm 1 ---------------------------------------------------------------------------
+int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const void* K, int32_t* k_labels,
+                 float* k_centroids, float* k_assign, float* k_bmin, float* k_bmax, int32_t* k_sizes,
+                 int32_t* k_count, int32_t* full_flag, int32_t* k_stage_offs, int32_t* k_stage_of,
+                 float* tau_used) {
+  const Dims D = dims_of(p);
+  const int u_min = (int)floor((double)p->min_unassigned_frac * (double)p->N);
+  RET_IF(launch_kstate_init(st, w.kstate, D.H, D.N));
+  if (k_stage_of) RET_IF(launch_fill_i32(st, k_stage_of, (size_t)D.H * D.N, -1));
+  if (p->tau_abs > 0.f) RET_IF(launch_tau(st, D.H, D.N, nullptr, nullptr, 0.f, p->tau_abs, w.tau));
+  for (int t = 0; t <= p->k_max_stages; ++t) {
+    RET_IF(launch_kstage_begin(st, w.kstate, D.H, D.N, p->k_max_clusters, p->k_m0, p->k_m_min, p->k_max_stages,
+                               u_min, w.summary));
+    int32_t summ[3] = {0, 0, 0};
+    if (hipMemcpyAsync(summ, w.summary, sizeof(summ), hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess)
+      return fail(ADACLUSTER_E_INTERNAL, "stage read-back failed: %s", hipGetErrorString(hipGetLastError()));
+    const int n_active = summ[0], n_bound = summ[1], m_bound = summ[2];
+    if (n_active == 0) break;
+    const int32_t* ul = (t == 0) ? nullptr : w.ulist[t & 1];
+    int32_t* ul_next = w.ulist[(t + 1) & 1];
+    RET_IF(launch_init_centroids(st, p->dtype, D.d, D.H, D.N, 1, 0, m_bound, w.kstate, ul, 0, 0, D.cap, p->k_m0, K,
+                                 w.master, w.cent_lp, k_assign, w.bias));
+    const int P = parts_for(n_bound, m_bound);
+    for (int it = 0; it < p->k_iters; ++it) {
+      RET_IF(launch_assign(st, p->dtype, D.d, D.H, D.N, n_bound, 1, 0, D.cap, w.kstate, ul, K, w.cent_lp, w.bias,
+                           w.labels_tmp, w.dist2));
+      if (it < p->k_iters - 1) {
+        RET_IF(launch_sort(st, D.H, D.N, n_bound, m_bound, w.labels_tmp, ul, &w.kstate->ucount,
+                           sizeof(KState) / 4, &w.kstate->m_t, sizeof(KState) / 4, &w.kstate->active,
+                           sizeof(KState) / 4, w.perm_tmp, w.offs_tmp, D.capmax + 1, w.sort));
+        RET_IF(launch_seg_reduce(st, p->dtype, D.d, D.H, D.N, 1, 0, m_bound, P, w.kstate, 0, 0, K, w.perm_tmp,
+                                 w.offs_tmp, D.capmax + 1, w.psum, w.pnorm, w.pmin, w.pmax));
+        RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 1, 0, m_bound, P, D.cap, p->k_m0, w.kstate, 0, 1, 0,
+                               w.offs_tmp, D.capmax + 1, w.psum, w.pnorm, w.pmin, w.pmax, w.master, w.cent_lp,
+                               k_assign, w.bias, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr));
+      }
+    }
+    if (t == 0 && !(p->tau_abs > 0.f))
+      RET_IF(launch_tau(st, D.H, D.N, w.dist2, w.tau_part, p->tau_factor, 0.f, w.tau));
+    RET_IF(launch_filter(st, w.kstate, D.H, D.N, n_bound, w.dist2, w.tau, w.blockcnt, w.u_prev, ul, ul_next,
+                         k_stage_of, t));
+  }
+  RET_IF(launch_kstate_export(st, w.kstate, D.H, k_count, full_flag, k_stage_offs));
+  if (tau_used && hipMemcpyAsync(tau_used, w.tau, 4, hipMemcpyDeviceToDevice, st) != hipSuccess)
+    return fail(ADACLUSTER_E_INTERNAL, "tau copy failed");
+  // last step of Algorithm 1: nearest centre among all stage centres, then member statistics
+  RET_IF(launch_assign(st, p->dtype, D.d, D.H, D.N, D.N, 2, 0, D.cap, w.kstate, nullptr, K, w.cent_lp, w.bias,
+                       k_labels, nullptr));
+  RET_IF(launch_sort(st, D.H, D.N, D.N, D.cap, k_labels, nullptr, nullptr, 0, &w.kstate->ccount, sizeof(KState) / 4,
+                     nullptr, 0, w.perm_k, w.offs_k, D.cap + 1, w.sort));
+  const int want_box = (k_bmin && k_bmax) ? 1 : 0;
+  const int P = parts_for(D.N, D.cap);
+  RET_IF(launch_seg_reduce(st, p->dtype, D.d, D.H, D.N, 2, 0, D.cap, P, w.kstate, 0, want_box, K, w.perm_k, w.offs_k,
+                           D.cap + 1, w.psum, w.pnorm, w.pmin, w.pmax));
+  RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 2, 0, D.cap, P, D.cap, D.cap, w.kstate, 0, 0, want_box, w.offs_k,
+                         D.cap + 1, w.psum, w.pnorm, w.pmin, w.pmax, nullptr, nullptr, nullptr, nullptr, k_centroids,
+                         k_assign, k_sizes, nullptr, k_bmin, k_bmax));
+  return 0;
+}
+
+// ---- attention over selected clusters, given both sorts ---------------------------------------
+int run_attention(const adacluster_params* p, const WS& w, hipStream_t st, const void* Q, const void* K,
+                  const void* V, void* O, const int32_t* k_count, const int32_t* sel_idx, const int32_t* sel_cnt) {
+  const Dims D = dims_of(p);
+  const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)D.d);
+  RET_IF(launch_permute_kv(st, D.H, D.N, D.d * (int)esize(p), K, V, w.perm_k, w.Kp, w.Vp));
+  RET_IF(launch_plan_sparse(st, D.H, D.Cq, D.cap, D.maxr, D.maxtiles, D.BM, w.offs_q, D.Cq + 1, w.offs_k, D.cap + 1,
+                            k_count, sel_idx, sel_cnt, w.rng_start, w.rng_pre, w.rng_cnt, w.tiles, w.ntiles));
+  RET_IF(launch_attention(st, p->dtype, D.d, D.H, D.N, D.Cq, D.maxtiles, D.maxr, scale, Q, w.Kp, w.Vp, O, w.perm_q,
+                          w.tiles, w.ntiles, w.rng_start, w.rng_pre, w.rng_cnt));
+  return 0;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+extern "C" {
+
+int adacluster_centroid_capacity(const adacluster_params* p) {
+  int rc = check_params(p);
+  if (rc) return rc;
+  return capacity(p);
+}
+
+int adacluster_workspace_bytes(const adacluster_params* p, size_t* bytes) {
+  int rc = check_params(p);
+  if (rc) return rc;
+  if (!bytes) return fail(ADACLUSTER_E_BADARG, "bytes is NULL");
+  *bytes = layout(p, nullptr, nullptr);
+  return 0;
+}
+
+int adacluster_last_error(char* buf, size_t buf_bytes) {
+  if (!buf || buf_bytes == 0) return ADACLUSTER_E_BADARG;
+  strncpy(buf, g_err, buf_bytes - 1);
+  buf[buf_bytes - 1] = 0;
+  return 0;
+}
+
+int adacluster_qcluster(const adacluster_params* p, const void* Q, int32_t* q_labels, float* q_centroids,
+                        float* q_assign_centroids, int32_t* q_sizes, float* q_mean_norm, void* ws,
+                        size_t ws_bytes, void* stream) {
+  int rc = check_params(p);
+  if (rc) return rc;
+  if (!Q || !q_labels || !q_centroids || !q_assign_centroids || !q_sizes || !q_mean_norm)
+    return fail(ADACLUSTER_E_BADARG, "qcluster: NULL tensor pointer");
+  WS w;
+  if ((rc = check_ws(p, ws, ws_bytes, &w))) return rc;
+  return run_qcluster(p, w, (hipStream_t)stream, Q, q_labels, q_centroids, q_assign_centroids, q_sizes, q_mean_norm);
+}
+
+int adacluster_kcluster(const adacluster_params* p, const void* K, int32_t* k_labels, float* k_centroids,
+                        float* k_assign_centroids, float* k_box_min, float* k_box_max, int32_t* k_sizes,
+                        int32_t* k_count, int32_t* full_flag, int32_t* k_stage_offs, int32_t* k_stage_of,
+                        float* tau_used, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_params(p);
+  if (rc) return rc;
+  if (!K || !k_labels || !k_centroids || !k_assign_centroids || !k_sizes || !k_count || !full_flag || !tau_used)
+    return fail(ADACLUSTER_E_BADARG, "kcluster: NULL tensor pointer");
+  if ((k_box_min == nullptr) != (k_box_max == nullptr))
+    return fail(ADACLUSTER_E_BADARG, "kcluster: pass both boxes or neither");
+  WS w;
+  if ((rc = check_ws(p, ws, ws_bytes, &w))) return rc;
+  return run_kcluster(p, w, (hipStream_t)stream, K, k_labels, k_centroids, k_assign_centroids, k_box_min, k_box_max,
+                      k_sizes, k_count, full_flag, k_stage_offs, k_stage_of, tau_used);
+}
+
+int adacluster_select(const adacluster_params* p, const float* q_centroids, const float* q_mean_norm,
+                      const float* k_centroids, const float* k_box_min, const float* k_box_max,
+                      const int32_t* k_sizes, const int32_t* k_count, const int32_t* full_flag,
+                      int32_t* sel_idx, int32_t* sel_cnt, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_params(p);
+  if (rc) return rc;
+  if (!q_centroids || !q_mean_norm || !k_centroids || !k_sizes || !k_count || !full_flag || !sel_idx || !sel_cnt)
+    return fail(ADACLUSTER_E_BADARG, "select: NULL tensor pointer");
+  if (p->score_mode == ADACLUSTER_SCORE_BOX && (!k_box_min || !k_box_max))
+    return fail(ADACLUSTER_E_BADARG, "select: BOX scores need k_box_min and k_box_max");
+  WS w;
+  if ((rc = check_ws(p, ws, ws_bytes, &w))) return rc;
+  const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->d);
+  RET_IF(launch_select((hipStream_t)stream, p->H, p->q_clusters, capacity(p), p->d, p->score_mode, p->select_mode,
+                       p->topk, p->top_p, scale, q_centroids, q_mean_norm, k_centroids, k_box_min, k_box_max, k_sizes,
+                       k_count, full_flag, sel_idx, sel_cnt));
+  return 0;
+}
+
+int adacluster_sparse_attn(const adacluster_params* p, const void* Q, const void* K, const void* V,
+                           const int32_t* q_labels, const int32_t* k_labels, const int32_t* k_count,
+                           const int32_t* sel_idx, const int32_t* sel_cnt, void* O, void* ws, size_t ws_bytes,
+                           void* stream) {
+  int rc = check_params(p);
+  if (rc) return rc;
+  if (!Q || !K || !V || !q_labels || !k_labels || !k_count || !sel_idx || !sel_cnt || !O)
+    return fail(ADACLUSTER_E_BADARG, "sparse_attn: NULL tensor pointer");
+  WS w;
+  if ((rc = check_ws(p, ws, ws_bytes, &w))) return rc;
+  const Dims D = dims_of(p);
+  hipStream_t st = (hipStream_t)stream;
+  RET_IF(launch_sort(st, D.H, D.N, D.N, D.Cq, q_labels, nullptr, nullptr, 0, nullptr, 0, nullptr, 0, w.perm_q, w.offs_q,
+                     D.Cq + 1, w.sort));
+  RET_IF(launch_sort(st, D.H, D.N, D.N, D.cap, k_labels, nullptr, nullptr, 0, k_count, 1, nullptr, 0, w.perm_k, w.offs_k,
+                     D.cap + 1, w.sort));
+  return run_attention(p, w, st, Q, K, V, O, k_count, sel_idx, sel_cnt);
+}
+
+int adacluster_attn(const adacluster_params* p, const void* Q, const void* K, const void* V, void* O,
+                    const adacluster_outputs* outs, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_params(p);
+  if (rc) return rc;
+  if (!Q || !K || !V || !O) return fail(ADACLUSTER_E_BADARG, "attn: NULL tensor pointer");
+  WS w;
+  if ((rc = check_ws(p, ws, ws_bytes, &w))) return rc;
+  adacluster_outputs o;
+  memset(&o, 0, sizeof(o));
+  if (outs) o = *outs;
+  if ((o.k_box_min == nullptr) != (o.k_box_max == nullptr))
+    return fail(ADACLUSTER_E_BADARG, "attn: pass both boxes or neither");
+  const bool need_box = p->score_mode == ADACLUSTER_SCORE_BOX;
+#define PICK(f, home) auto f = o.f ? o.f : home
+  PICK(q_labels, w.q_labels); PICK(q_centroids, w.q_centroids); PICK(q_assign_centroids, w.q_assign);
+  PICK(q_sizes, w.q_sizes); PICK(q_mean_norm, w.q_mean_norm);
+  PICK(k_labels, w.k_labels); PICK(k_centroids, w.k_centroids); PICK(k_assign_centroids, w.k_assign);
+  PICK(k_sizes, w.k_sizes); PICK(k_count, w.k_count); PICK(full_flag, w.full_flag);
+  PICK(sel_idx, w.sel_idx); PICK(sel_cnt, w.sel_cnt);
+#undef PICK
+  float* k_bmin = o.k_box_min ? o.k_box_min : (need_box ? w.k_bmin : nullptr);
+  float* k_bmax = o.k_box_max ? o.k_box_max : (need_box ? w.k_bmax : nullptr);
+  float* tau_used = o.tau_used ? o.tau_used : w.tau + 2;
+  hipStream_t st = (hipStream_t)stream;
+  if (p->q_init_mode == 1 && !o.q_centroids)
+    return fail(ADACLUSTER_E_BADARG, "attn: q_init_mode 1 needs outs->q_centroids");
+  if ((rc = run_qcluster(p, w, st, Q, q_labels, q_centroids, q_assign_centroids, q_sizes, q_mean_norm))) return rc;
+  if ((rc = run_kcluster(p, w, st, K, k_labels, k_centroids, k_assign_centroids, k_bmin, k_bmax, k_sizes, k_count,
+                         full_flag, o.k_stage_offs, o.k_stage_of, tau_used)))
+    return rc;
+  const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->d);
+  RET_IF(launch_select(st, p->H, p->q_clusters, capacity(p), p->d, p->score_mode, p->select_mode, p->topk, p->top_p,
+                       scale, q_centroids, q_mean_norm, k_centroids, k_bmin, k_bmax, k_sizes, k_count, full_flag,
+                       sel_idx, sel_cnt));
+  // both label sorts were left in the workspace by the clustering steps
+  return run_attention(p, w, st, Q, K, V, O, k_count, sel_idx, sel_cnt);
+}
+
+int adacluster_dense_attn(const adacluster_params* p, const void* Q, const void* K, const void* V, void* O,
+                          void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_params(p);
+  if (rc) return rc;
+  if (!Q || !K || !V || !O) return fail(ADACLUSTER_E_BADARG, "dense_attn: NULL tensor pointer");
+  WS w;
+  if ((rc = check_ws(p, ws, ws_bytes, &w))) return rc;
+  const Dims D = dims_of(p);
+  hipStream_t st = (hipStream_t)stream;
+  const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)D.d);
+  RET_IF(launch_plan_dense(st, D.H, D.N, D.maxtiles, D.BM, w.rng_start, w.rng_pre, w.rng_cnt, w.tiles, w.ntiles));
+  RET_IF(launch_attention(st, p->dtype, D.d, D.H, D.N, 1, D.maxtiles, 1, scale, Q, K, V, O, nullptr, w.tiles,
+                          w.ntiles, w.rng_start, w.rng_pre, w.rng_cnt));
+  return 0;
+}
+
+}  // extern "C"

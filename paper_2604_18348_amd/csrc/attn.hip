@@ -1,0 +1,492 @@
+// Attention over the selected key clusters (Alg. 3 lines 9-10) and the dense branch.
+//
+// Keys and values are first permuted cluster-contiguous (row gathers, HBM bound).  For every
+// query cluster the selected key clusters then form a short list of row ranges in that order; a
+// query tile walks the concatenation of its ranges in full 64-key tiles, so cluster raggedness
+// costs nothing but one masked tail tile.  The flash-style kernel keeps the S^T = K Q^T
+// orientation: in the 32x32 MFMA accumulator a lane then owns one query and 16 keys, soft-max
+// statistics are per-lane scalars, and the exponentiated block feeds the P V product as the B
+// operand straight from registers.  V is transposed on its way into LDS so that the A operand of
+// that product is one 16-byte read.
+#include "common.h"
+#include "launch.h"
+
+namespace adac {
+
+// ------------------------------------------------------------------------------------------
+// permutation of K and V rows
+// ------------------------------------------------------------------------------------------
+// dst[h][i][:] = src[h][perm[h][i]][:], 16-byte pieces, one row per group of ROWB/16 lanes.
+template <int ROWB>
+__global__ __launch_bounds__(256) void gather_rows2(const uint8_t* __restrict__ a, const uint8_t* __restrict__ b,
+                                                    const int32_t* __restrict__ perm, int N,
+                                                    uint8_t* __restrict__ ao, uint8_t* __restrict__ bo) {
+  constexpr int LPR = ROWB / 16;
+  const int h = blockIdx.y;
+  const int r = blockIdx.x * (256 / LPR) + threadIdx.x / LPR;
+  const int q = threadIdx.x % LPR;
+  if (r >= N) return;
+  const int src = perm[(size_t)h * N + r];
+  const size_t so = ((size_t)h * N + src) * ROWB + q * 16;
+  const size_t dd = ((size_t)h * N + r) * ROWB + q * 16;
+  const uint4 va = *reinterpret_cast<const uint4*>(a + so);
+  const uint4 vb = *reinterpret_cast<const uint4*>(b + so);
+  *reinterpret_cast<uint4*>(ao + dd) = va;
+  *reinterpret_cast<uint4*>(bo + dd) = vb;
+}
+
+int launch_permute_kv(hipStream_t s, int H, int N, int row_bytes, const void* K, const void* V,
+                      const int32_t* perm, void* Kp, void* Vp) {
+  auto A = (const uint8_t*)K; auto B = (const uint8_t*)V; auto Ao = (uint8_t*)Kp; auto Bo = (uint8_t*)Vp;
+  if (row_bytes == 128) gather_rows2<128><<<dim3((N + 31) / 32, H), 256, 0, s>>>(A, B, perm, N, Ao, Bo);
+  else if (row_bytes == 256) gather_rows2<256><<<dim3((N + 15) / 16, H), 256, 0, s>>>(A, B, perm, N, Ao, Bo);
+  else if (row_bytes == 512) gather_rows2<512><<<dim3((N + 7) / 8, H), 256, 0, s>>>(A, B, perm, N, Ao, Bo);
+  else return ADACLUSTER_E_BADSHAPE;
+  return hipGetLastError() == hipSuccess ? 0 : ADACLUSTER_E_INTERNAL;
+}
+
+// ------------------------------------------------------------------------------------------
+// plan: per query cluster the merged key ranges; per head the list of query tiles
+// ------------------------------------------------------------------------------------------
+// rng_start [H][Cq][maxr]   first permuted key row of range r
+// rng_pre   [H][Cq][maxr+1] keys before range r in the concatenation (last = total)
+// rng_cnt   [H][Cq]
+// tiles     [H][maxtiles] x {cluster, first sorted query position, rows}; ntiles [H]
+__global__ void plan_sparse(int Cq, int cap, int maxr, int maxtiles, int BM,
+                            const int32_t* __restrict__ q_offs, int q_offs_stride,
+                            const int32_t* __restrict__ k_offs, int k_offs_stride,
+                            const int32_t* __restrict__ k_count,
+                            const int32_t* __restrict__ sel_idx, const int32_t* __restrict__ sel_cnt,
+                            int32_t* __restrict__ rng_start, int32_t* __restrict__ rng_pre,
+                            int32_t* __restrict__ rng_cnt, int32_t* __restrict__ tiles,
+                            int32_t* __restrict__ ntiles) {
+  const int h = blockIdx.y, i = blockIdx.x;
+  if (threadIdx.x != 0) return;
+  if (i < Cq) {
+    const int32_t* sel = sel_idx + ((size_t)h * Cq + i) * cap;
+    const int cnt = sel_cnt[(size_t)h * Cq + i];
+    const int32_t* ko = k_offs + (size_t)h * k_offs_stride;
+    const int kc = k_count[h];
+    int32_t* rs = rng_start + ((size_t)h * Cq + i) * maxr;
+    int32_t* rp = rng_pre + ((size_t)h * Cq + i) * (maxr + 1);
+    int nr = 0, total = 0, cur_s = 0, cur_e = -1;
+    for (int t = 0; t < cnt; ++t) {
+      const int j = sel[t];
+      if (j < 0 || j >= kc) continue;
+      const int s = ko[j], e = ko[j + 1];
+      if (e <= s) continue;
+      if (s == cur_e) { cur_e = e; continue; }
+      if (cur_e > cur_s) { rs[nr] = cur_s; rp[nr] = total; total += cur_e - cur_s; ++nr; }
+      cur_s = s; cur_e = e;
+    }
+    if (cur_e > cur_s) { rs[nr] = cur_s; rp[nr] = total; total += cur_e - cur_s; ++nr; }
+    rp[nr] = total;
+    rng_cnt[(size_t)h * Cq + i] = nr;
+  } else {
+    // query tiles of this head, cluster by cluster
+    const int32_t* qo = q_offs + (size_t)h * q_offs_stride;
+    int32_t* tl = tiles + (size_t)h * maxtiles * 3;
+    int nt = 0;
+    for (int c = 0; c < Cq; ++c) {
+      const int s = qo[c], e = qo[c + 1];
+      for (int r0 = s; r0 < e; r0 += BM) {
+        tl[nt * 3 + 0] = c; tl[nt * 3 + 1] = r0; tl[nt * 3 + 2] = min(BM, e - r0);
+        ++nt;
+      }
+    }
+    ntiles[h] = nt;
+  }
+}
+
+// dense: one query "cluster" over all rows, one key range [0,N)
+__global__ void plan_dense(int N, int maxtiles, int BM, int32_t* __restrict__ rng_start,
+                           int32_t* __restrict__ rng_pre, int32_t* __restrict__ rng_cnt,
+                           int32_t* __restrict__ tiles, int32_t* __restrict__ ntiles) {
+  const int h = blockIdx.x;
+  if (threadIdx.x == 0) {
+    rng_start[h] = 0; rng_pre[(size_t)h * 2] = 0; rng_pre[(size_t)h * 2 + 1] = N; rng_cnt[h] = 1;
+    ntiles[h] = (N + BM - 1) / BM;
+  }
+  int32_t* tl = tiles + (size_t)h * maxtiles * 3;
+  for (int t = threadIdx.x; t * BM < N; t += blockDim.x) {
+    tl[t * 3 + 0] = 0; tl[t * 3 + 1] = t * BM; tl[t * 3 + 2] = min(BM, N - t * BM);
+  }
+}
+
+struct AttnArgs {
+  const void* Q; const void* Kp; const void* Vp; void* O;
+  const int32_t* perm_q;        // sorted query position -> token (NULL: identity)
+  const int32_t* tiles; const int32_t* ntiles;
+  const int32_t* rng_start; const int32_t* rng_pre; const int32_t* rng_cnt;
+  int N, Cq, maxtiles, maxr;
+  float scale_log2e;            // softmax scale x log2(e)
+};
+
+// position in the concatenation of ranges -> permuted key row; a cursor that only moves forward
+struct RangeCursor {
+  const int32_t* rs; const int32_t* rp; int nr; int r; int cur_end; int delta;
+  __device__ __forceinline__ void init(const int32_t* rs_, const int32_t* rp_, int nr_) {
+    rs = rs_; rp = rp_; nr = nr_; r = 0;
+    cur_end = nr > 0 ? rp[1] : 0;
+    delta = nr > 0 ? rs[0] - rp[0] : 0;
+  }
+  __device__ __forceinline__ int row(int p) {      // p is non-decreasing across calls
+    while (r < nr && p >= cur_end) {
+      ++r;
+      if (r < nr) { cur_end = rp[r + 1]; delta = rs[r] - rp[r]; }
+    }
+    return r < nr ? p + delta : -1;
+  }
+};
+
+// ------------------------------------------------------------------------------------------
+// bf16 MFMA kernel
+// ------------------------------------------------------------------------------------------
+template <int D, int QB>
+__global__ __launch_bounds__(256) void attn_mfma(AttnArgs a) {
+  constexpr int BN = 64;
+  constexpr int BM = 128 * QB;
+  constexpr int KLD = D + 8;         // K tile row stride (bf16)
+  constexpr int VLD = BN + 8;        // transposed V tile row stride (bf16)
+  constexpr int KS = D / 16;         // contraction steps of S
+  constexpr int DB = D / 32;         // 32-row blocks of O^T
+  constexpr int KCH = D / 8;         // 16-byte chunks per K row
+  constexpr int KPT = BN * KCH / 256;            // K chunks per thread per tile
+  constexpr int VIT = (BN / 8) * (D / 2) / 256;  // V (8-key group, column pair) items per thread
+
+  const int h = blockIdx.y;
+  const int tile = blockIdx.x;
+  if (tile >= a.ntiles[h]) return;
+  const int32_t* tl = a.tiles + ((size_t)h * a.maxtiles + tile) * 3;
+  const int qc = tl[0], row0 = tl[1], nrows = tl[2];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = lane & 31, hb = lane >> 5;
+
+  const int nr = a.rng_cnt[(size_t)h * a.Cq + qc];
+  const int32_t* rs = a.rng_start + ((size_t)h * a.Cq + qc) * a.maxr;
+  const int32_t* rp = a.rng_pre + ((size_t)h * a.Cq + qc) * (a.maxr + 1);
+  const int total = rp[nr];
+  const int T = (total + BN - 1) / BN;
+
+  const bf16raw* Qh = (const bf16raw*)a.Q + (size_t)h * a.N * D;
+  const bf16raw* Kh = (const bf16raw*)a.Kp + (size_t)h * a.N * D;
+  const bf16raw* Vh = (const bf16raw*)a.Vp + (size_t)h * a.N * D;
+  bf16raw* Oh = (bf16raw*)a.O + (size_t)h * a.N * D;
+  const int32_t* pq = a.perm_q ? a.perm_q + (size_t)h * a.N : nullptr;
+
+  __shared__ __attribute__((aligned(16))) bf16raw Ks[BN * KLD];
+  __shared__ __attribute__((aligned(16))) bf16raw Vt[D * VLD];
+  __shared__ int32_t ridx[2][BN];
+
+  // query tokens of this lane and the B operand of S
+  int qtok[QB];
+  bf16x8_t qf[QB][KS];
+  const bool wave_has_rows = wave * (32 * QB) < nrows;
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    const int rr = wave * (32 * QB) + qb * 32 + c;
+    qtok[qb] = -1;
+    if (rr < nrows) qtok[qb] = pq ? pq[row0 + rr] : row0 + rr;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      uint4 raw = {0, 0, 0, 0};
+      if (qtok[qb] >= 0) raw = *reinterpret_cast<const uint4*>(Qh + (size_t)qtok[qb] * D + ks * 16 + hb * 8);
+      qf[qb][ks] = *reinterpret_cast<const bf16x8_t*>(&raw);
+    }
+  }
+
+  f32x16_t oacc[DB][QB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) oacc[db][qb][v] = 0.f;
+  float mrun[QB], lrun[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) { mrun[qb] = -INFINITY; lrun[qb] = 0.f; }
+
+  RangeCursor cur;
+  if (tid < BN) {
+    cur.init(rs, rp, nr);
+    ridx[0][tid] = (T > 0) ? cur.row(tid) : -1;
+  }
+  __syncthreads();
+
+  uint4 kreg[KPT];
+  uint32_t vreg[VIT][8];
+  auto issue_loads = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) {
+      const int item = tid + i * 256;
+      const int r = item / KCH, q = item % KCH;
+      const int row = ridx[buf][r];
+      uint4 v = {0, 0, 0, 0};
+      if (row >= 0) v = *reinterpret_cast<const uint4*>(Kh + (size_t)row * D + q * 8);
+      kreg[i] = v;
+    }
+#pragma unroll
+    for (int i = 0; i < VIT; ++i) {
+      const int item = tid + i * 256;
+      const int g = item / (D / 2), dp = item % (D / 2);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int row = ridx[buf][g * 8 + j];
+        uint32_t v = 0;
+        if (row >= 0) v = *reinterpret_cast<const uint32_t*>(Vh + (size_t)row * D + 2 * dp);
+        vreg[i][j] = v;
+      }
+    }
+  };
+  auto store_lds = [&]() {
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) {
+      const int item = tid + i * 256;
+      const int r = item / KCH, q = item % KCH;
+      *reinterpret_cast<uint4*>(&Ks[r * KLD + q * 8]) = kreg[i];
+    }
+#pragma unroll
+    for (int i = 0; i < VIT; ++i) {
+      const int item = tid + i * 256;
+      const int g = item / (D / 2), dp = item % (D / 2);
+      uint4 lo, hi;
+      // low halves = column 2dp of keys 0..7, high halves = column 2dp+1
+      lo.x = __builtin_amdgcn_perm(vreg[i][1], vreg[i][0], 0x05040100u);
+      lo.y = __builtin_amdgcn_perm(vreg[i][3], vreg[i][2], 0x05040100u);
+      lo.z = __builtin_amdgcn_perm(vreg[i][5], vreg[i][4], 0x05040100u);
+      lo.w = __builtin_amdgcn_perm(vreg[i][7], vreg[i][6], 0x05040100u);
+      hi.x = __builtin_amdgcn_perm(vreg[i][1], vreg[i][0], 0x07060302u);
+      hi.y = __builtin_amdgcn_perm(vreg[i][3], vreg[i][2], 0x07060302u);
+      hi.z = __builtin_amdgcn_perm(vreg[i][5], vreg[i][4], 0x07060302u);
+      hi.w = __builtin_amdgcn_perm(vreg[i][7], vreg[i][6], 0x07060302u);
+      *reinterpret_cast<uint4*>(&Vt[(2 * dp) * VLD + g * 8]) = lo;
+      *reinterpret_cast<uint4*>(&Vt[(2 * dp + 1) * VLD + g * 8]) = hi;
+    }
+  };
+
+  if (T > 0) issue_loads(0);
+  if (tid < BN && T > 1) ridx[1][tid] = cur.row(BN + tid);
+
+  // MFMA row rho of a 32-key block holds key kappa(rho): bits 2 and 3 swapped, so that the 8
+  // accumulator values a lane feeds to one P V step are 8 consecutive keys.
+  const int kappa = (c & 0x13) | ((c & 4) << 1) | ((c & 8) >> 1);
+
+  for (int t = 0; t < T; ++t) {
+    store_lds();
+    __syncthreads();
+    if (t + 1 < T) issue_loads((t + 1) & 1);
+
+    if (wave_has_rows) {
+      f32x16_t sacc[2][QB];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) sacc[kb][qb][v] = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          const bf16x8_t ka = *reinterpret_cast<const bf16x8_t*>(&Ks[(kb * 32 + kappa) * KLD + ks * 16 + hb * 8]);
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb)
+            sacc[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[qb][ks], sacc[kb][qb], 0, 0, 0);
+        }
+      // accumulator value v of block kb is key  kb*32 + 16*(v/8) + 8*hb + v%8
+      if (t == T - 1 && (total & (BN - 1))) {
+        const int nvalid = total - t * BN;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int key = kb * 32 + 16 * (v >> 3) + 8 * hb + (v & 7);
+            if (key >= nvalid) {
+#pragma unroll
+              for (int qb = 0; qb < QB; ++qb) sacc[kb][qb][v] = -INFINITY;
+            }
+          }
+      }
+      bf16x8_t pf[QB][2][2];
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        float tmax = sacc[0][qb][0];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, sacc[kb][qb][v]);
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        const float mnew = fmaxf(mrun[qb], tmax);           // finite: every tile holds a valid key
+        const float alpha = __builtin_amdgcn_exp2f((mrun[qb] - mnew) * a.scale_log2e);
+        const float moff = mnew * a.scale_log2e;
+        mrun[qb] = mnew;
+        float rsum = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int s2 = 0; s2 < 2; ++s2) {
+            uint32_t w[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][qb][8 * s2 + 2 * j], a.scale_log2e, -moff));
+              const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][qb][8 * s2 + 2 * j + 1], a.scale_log2e, -moff));
+              rsum += p0 + p1;
+              w[j] = pack_bf16x2(p0, p1);
+            }
+            const uint4 pk = {w[0], w[1], w[2], w[3]};
+            pf[qb][kb][s2] = *reinterpret_cast<const bf16x8_t*>(&pk);
+          }
+        lrun[qb] = lrun[qb] * alpha + rsum;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) oacc[db][qb][v] *= alpha;
+      }
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int s2 = 0; s2 < 2; ++s2) {
+            const bf16x8_t va = *reinterpret_cast<const bf16x8_t*>(&Vt[(db * 32 + c) * VLD + kb * 32 + 16 * s2 + 8 * hb]);
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+              oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf[qb][kb][s2], oacc[db][qb], 0, 0, 0);
+          }
+    }
+    __syncthreads();
+    if (tid < BN && t + 2 < T) ridx[t & 1][tid] = cur.row((t + 2) * BN + tid);
+  }
+
+  // O^T accumulator value v of block db is column  db*32 + 8*(v/4) + 4*hb + v%4  of query c
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    const float l = lrun[qb] + __shfl_xor(lrun[qb], 32);
+    const float inv = l > 0.f ? 1.0f / l : 0.f;
+    if (qtok[qb] < 0) continue;
+    bf16raw* orow = Oh + (size_t)qtok[qb] * D;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        uint2 o;
+        o.x = pack_bf16x2(oacc[db][qb][4 * i] * inv, oacc[db][qb][4 * i + 1] * inv);
+        o.y = pack_bf16x2(oacc[db][qb][4 * i + 2] * inv, oacc[db][qb][4 * i + 3] * inv);
+        *reinterpret_cast<uint2*>(orow + db * 32 + 8 * i + 4 * hb) = o;
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// fp32 kernel: one query per thread, key tiles broadcast from LDS (accuracy path, small inputs)
+// ------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(64) void attn_f32(AttnArgs a) {
+  constexpr int BN = 32;
+  const int h = blockIdx.y, tile = blockIdx.x;
+  if (tile >= a.ntiles[h]) return;
+  const int32_t* tl = a.tiles + ((size_t)h * a.maxtiles + tile) * 3;
+  const int qc = tl[0], row0 = tl[1], nrows = tl[2];
+  const int tid = threadIdx.x;
+  const int nr = a.rng_cnt[(size_t)h * a.Cq + qc];
+  const int32_t* rs = a.rng_start + ((size_t)h * a.Cq + qc) * a.maxr;
+  const int32_t* rp = a.rng_pre + ((size_t)h * a.Cq + qc) * (a.maxr + 1);
+  const int total = rp[nr];
+  const float* Qh = (const float*)a.Q + (size_t)h * a.N * D;
+  const float* Kh = (const float*)a.Kp + (size_t)h * a.N * D;
+  const float* Vh = (const float*)a.Vp + (size_t)h * a.N * D;
+  float* Oh = (float*)a.O + (size_t)h * a.N * D;
+  __shared__ __attribute__((aligned(16))) float Ks[BN * D];
+  __shared__ __attribute__((aligned(16))) float Vs[BN * D];
+  __shared__ int32_t ridx[BN];
+  int tok = -1;
+  if (tid < nrows) tok = a.perm_q ? a.perm_q[(size_t)h * a.N + row0 + tid] : row0 + tid;
+  float q[D], o[D];
+#pragma unroll
+  for (int j = 0; j < D; ++j) { q[j] = tok >= 0 ? Qh[(size_t)tok * D + j] : 0.f; o[j] = 0.f; }
+  float m = -INFINITY, l = 0.f;
+  RangeCursor cur;
+  if (tid < BN) cur.init(rs, rp, nr);
+  for (int k0 = 0; k0 < total; k0 += BN) {
+    __syncthreads();
+    if (tid < BN) ridx[tid] = cur.row(k0 + tid);
+    __syncthreads();
+    for (int i = tid; i < BN * D / 4; i += 64) {
+      const int r = i / (D / 4), qd = i % (D / 4);
+      const int row = ridx[r];
+      float4 kv = {0.f, 0.f, 0.f, 0.f}, vv = {0.f, 0.f, 0.f, 0.f};
+      if (row >= 0) {
+        kv = reinterpret_cast<const float4*>(Kh + (size_t)row * D)[qd];
+        vv = reinterpret_cast<const float4*>(Vh + (size_t)row * D)[qd];
+      }
+      reinterpret_cast<float4*>(Ks)[i] = kv;
+      reinterpret_cast<float4*>(Vs)[i] = vv;
+    }
+    __syncthreads();
+    const int kn = min(BN, total - k0);
+    for (int r = 0; r < kn; ++r) {
+      float s = 0.f;
+#pragma unroll
+      for (int j = 0; j < D; j += 4) {
+        const float4 kv = *reinterpret_cast<const float4*>(&Ks[r * D + j]);
+        s = fmaf(q[j], kv.x, s); s = fmaf(q[j + 1], kv.y, s);
+        s = fmaf(q[j + 2], kv.z, s); s = fmaf(q[j + 3], kv.w, s);
+      }
+      s *= a.scale_log2e;
+      const float mnew = fmaxf(m, s);
+      const float alpha = exp2f(m - mnew);
+      const float p = exp2f(s - mnew);
+      l = l * alpha + p;
+#pragma unroll
+      for (int j = 0; j < D; j += 4) {
+        const float4 vv = *reinterpret_cast<const float4*>(&Vs[r * D + j]);
+        o[j] = fmaf(o[j], alpha, p * vv.x); o[j + 1] = fmaf(o[j + 1], alpha, p * vv.y);
+        o[j + 2] = fmaf(o[j + 2], alpha, p * vv.z); o[j + 3] = fmaf(o[j + 3], alpha, p * vv.w);
+      }
+      m = mnew;
+    }
+  }
+  if (tok >= 0) {
+    const float inv = l > 0.f ? 1.0f / l : 0.f;
+#pragma unroll
+    for (int j = 0; j < D; ++j) Oh[(size_t)tok * D + j] = o[j] * inv;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+int attn_block_rows(int dtype, int d) { return dtype == ADACLUSTER_BF16 ? 256 : 64; }
+
+int launch_plan_sparse(hipStream_t s, int H, int Cq, int cap, int maxr, int maxtiles, int BM,
+                       const int32_t* q_offs, int q_offs_stride, const int32_t* k_offs, int k_offs_stride,
+                       const int32_t* k_count, const int32_t* sel_idx, const int32_t* sel_cnt,
+                       int32_t* rng_start, int32_t* rng_pre, int32_t* rng_cnt, int32_t* tiles, int32_t* ntiles) {
+  plan_sparse<<<dim3(Cq + 1, H), 64, 0, s>>>(Cq, cap, maxr, maxtiles, BM, q_offs, q_offs_stride, k_offs,
+                                            k_offs_stride, k_count, sel_idx, sel_cnt, rng_start, rng_pre,
+                                            rng_cnt, tiles, ntiles);
+  return hipGetLastError() == hipSuccess ? 0 : ADACLUSTER_E_INTERNAL;
+}
+
+int launch_plan_dense(hipStream_t s, int H, int N, int maxtiles, int BM, int32_t* rng_start, int32_t* rng_pre,
+                      int32_t* rng_cnt, int32_t* tiles, int32_t* ntiles) {
+  plan_dense<<<H, 256, 0, s>>>(N, maxtiles, BM, rng_start, rng_pre, rng_cnt, tiles, ntiles);
+  return hipGetLastError() == hipSuccess ? 0 : ADACLUSTER_E_INTERNAL;
+}
+
+int launch_attention(hipStream_t s, int dtype, int d, int H, int N, int Cq, int maxtiles, int maxr, float scale,
+                     const void* Q, const void* Kp, const void* Vp, void* O, const int32_t* perm_q,
+                     const int32_t* tiles, const int32_t* ntiles, const int32_t* rng_start,
+                     const int32_t* rng_pre, const int32_t* rng_cnt) {
+  AttnArgs a{Q, Kp, Vp, O, perm_q, tiles, ntiles, rng_start, rng_pre, rng_cnt, N, Cq, maxtiles, maxr,
+             scale * 1.4426950408889634f};
+  dim3 g(maxtiles, H);
+  if (dtype == ADACLUSTER_BF16) {
+    if (d == 64) attn_mfma<64, 2><<<g, 256, 0, s>>>(a);
+    else attn_mfma<128, 2><<<g, 256, 0, s>>>(a);
+  } else {
+    if (d == 64) attn_f32<64><<<g, 64, 0, s>>>(a);
+    else attn_f32<128><<<g, 64, 0, s>>>(a);
+  }
+  return hipGetLastError() == hipSuccess ? 0 : ADACLUSTER_E_INTERNAL;
+}
+
+}  // namespace adac

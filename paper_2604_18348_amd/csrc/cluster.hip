@@ -1,0 +1,754 @@
+// k-means building blocks for the query clustering (Sec. 3.1, Alg. 3 line 1) and the
+// multi-stage key clustering (Algorithm 1):
+//   * point-to-centre assignment as an MFMA GEMM  C . X^T  with an in-lane running arg-max
+//     (bf16 I/O) or a plain fp32 kernel (fp32 I/O);
+//   * atomic-free centroid update: segmented sums over the label-sorted token order;
+//   * the stage bookkeeping of Algorithm 1 (centre count rule, threshold filter, compaction
+//     of the unassigned set U), kept on the device.
+#include "common.h"
+#include "launch.h"
+
+namespace adac {
+
+// ------------------------------------------------------------------------------------------
+// assignment
+// ------------------------------------------------------------------------------------------
+// modes: 0 = fixed (row_off 0, m = m_const, n = N, every head)
+//        1 = stage (row_off = ccount, m = m_t, n = ucount, only active heads)
+//        2 = final (row_off 0, m = ccount, n = N, every head)
+struct AssignCfg {
+  int mode; int m_const; int N; int cap;
+  const KState* st; const int32_t* ulist;
+};
+
+__device__ __forceinline__ bool assign_setup(const AssignCfg& c, int h, int& n, int& m, int& row_off) {
+  if (c.mode == 0) { n = c.N; m = c.m_const; row_off = 0; return true; }
+  const KState& s = c.st[h];
+  if (c.mode == 1) { n = s.ucount; m = s.m_t; row_off = s.ccount; return s.active != 0; }
+  n = c.N; m = s.ccount; row_off = 0; return true;
+}
+
+// score(x, c) = x.c + bias(c), bias = -||c||^2/2 (Euclidean arg-min) or 0 (cosine arg-max);
+// label = arg-max, ties to the lowest index;  dist2 = ||x||^2 - 2 score.
+//
+// MFMA formulation: D[32 centres x 32 points] += A[32 x 16] B[16 x 32] with A = centre rows from
+// LDS and B = point rows held in registers for the whole kernel.  In the 32x32 accumulator a lane
+// owns ONE point (column lane%32) and 16 centres, so the arg-max over centres runs in-lane; the
+// two half-waves are merged once at the end.
+template <int D>
+__global__ __launch_bounds__(256) void assign_mfma(const bf16raw* __restrict__ X, AssignCfg cfg,
+                                                   const bf16raw* __restrict__ cent,
+                                                   const float* __restrict__ bias,
+                                                   int32_t* __restrict__ labels, float* __restrict__ dist2) {
+  constexpr int CB = 128;               // centres per LDS chunk
+  constexpr int LDW = D + 8;            // padded row (bf16 elements): conflict-free 16-byte reads
+  constexpr int KS = D / 16;
+  constexpr int PB = 2;                 // 32-point blocks per wave
+  const int h = blockIdx.y;
+  int n, m, row_off;
+  if (!assign_setup(cfg, h, n, m, row_off)) return;
+  const int base = blockIdx.x * (4 * PB * 32);
+  if (base >= n) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = lane & 31, hb = lane >> 5;
+
+  __shared__ __attribute__((aligned(16))) bf16raw cs[CB * LDW];
+  __shared__ __attribute__((aligned(16))) float bs[CB];
+
+  // B operand: this lane's point rows
+  bf16x8_t xf[PB][KS];
+  float xn2[PB];
+  int pos[PB];
+#pragma unroll
+  for (int pb = 0; pb < PB; ++pb) {
+    pos[pb] = base + wave * (PB * 32) + pb * 32 + c;
+    float ss = 0.f;
+    if (pos[pb] < n) {
+      const int tok = cfg.ulist ? cfg.ulist[(size_t)h * cfg.N + pos[pb]] : pos[pb];
+      const bf16raw* row = X + ((size_t)h * cfg.N + tok) * D + hb * 8;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const uint4 raw = *reinterpret_cast<const uint4*>(row + ks * 16);
+        xf[pb][ks] = *reinterpret_cast<const bf16x8_t*>(&raw);
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const float a = __uint_as_float(w[q] << 16), b = __uint_as_float(w[q] & 0xFFFF0000u);
+          ss = fmaf(a, a, ss); ss = fmaf(b, b, ss);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) { const uint4 z = {0, 0, 0, 0}; xf[pb][ks] = *reinterpret_cast<const bf16x8_t*>(&z); }
+    }
+    xn2[pb] = ss + __shfl_xor(ss, 32);
+  }
+
+  float best[PB]; int bidx[PB];
+#pragma unroll
+  for (int pb = 0; pb < PB; ++pb) { best[pb] = -INFINITY; bidx[pb] = 0; }
+
+  const bf16raw* ch = cent + ((size_t)h * cfg.cap + row_off) * D;
+  const float* bh = bias + (size_t)h * cfg.cap + row_off;
+
+  for (int c0 = 0; c0 < m; c0 += CB) {
+    __syncthreads();
+    // stage CB centre rows (zero rows and -inf bias beyond m)
+    constexpr int CHUNKS = D / 8;                      // 16-byte chunks per row
+    for (int i = tid; i < CB * CHUNKS; i += 256) {
+      const int r = i / CHUNKS, q = i % CHUNKS;
+      uint4 v = {0, 0, 0, 0};
+      if (c0 + r < m) v = *reinterpret_cast<const uint4*>(ch + (size_t)(c0 + r) * D + q * 8);
+      *reinterpret_cast<uint4*>(&cs[r * LDW + q * 8]) = v;
+    }
+    if (tid < CB) bs[tid] = (c0 + tid < m) ? bh[c0 + tid] : -INFINITY;
+    __syncthreads();
+    const int rbmax = min(CB / 32, (m - c0 + 31) / 32);
+    for (int rb = 0; rb < rbmax; ++rb) {
+      f32x16_t acc[PB];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float4 b4 = *reinterpret_cast<const float4*>(&bs[rb * 32 + 8 * i + 4 * hb]);
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb) {
+          acc[pb][4 * i + 0] = b4.x; acc[pb][4 * i + 1] = b4.y;
+          acc[pb][4 * i + 2] = b4.z; acc[pb][4 * i + 3] = b4.w;
+        }
+      }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(&cs[(rb * 32 + c) * LDW + ks * 16 + hb * 8]);
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb)
+          acc[pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xf[pb][ks], acc[pb], 0, 0, 0);
+      }
+      const int idx0 = c0 + rb * 32 + 4 * hb;
+#pragma unroll
+      for (int pb = 0; pb < PB; ++pb) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float val = acc[pb][v];
+          const int idx = idx0 + 8 * (v >> 2) + (v & 3);
+          if (val > best[pb]) { best[pb] = val; bidx[pb] = idx; }
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int pb = 0; pb < PB; ++pb) {
+    const float ob = __shfl_xor(best[pb], 32);
+    const int oi = __shfl_xor(bidx[pb], 32);
+    if (ob > best[pb] || (ob == best[pb] && oi < bidx[pb])) { best[pb] = ob; bidx[pb] = oi; }
+    if (hb == 0 && pos[pb] < n) {
+      labels[(size_t)h * cfg.N + pos[pb]] = bidx[pb];
+      if (dist2) dist2[(size_t)h * cfg.N + pos[pb]] = fmaxf(xn2[pb] - 2.f * best[pb], 0.f);
+    }
+  }
+}
+
+// fp32 I/O: one point per thread, centre chunks broadcast from LDS.
+template <int D>
+__global__ __launch_bounds__(128) void assign_f32(const float* __restrict__ X, AssignCfg cfg,
+                                                  const float* __restrict__ cent,
+                                                  const float* __restrict__ bias,
+                                                  int32_t* __restrict__ labels, float* __restrict__ dist2) {
+  constexpr int CB = 32;
+  const int h = blockIdx.y;
+  int n, m, row_off;
+  if (!assign_setup(cfg, h, n, m, row_off)) return;
+  const int base = blockIdx.x * 128;
+  if (base >= n) return;
+  const int tid = threadIdx.x;
+  const int p = base + tid;
+  __shared__ __attribute__((aligned(16))) float cs[CB * D];
+  __shared__ float bs[CB];
+  float x[D];
+  float xn2 = 0.f;
+  if (p < n) {
+    const int tok = cfg.ulist ? cfg.ulist[(size_t)h * cfg.N + p] : p;
+    const float4* row = reinterpret_cast<const float4*>(X + ((size_t)h * cfg.N + tok) * D);
+#pragma unroll
+    for (int q = 0; q < D / 4; ++q) {
+      const float4 v = row[q];
+      x[4 * q] = v.x; x[4 * q + 1] = v.y; x[4 * q + 2] = v.z; x[4 * q + 3] = v.w;
+    }
+#pragma unroll
+    for (int j = 0; j < D; ++j) xn2 = fmaf(x[j], x[j], xn2);
+  } else {
+#pragma unroll
+    for (int j = 0; j < D; ++j) x[j] = 0.f;
+  }
+  const float* ch = cent + ((size_t)h * cfg.cap + row_off) * D;
+  const float* bh = bias + (size_t)h * cfg.cap + row_off;
+  float best = -INFINITY; int bidx = 0;
+  for (int c0 = 0; c0 < m; c0 += CB) {
+    __syncthreads();
+    for (int i = tid; i < CB * D / 4; i += 128) {
+      const int r = i / (D / 4);
+      float4 v = {0.f, 0.f, 0.f, 0.f};
+      if (c0 + r < m) v = reinterpret_cast<const float4*>(ch + (size_t)c0 * D)[i];
+      reinterpret_cast<float4*>(cs)[i] = v;
+    }
+    if (tid < CB) bs[tid] = (c0 + tid < m) ? bh[c0 + tid] : -INFINITY;
+    __syncthreads();
+    const int rmax = min(CB, m - c0);
+    for (int r = 0; r < rmax; ++r) {
+      float s = 0.f;
+#pragma unroll
+      for (int q = 0; q < D / 4; ++q) {
+        const float4 v = *reinterpret_cast<const float4*>(&cs[r * D + 4 * q]);
+        s = fmaf(x[4 * q], v.x, s); s = fmaf(x[4 * q + 1], v.y, s);
+        s = fmaf(x[4 * q + 2], v.z, s); s = fmaf(x[4 * q + 3], v.w, s);
+      }
+      s += bs[r];
+      if (s > best) { best = s; bidx = c0 + r; }
+    }
+  }
+  if (p < n) {
+    labels[(size_t)h * cfg.N + p] = bidx;
+    if (dist2) dist2[(size_t)h * cfg.N + p] = fmaxf(xn2 - 2.f * best, 0.f);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// centroid update: segmented sums over the sorted order (no atomics, fixed summation order)
+// ------------------------------------------------------------------------------------------
+struct ReduceCfg {
+  int mode;            // same meaning as AssignCfg::mode (where m and activity come from)
+  int m_const; int N; int P; int m_bound;
+  const KState* st;
+  int normalize;       // rows are scaled to unit length before summing (query clustering)
+  int want_box;
+};
+
+__device__ __forceinline__ bool reduce_setup(const ReduceCfg& c, int h, int& m) {
+  if (c.mode == 0) { m = c.m_const; return true; }
+  const KState& s = c.st[h];
+  if (c.mode == 1) { m = s.m_t; return s.active != 0; }
+  m = s.ccount; return true;
+}
+
+// One wave sums one part of one cluster.  A lane owns two adjacent columns; with D = 64 the two
+// half-waves take alternate rows.  psum [H][m_bound][P][D]; pnorm [H][m_bound][P];
+// pmin/pmax like psum.
+template <typename T, int D>
+__global__ __launch_bounds__(64) void seg_reduce(const T* __restrict__ X, ReduceCfg cfg,
+                                                 const int32_t* __restrict__ perm,
+                                                 const int32_t* __restrict__ offs, int offs_stride,
+                                                 float* __restrict__ psum, float* __restrict__ pnorm,
+                                                 float* __restrict__ pmin, float* __restrict__ pmax) {
+  constexpr int LPR = D / 2;          // lanes per row
+  constexpr int RPI = 64 / LPR;       // rows per wave step
+  const int h = blockIdx.y;
+  int m;
+  if (!reduce_setup(cfg, h, m)) return;
+  const int j = blockIdx.x / cfg.P, part = blockIdx.x % cfg.P;
+  if (j >= m) return;
+  const int lane = threadIdx.x, sub = lane / LPR, c2 = lane % LPR;
+  const int beg = offs[(size_t)h * offs_stride + j], end = offs[(size_t)h * offs_stride + j + 1];
+  const int nj = end - beg;
+  const int chunk = (nj + cfg.P - 1) / cfg.P;
+  const int mb = beg + part * chunk;
+  const int me = min(end, mb + chunk);
+  const int32_t* pm = perm + (size_t)h * cfg.N;
+  const T* Xh = X + (size_t)h * cfg.N * D;
+  float a0 = 0.f, a1 = 0.f, nsum = 0.f;
+  float mn0 = INFINITY, mn1 = INFINITY, mx0 = -INFINITY, mx1 = -INFINITY;
+  for (int r = mb + sub; r < me; r += RPI) {
+    const int tok = pm[r];
+    const T* row = Xh + (size_t)tok * D + 2 * c2;
+    float x0 = Elem<T>::load(row), x1 = Elem<T>::load(row + 1);
+    if (cfg.normalize) {
+      float ss = fmaf(x0, x0, x1 * x1);
+#pragma unroll
+      for (int o = 1; o < LPR; o <<= 1) ss += __shfl_xor(ss, o);
+      const float nrm = sqrtf(ss);
+      const float inv = 1.0f / fmaxf(nrm, 1e-12f);
+      x0 *= inv; x1 *= inv;
+      nsum += nrm;
+    }
+    a0 += x0; a1 += x1;
+    if (cfg.want_box) { mn0 = fminf(mn0, x0); mn1 = fminf(mn1, x1); mx0 = fmaxf(mx0, x0); mx1 = fmaxf(mx1, x1); }
+  }
+  if (RPI == 2) {
+    a0 += __shfl_xor(a0, 32); a1 += __shfl_xor(a1, 32); nsum += __shfl_xor(nsum, 32);
+    mn0 = fminf(mn0, __shfl_xor(mn0, 32)); mn1 = fminf(mn1, __shfl_xor(mn1, 32));
+    mx0 = fmaxf(mx0, __shfl_xor(mx0, 32)); mx1 = fmaxf(mx1, __shfl_xor(mx1, 32));
+  }
+  if (sub == 0) {
+    const size_t o = (((size_t)h * cfg.m_bound + j) * cfg.P + part);
+    psum[o * D + 2 * c2] = a0; psum[o * D + 2 * c2 + 1] = a1;
+    if (cfg.want_box) {
+      pmin[o * D + 2 * c2] = mn0; pmin[o * D + 2 * c2 + 1] = mn1;
+      pmax[o * D + 2 * c2] = mx0; pmax[o * D + 2 * c2 + 1] = mx1;
+    }
+    if (cfg.normalize && c2 == 0) pnorm[o] = nsum;
+  }
+}
+
+// Combine the parts and write centres.
+//   update_assign = 1 (Lloyd step): non-empty clusters get master := mean (or unit mean), the
+//     I/O-dtype copy used by the next assignment, its fp32 image and the arg-max bias.
+//   update_assign = 0 (final): out_cent := mean / unit mean (empty: `fallback` row), sizes, mean
+//     norms, boxes.  `master` is also refreshed when given (query clustering returns it).
+struct FinalizeCfg {
+  int mode; int m_const; int P; int m_bound; int cap; int master_stride;
+  const KState* st;
+  int spherical; int update_assign; int lp_is_bf16; int want_box;
+};
+
+template <int D>
+__global__ __launch_bounds__(64) void finalize_centroids(FinalizeCfg cfg, const int32_t* __restrict__ offs,
+                                                         int offs_stride, const float* __restrict__ psum,
+                                                         const float* __restrict__ pnorm,
+                                                         const float* __restrict__ pmin,
+                                                         const float* __restrict__ pmax,
+                                                         float* __restrict__ master, void* __restrict__ assign_lp,
+                                                         float* __restrict__ assign_f32, float* __restrict__ bias,
+                                                         float* __restrict__ out_cent, const float* __restrict__ fallback,
+                                                         int32_t* __restrict__ out_sizes, float* __restrict__ out_mean_norm,
+                                                         float* __restrict__ out_bmin, float* __restrict__ out_bmax) {
+  constexpr int CPL = D / 64;          // columns per lane
+  const int h = blockIdx.y, j = blockIdx.x, lane = threadIdx.x;
+  int m, row_off = 0;
+  if (cfg.mode == 0) m = cfg.m_const;
+  else {
+    const KState& s = cfg.st[h];
+    if (cfg.mode == 1) { if (!s.active) return; m = s.m_t; row_off = s.ccount; }
+    else m = s.ccount;
+  }
+  if (j >= m) {
+    if (!cfg.update_assign && out_sizes && j < cfg.cap) out_sizes[(size_t)h * cfg.cap + j] = 0;
+    return;
+  }
+  const int nj = offs[(size_t)h * offs_stride + j + 1] - offs[(size_t)h * offs_stride + j];
+  const size_t pbase = ((size_t)h * cfg.m_bound + j) * cfg.P;
+  float s[CPL], mn[CPL], mx[CPL];
+#pragma unroll
+  for (int q = 0; q < CPL; ++q) { s[q] = 0.f; mn[q] = INFINITY; mx[q] = -INFINITY; }
+  float ns = 0.f;
+  for (int p = 0; p < cfg.P; ++p) {
+#pragma unroll
+    for (int q = 0; q < CPL; ++q) {
+      s[q] += psum[(pbase + p) * D + lane + 64 * q];
+      if (cfg.want_box) {
+        mn[q] = fminf(mn[q], pmin[(pbase + p) * D + lane + 64 * q]);
+        mx[q] = fmaxf(mx[q], pmax[(pbase + p) * D + lane + 64 * q]);
+      }
+    }
+    if (cfg.spherical) ns += pnorm[pbase + p];
+  }
+  bool ok = nj > 0;
+  float val[CPL];
+  if (cfg.spherical) {
+    float ss = 0.f;
+#pragma unroll
+    for (int q = 0; q < CPL; ++q) ss = fmaf(s[q], s[q], ss);
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) ss += __shfl_xor(ss, o);
+    const float nrm = sqrtf(ss);
+    ok = ok && (nrm >= 1e-12f);
+#pragma unroll
+    for (int q = 0; q < CPL; ++q) val[q] = s[q] / fmaxf(nrm, 1e-30f);
+  } else {
+#pragma unroll
+    for (int q = 0; q < CPL; ++q) val[q] = s[q] / (float)max(nj, 1);
+  }
+  if (cfg.update_assign) {
+    if (!ok) return;
+    float bsum = 0.f;
+#pragma unroll
+    for (int q = 0; q < CPL; ++q) {
+      const int col = lane + 64 * q;
+      master[((size_t)h * cfg.master_stride + j) * D + col] = val[q];
+      const size_t ao = ((size_t)h * cfg.cap + row_off + j) * D + col;
+      float img = val[q];
+      if (cfg.lp_is_bf16) {
+        const bf16raw r = f32_to_bf16(val[q]);
+        reinterpret_cast<bf16raw*>(assign_lp)[ao] = r;
+        img = bf16_to_f32(r);
+      } else {
+        reinterpret_cast<float*>(assign_lp)[ao] = img;
+      }
+      assign_f32[ao] = img;
+      bsum = fmaf(img, img, bsum);
+    }
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) bsum += __shfl_xor(bsum, o);
+    if (lane == 0) bias[(size_t)h * cfg.cap + row_off + j] = cfg.spherical ? 0.f : -0.5f * bsum;
+    return;
+  }
+  // final outputs
+#pragma unroll
+  for (int q = 0; q < CPL; ++q) {
+    const int col = lane + 64 * q;
+    const size_t oo = ((size_t)h * cfg.cap + j) * D + col;
+    if (ok) {
+      out_cent[oo] = val[q];
+    } else if (fallback) {
+      out_cent[oo] = fallback[oo];
+    }
+    if (cfg.want_box) {
+      out_bmin[oo] = nj > 0 ? mn[q] : 0.f;
+      out_bmax[oo] = nj > 0 ? mx[q] : 0.f;
+    }
+  }
+  if (lane == 0) {
+    if (out_sizes) out_sizes[(size_t)h * cfg.cap + j] = nj;
+    if (out_mean_norm) out_mean_norm[(size_t)h * cfg.cap + j] = nj > 0 ? ns / (float)nj : 0.f;
+  }
+}
+
+// Initial centres: strided sample of the current point list (or the rows of `master` as given).
+//   source_master = 1: master already holds the centres (warm start)
+template <typename T, int D>
+__global__ __launch_bounds__(64) void init_centroids(const T* __restrict__ X, int N, int mode, int m_const,
+                                                     const KState* __restrict__ st,
+                                                     const int32_t* __restrict__ ulist, int spherical,
+                                                     int source_master, int cap, int master_stride,
+                                                     int lp_is_bf16, float* __restrict__ master,
+                                                     void* __restrict__ assign_lp, float* __restrict__ assign_f32,
+                                                     float* __restrict__ bias) {
+  constexpr int CPL = D / 64;
+  const int h = blockIdx.y, j = blockIdx.x, lane = threadIdx.x;
+  int n = N, m = m_const, row_off = 0;
+  if (mode == 1) {
+    const KState& s = st[h];
+    if (!s.active) return;
+    n = s.ucount; m = s.m_t; row_off = s.ccount;
+  }
+  if (j >= m) return;
+  float val[CPL];
+  if (source_master) {
+#pragma unroll
+    for (int q = 0; q < CPL; ++q) val[q] = master[((size_t)h * master_stride + j) * D + lane + 64 * q];
+  } else {
+    const long long pos = ((2ll * j + 1) * (long long)n) / (2ll * m);
+    const int tok = ulist ? ulist[(size_t)h * N + pos] : (int)pos;
+    const T* row = X + ((size_t)h * N + tok) * D;
+#pragma unroll
+    for (int q = 0; q < CPL; ++q) val[q] = Elem<T>::load(row + lane + 64 * q);
+    if (spherical) {
+      float ss = 0.f;
+#pragma unroll
+      for (int q = 0; q < CPL; ++q) ss = fmaf(val[q], val[q], ss);
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) ss += __shfl_xor(ss, o);
+      const float inv = 1.0f / fmaxf(sqrtf(ss), 1e-12f);
+#pragma unroll
+      for (int q = 0; q < CPL; ++q) val[q] *= inv;
+    }
+  }
+  float bsum = 0.f;
+#pragma unroll
+  for (int q = 0; q < CPL; ++q) {
+    const int col = lane + 64 * q;
+    master[((size_t)h * master_stride + j) * D + col] = val[q];
+    const size_t ao = ((size_t)h * cap + row_off + j) * D + col;
+    float img = val[q];
+    if (lp_is_bf16) {
+      const bf16raw r = f32_to_bf16(val[q]);
+      reinterpret_cast<bf16raw*>(assign_lp)[ao] = r;
+      img = bf16_to_f32(r);
+    } else {
+      reinterpret_cast<float*>(assign_lp)[ao] = img;
+    }
+    assign_f32[ao] = img;
+    bsum = fmaf(img, img, bsum);
+  }
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) bsum += __shfl_xor(bsum, o);
+  if (lane == 0) bias[(size_t)h * cap + row_off + j] = spherical ? 0.f : -0.5f * bsum;
+}
+
+// ------------------------------------------------------------------------------------------
+// Algorithm 1 bookkeeping
+// ------------------------------------------------------------------------------------------
+__global__ void kstate_init(KState* st, int H, int N) {
+  const int h = blockIdx.x * blockDim.x + threadIdx.x;
+  if (h >= H) return;
+  KState s;
+  s.ucount = N; s.ccount = 0; s.m_t = 0; s.stage = 0; s.done = 0; s.full = 0; s.active = 0; s.pad = 0;
+  for (int i = 0; i <= ADACLUSTER_MAX_STAGES; ++i) s.stage_offs[i] = 0;
+  st[h] = s;
+}
+
+// Head of the while-loop of Algorithm 1: U empty? |C| >= N_max (flag F)?  stage / leftover limits?
+// then the centre count m_t of the next stage.  summary = {active heads, max |U|, max m_t}.
+__global__ void kstage_begin(KState* st, int H, int N, int n_max, int m0, int m_min, int max_stages,
+                             int u_min, int32_t* summary) {
+  __shared__ int32_t s_act, s_u, s_m;
+  if (threadIdx.x == 0) { s_act = 0; s_u = 0; s_m = 0; }
+  __syncthreads();
+  for (int h = threadIdx.x; h < H; h += blockDim.x) {
+    KState s = st[h];
+    if (!s.done) {
+      if (s.ucount == 0) s.done = 1;
+      else if (s.ccount >= n_max) { s.full = 1; s.done = 1; }
+      else if (s.stage >= max_stages || s.ucount <= u_min) s.done = 1;
+    }
+    s.active = !s.done;
+    if (s.active) {
+      long long mm = ((long long)m0 * s.ucount + N - 1) / N;
+      int m = (int)mm;
+      m = max(m_min, min(m0, m));
+      m = min(m, s.ucount);
+      s.m_t = m;
+      atomicAdd(&s_act, 1); atomicMax(&s_u, s.ucount); atomicMax(&s_m, m);
+    } else {
+      s.m_t = 0;
+    }
+    st[h] = s;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) { summary[0] = s_act; summary[1] = s_u; summary[2] = s_m; }
+}
+
+// tau = factor x mean first-stage distance over all heads and tokens (Sec. 4.1).
+__global__ __launch_bounds__(256) void tau_partial(const float* __restrict__ dist2, int N, int nblk,
+                                                   double* __restrict__ part) {
+  const int h = blockIdx.y, b = blockIdx.x, tid = threadIdx.x;
+  double s = 0.0;
+  const int beg = b * 1024;
+  for (int i = 0; i < 4; ++i) {
+    const int p = beg + i * 256 + tid;
+    if (p < N) s += (double)sqrtf(dist2[(size_t)h * N + p]);
+  }
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) s += __shfl_xor(s, o);
+  __shared__ double ws[4];
+  if ((tid & 63) == 0) ws[tid >> 6] = s;
+  __syncthreads();
+  if (tid == 0) part[(size_t)h * nblk + b] = (ws[0] + ws[1]) + (ws[2] + ws[3]);
+}
+
+__global__ void tau_final(const double* __restrict__ part, int count, double denom, float factor,
+                          float* __restrict__ tau_out /* [0]=tau, [1]=tau^2 */) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  double s = 0.0;
+  for (int i = 0; i < count; ++i) s += part[i];
+  const double tau = (double)factor * s / denom;
+  tau_out[0] = (float)tau;
+  tau_out[1] = (float)tau * (float)tau;
+}
+
+__global__ void tau_set(float tau, float* __restrict__ tau_out) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) { tau_out[0] = tau; tau_out[1] = tau * tau; }
+}
+
+// threshold filter of Algorithm 1: tokens with d < tau leave U.  Three passes keep U ascending.
+__global__ __launch_bounds__(256) void filter_count(const KState* __restrict__ st, const float* __restrict__ dist2,
+                                                    int N, int nblk, const float* __restrict__ tau,
+                                                    int32_t* __restrict__ blockcnt) {
+  const int h = blockIdx.y, b = blockIdx.x, tid = threadIdx.x;
+  const KState& s = st[h];
+  if (!s.active) return;
+  const int n = s.ucount;
+  const float t2 = tau[1];
+  int c = 0;
+  for (int i = 0; i < 4; ++i) {
+    const int p = b * 1024 + i * 256 + tid;
+    if (p < n && !(dist2[(size_t)h * N + p] < t2)) ++c;
+  }
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) c += __shfl_xor(c, o);
+  __shared__ int32_t ws[4];
+  if ((tid & 63) == 0) ws[tid >> 6] = c;
+  __syncthreads();
+  if (tid == 0) blockcnt[(size_t)h * nblk + b] = ws[0] + ws[1] + ws[2] + ws[3];
+}
+
+__global__ void filter_scan(KState* __restrict__ st, int nblk_used, int nblk, int32_t* __restrict__ blockcnt,
+                            int32_t* __restrict__ u_prev) {
+  const int h = blockIdx.x;
+  if (threadIdx.x != 0) return;
+  KState s = st[h];
+  if (!s.active) return;
+  const int nb = (s.ucount + 1023) / 1024;
+  int run = 0;
+  for (int b = 0; b < nb && b < nblk_used; ++b) {
+    const int c = blockcnt[(size_t)h * nblk + b];
+    blockcnt[(size_t)h * nblk + b] = run;
+    run += c;
+  }
+  u_prev[h] = s.ucount;
+  s.ucount = run;
+  s.ccount += s.m_t;
+  s.stage += 1;
+  s.stage_offs[s.stage] = s.ccount;
+  st[h] = s;
+}
+
+__global__ __launch_bounds__(256) void filter_scatter(const KState* __restrict__ st, const int32_t* __restrict__ u_prev,
+                                                      const float* __restrict__ dist2, int N, int nblk,
+                                                      const float* __restrict__ tau,
+                                                      const int32_t* __restrict__ blockbase,
+                                                      const int32_t* __restrict__ ulist_in,
+                                                      int32_t* __restrict__ ulist_out,
+                                                      int32_t* __restrict__ stage_of, int stage) {
+  const int h = blockIdx.y, b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const KState& s = st[h];
+  if (!s.active) return;
+  const int n = u_prev[h];
+  if (b * 1024 >= n) return;
+  const float t2 = tau[1];
+  int run = blockbase[(size_t)h * nblk + b];
+  __shared__ int32_t ws[4];
+  const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  for (int i = 0; i < 4; ++i) {
+    const int p = b * 1024 + i * 256 + tid;
+    const bool valid = p < n;
+    const bool keep = valid && !(dist2[(size_t)h * N + p] < t2);
+    const int tok = valid ? (ulist_in ? ulist_in[(size_t)h * N + p] : p) : 0;
+    const uint64_t bal = __ballot(keep);
+    __syncthreads();
+    if (lane == 0) ws[wave] = __popcll(bal);
+    __syncthreads();
+    int before = 0;
+    for (int w = 0; w < wave; ++w) before += ws[w];
+    const int total = ws[0] + ws[1] + ws[2] + ws[3];
+    if (keep) ulist_out[(size_t)h * N + run + before + __popcll(bal & lt_mask)] = tok;
+    if (valid && !keep && stage_of) stage_of[(size_t)h * N + tok] = stage;
+    run += total;
+  }
+}
+
+__global__ void fill_i32(int32_t* p, size_t n, int32_t v) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// k_count, full_flag and stage offsets out of the state
+__global__ void kstate_export(const KState* __restrict__ st, int H, int32_t* k_count, int32_t* full_flag,
+                              int32_t* stage_offs) {
+  const int h = blockIdx.x * blockDim.x + threadIdx.x;
+  if (h >= H) return;
+  const KState& s = st[h];
+  if (k_count) k_count[h] = s.ccount;
+  if (full_flag) full_flag[h] = s.full;
+  if (stage_offs)
+    for (int i = 0; i <= ADACLUSTER_MAX_STAGES; ++i)
+      stage_offs[(size_t)h * (ADACLUSTER_MAX_STAGES + 1) + i] = (i <= s.stage) ? s.stage_offs[i] : s.ccount;
+}
+
+// ------------------------------------------------------------------------------------------
+// host-side launchers
+// ------------------------------------------------------------------------------------------
+static inline int chk() { return hipGetLastError() == hipSuccess ? 0 : ADACLUSTER_E_INTERNAL; }
+
+int launch_assign(hipStream_t s, int dtype, int d, int H, int N, int n_bound, int mode, int m_const, int cap,
+                  const KState* st, const int32_t* ulist, const void* X, const void* cent_lp, const float* bias,
+                  int32_t* labels, float* dist2) {
+  AssignCfg c{mode, m_const, N, cap, st, ulist};
+  if (dtype == ADACLUSTER_BF16) {
+    dim3 g((n_bound + 255) / 256, H);
+    if (d == 64) assign_mfma<64><<<g, 256, 0, s>>>((const bf16raw*)X, c, (const bf16raw*)cent_lp, bias, labels, dist2);
+    else assign_mfma<128><<<g, 256, 0, s>>>((const bf16raw*)X, c, (const bf16raw*)cent_lp, bias, labels, dist2);
+  } else {
+    dim3 g((n_bound + 127) / 128, H);
+    if (d == 64) assign_f32<64><<<g, 128, 0, s>>>((const float*)X, c, (const float*)cent_lp, bias, labels, dist2);
+    else assign_f32<128><<<g, 128, 0, s>>>((const float*)X, c, (const float*)cent_lp, bias, labels, dist2);
+  }
+  return chk();
+}
+
+int launch_seg_reduce(hipStream_t s, int dtype, int d, int H, int N, int mode, int m_const, int m_bound, int P,
+                      const KState* st, int normalize, int want_box, const void* X, const int32_t* perm,
+                      const int32_t* offs, int offs_stride, float* psum, float* pnorm, float* pmin, float* pmax) {
+  ReduceCfg c{mode, m_const, N, P, m_bound, st, normalize, want_box};
+  dim3 g(m_bound * P, H);
+  if (dtype == ADACLUSTER_BF16) {
+    if (d == 64) seg_reduce<bf16raw, 64><<<g, 64, 0, s>>>((const bf16raw*)X, c, perm, offs, offs_stride, psum, pnorm, pmin, pmax);
+    else seg_reduce<bf16raw, 128><<<g, 64, 0, s>>>((const bf16raw*)X, c, perm, offs, offs_stride, psum, pnorm, pmin, pmax);
+  } else {
+    if (d == 64) seg_reduce<float, 64><<<g, 64, 0, s>>>((const float*)X, c, perm, offs, offs_stride, psum, pnorm, pmin, pmax);
+    else seg_reduce<float, 128><<<g, 64, 0, s>>>((const float*)X, c, perm, offs, offs_stride, psum, pnorm, pmin, pmax);
+  }
+  return chk();
+}
+
+int launch_finalize(hipStream_t s, int dtype, int d, int H, int mode, int m_const, int m_bound, int P, int cap,
+                    int master_stride, const KState* st, int spherical, int update_assign, int want_box,
+                    const int32_t* offs, int offs_stride, const float* psum, const float* pnorm,
+                    const float* pmin, const float* pmax, float* master, void* assign_lp, float* assign_f32,
+                    float* bias, float* out_cent, const float* fallback, int32_t* out_sizes,
+                    float* out_mean_norm, float* out_bmin, float* out_bmax) {
+  FinalizeCfg c{mode, m_const, P, m_bound, cap, master_stride, st, spherical, update_assign,
+                dtype == ADACLUSTER_BF16, want_box};
+  // in final mode every row of the output (up to cap) gets a size, so cover cap rows
+  dim3 g(update_assign ? m_bound : cap, H);
+  if (d == 64)
+    finalize_centroids<64><<<g, 64, 0, s>>>(c, offs, offs_stride, psum, pnorm, pmin, pmax, master, assign_lp,
+                                            assign_f32, bias, out_cent, fallback, out_sizes, out_mean_norm,
+                                            out_bmin, out_bmax);
+  else
+    finalize_centroids<128><<<g, 64, 0, s>>>(c, offs, offs_stride, psum, pnorm, pmin, pmax, master, assign_lp,
+                                             assign_f32, bias, out_cent, fallback, out_sizes, out_mean_norm,
+                                             out_bmin, out_bmax);
+  return chk();
+}
+
+int launch_init_centroids(hipStream_t s, int dtype, int d, int H, int N, int mode, int m_const, int m_bound,
+                          const KState* st, const int32_t* ulist, int spherical, int source_master, int cap,
+                          int master_stride, const void* X, float* master, void* assign_lp, float* assign_f32,
+                          float* bias) {
+  dim3 g(m_bound, H);
+  const int lp = dtype == ADACLUSTER_BF16;
+  if (dtype == ADACLUSTER_BF16) {
+    if (d == 64) init_centroids<bf16raw, 64><<<g, 64, 0, s>>>((const bf16raw*)X, N, mode, m_const, st, ulist, spherical, source_master, cap, master_stride, lp, master, assign_lp, assign_f32, bias);
+    else init_centroids<bf16raw, 128><<<g, 64, 0, s>>>((const bf16raw*)X, N, mode, m_const, st, ulist, spherical, source_master, cap, master_stride, lp, master, assign_lp, assign_f32, bias);
+  } else {
+    if (d == 64) init_centroids<float, 64><<<g, 64, 0, s>>>((const float*)X, N, mode, m_const, st, ulist, spherical, source_master, cap, master_stride, lp, master, assign_lp, assign_f32, bias);
+    else init_centroids<float, 128><<<g, 64, 0, s>>>((const float*)X, N, mode, m_const, st, ulist, spherical, source_master, cap, master_stride, lp, master, assign_lp, assign_f32, bias);
+  }
+  return chk();
+}
+
+int launch_kstate_init(hipStream_t s, KState* st, int H, int N) {
+  kstate_init<<<(H + 63) / 64, 64, 0, s>>>(st, H, N);
+  return chk();
+}
+
+int launch_kstage_begin(hipStream_t s, KState* st, int H, int N, int n_max, int m0, int m_min, int max_stages,
+                        int u_min, int32_t* summary) {
+  kstage_begin<<<1, 256, 0, s>>>(st, H, N, n_max, m0, m_min, max_stages, u_min, summary);
+  return chk();
+}
+
+int launch_tau(hipStream_t s, int H, int N, const float* dist2, double* part, float factor, float tau_abs,
+               float* tau_out) {
+  if (tau_abs > 0.f) {
+    tau_set<<<1, 64, 0, s>>>(tau_abs, tau_out);
+    return chk();
+  }
+  const int nblk = (N + 1023) / 1024;
+  tau_partial<<<dim3(nblk, H), 256, 0, s>>>(dist2, N, nblk, part);
+  tau_final<<<1, 64, 0, s>>>(part, nblk * H, (double)H * (double)N, factor, tau_out);
+  return chk();
+}
+
+int launch_filter(hipStream_t s, KState* st, int H, int N, int n_bound, const float* dist2, const float* tau,
+                  int32_t* blockcnt, int32_t* u_prev, const int32_t* ulist_in, int32_t* ulist_out,
+                  int32_t* stage_of, int stage) {
+  const int nblk = (N + 1023) / 1024;
+  const int nb = (n_bound + 1023) / 1024;
+  filter_count<<<dim3(nb, H), 256, 0, s>>>(st, dist2, N, nblk, tau, blockcnt);
+  filter_scan<<<H, 64, 0, s>>>(st, nb, nblk, blockcnt, u_prev);
+  filter_scatter<<<dim3(nb, H), 256, 0, s>>>(st, u_prev, dist2, N, nblk, tau, blockcnt, ulist_in, ulist_out,
+                                             stage_of, stage);
+  return chk();
+}
+
+int launch_fill_i32(hipStream_t s, int32_t* p, size_t n, int32_t v) {
+  if (n == 0) return 0;
+  fill_i32<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(p, n, v);
+  return chk();
+}
+
+int launch_kstate_export(hipStream_t s, const KState* st, int H, int32_t* k_count, int32_t* full_flag,
+                         int32_t* stage_offs) {
+  kstate_export<<<(H + 63) / 64, 64, 0, s>>>(st, H, k_count, full_flag, stage_offs);
+  return chk();
+}
+
+}  // namespace adac

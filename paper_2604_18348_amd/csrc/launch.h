@@ -1,0 +1,72 @@
+// Host-side launchers of the kernels (each enqueues on the given stream and returns 0 or
+// ADACLUSTER_E_INTERNAL).
+#pragma once
+#include "common.h"
+
+namespace adac {
+
+struct SortScratch {
+  int32_t* hist;                     // [H][nseg][128]
+  int32_t* lab_a; int32_t* val_a;    // [H][N] intermediate pass
+  int32_t* lab_b;                    // [H][N] sorted labels
+};
+
+// Stable sort of the first n_h items of every head by label (labels are indexed by position in
+// the item list; the items are token ids from `ulist`, or the positions themselves).
+//   n_dev / m_dev: per-head item and label counts read on the device (NULL: n_bound / m_bound)
+//   active_dev:    per-head flag; heads with 0 are skipped (NULL: all heads)
+// Outputs: perm [H][N] token ids ordered by (label, position); offs [H][offs_stride] with
+// offs[j] = first sorted position of label j for j = 0..m_h.
+int launch_sort(hipStream_t st, int H, int N, int n_bound, int m_bound, const int32_t* labels,
+                const int32_t* ulist, const int32_t* n_dev, int n_stride, const int32_t* m_dev, int m_stride,
+                const int32_t* active_dev, int active_stride, int32_t* perm, int32_t* offs, int offs_stride,
+                const SortScratch& sc);
+
+int launch_assign(hipStream_t s, int dtype, int d, int H, int N, int n_bound, int mode, int m_const, int cap,
+                  const KState* st, const int32_t* ulist, const void* X, const void* cent_lp, const float* bias,
+                  int32_t* labels, float* dist2);
+int launch_seg_reduce(hipStream_t s, int dtype, int d, int H, int N, int mode, int m_const, int m_bound, int P,
+                      const KState* st, int normalize, int want_box, const void* X, const int32_t* perm,
+                      const int32_t* offs, int offs_stride, float* psum, float* pnorm, float* pmin, float* pmax);
+int launch_finalize(hipStream_t s, int dtype, int d, int H, int mode, int m_const, int m_bound, int P, int cap,
+                    int master_stride, const KState* st, int spherical, int update_assign, int want_box,
+                    const int32_t* offs, int offs_stride, const float* psum, const float* pnorm,
+                    const float* pmin, const float* pmax, float* master, void* assign_lp, float* assign_f32,
+                    float* bias, float* out_cent, const float* fallback, int32_t* out_sizes,
+                    float* out_mean_norm, float* out_bmin, float* out_bmax);
+int launch_init_centroids(hipStream_t s, int dtype, int d, int H, int N, int mode, int m_const, int m_bound,
+                          const KState* st, const int32_t* ulist, int spherical, int source_master, int cap,
+                          int master_stride, const void* X, float* master, void* assign_lp, float* assign_f32,
+                          float* bias);
+int launch_kstate_init(hipStream_t s, KState* st, int H, int N);
+int launch_kstage_begin(hipStream_t s, KState* st, int H, int N, int n_max, int m0, int m_min, int max_stages,
+                        int u_min, int32_t* summary);
+int launch_tau(hipStream_t s, int H, int N, const float* dist2, double* part, float factor, float tau_abs,
+               float* tau_out);
+int launch_filter(hipStream_t s, KState* st, int H, int N, int n_bound, const float* dist2, const float* tau,
+                  int32_t* blockcnt, int32_t* u_prev, const int32_t* ulist_in, int32_t* ulist_out,
+                  int32_t* stage_of, int stage);
+int launch_fill_i32(hipStream_t s, int32_t* p, size_t n, int32_t v);
+int launch_kstate_export(hipStream_t s, const KState* st, int H, int32_t* k_count, int32_t* full_flag,
+                         int32_t* stage_offs);
+
+int launch_select(hipStream_t s, int H, int Cq, int cap, int d, int score_mode, int select_mode, int topk,
+                  float top_p, float scale, const float* q_cent, const float* q_mean_norm, const float* k_cent,
+                  const float* k_bmin, const float* k_bmax, const int32_t* k_sizes, const int32_t* k_count,
+                  const int32_t* full_flag, int32_t* sel_idx, int32_t* sel_cnt);
+
+int attn_block_rows(int dtype, int d);
+int launch_permute_kv(hipStream_t s, int H, int N, int row_bytes, const void* K, const void* V,
+                      const int32_t* perm, void* Kp, void* Vp);
+int launch_plan_sparse(hipStream_t s, int H, int Cq, int cap, int maxr, int maxtiles, int BM,
+                       const int32_t* q_offs, int q_offs_stride, const int32_t* k_offs, int k_offs_stride,
+                       const int32_t* k_count, const int32_t* sel_idx, const int32_t* sel_cnt,
+                       int32_t* rng_start, int32_t* rng_pre, int32_t* rng_cnt, int32_t* tiles, int32_t* ntiles);
+int launch_plan_dense(hipStream_t s, int H, int N, int maxtiles, int BM, int32_t* rng_start, int32_t* rng_pre,
+                      int32_t* rng_cnt, int32_t* tiles, int32_t* ntiles);
+int launch_attention(hipStream_t s, int dtype, int d, int H, int N, int Cq, int maxtiles, int maxr, float scale,
+                     const void* Q, const void* Kp, const void* Vp, void* O, const int32_t* perm_q,
+                     const int32_t* tiles, const int32_t* ntiles, const int32_t* rng_start,
+                     const int32_t* rng_pre, const int32_t* rng_cnt);
+
+}  // namespace adac

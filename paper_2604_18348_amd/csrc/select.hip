@@ -1,0 +1,212 @@
+// Critical-cluster selection: centroid scores (Eq. 1 / Eq. 2, Algorithm 2), arg-top-k (Alg. 3
+// line 8) and the top-p budget.
+//
+// The score matrix is tiny (Cq x Ck x d per head), so it is evaluated in fp64 with one rounded
+// multiply and one rounded add per term, summed in ascending dimension order.  That makes every
+// bit of a score, and therefore every selected index set, reproducible by a CPU implementation.
+// Floating-point contraction is switched off for this file for the same reason.
+#include "common.h"
+#include "launch.h"
+
+#pragma clang fp contract(off)
+
+namespace adac {
+
+struct SelectCfg {
+  int Cq, cap, d;
+  int score_mode, select_mode, topk;
+  double top_p, scale;
+};
+
+// exp(x), x <= 0, from rounded +,* only: k = rint(x log2 e); r = (x - k ln2_hi) - k ln2_lo;
+// degree-13 Taylor polynomial in Horner form; scaled by 2^k.  0 below -700.
+__device__ double exp_det(double x) {
+#pragma clang fp contract(off)
+  if (x < -700.0) return 0.0;
+  const double k = rint(x * 1.4426950408889634);
+  const double r = (x - k * 0.693147180369123816490) - k * 1.90821492927058770002e-10;
+  double fact = 6227020800.0;          // 13!
+  double p = 1.0 / fact;
+  for (int n = 12; n >= 0; --n) {
+    fact = fact / (double)(n + 1);     // n!
+    p = p * r + 1.0 / fact;
+  }
+  return ldexp(p, (int)k);
+}
+
+// monotone map double -> uint64 (larger double = larger key); -inf is the smallest key
+__device__ __forceinline__ uint64_t order_key(double v) {
+  const uint64_t u = (uint64_t)__double_as_longlong(v);
+  return (u >> 63) ? ~u : (u | 0x8000000000000000ull);
+}
+
+// One block per (query cluster, head).  Dynamic LDS: key[cap] (uint64) + flag[cap] (int).
+__global__ __launch_bounds__(256) void select_kernel(SelectCfg cfg, const float* __restrict__ q_cent,
+                                                     const float* __restrict__ q_mean_norm,
+                                                     const float* __restrict__ k_cent,
+                                                     const float* __restrict__ k_bmin,
+                                                     const float* __restrict__ k_bmax,
+                                                     const int32_t* __restrict__ k_sizes,
+                                                     const int32_t* __restrict__ k_count,
+                                                     const int32_t* __restrict__ full_flag,
+                                                     int32_t* __restrict__ sel_idx, int32_t* __restrict__ sel_cnt) {
+#pragma clang fp contract(off)
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  double* sval = reinterpret_cast<double*>(smem);                        // [cap] score, then weight
+  uint64_t* skey = reinterpret_cast<uint64_t*>(smem + (size_t)cfg.cap * 8);   // [cap]
+  int32_t* sflag = reinterpret_cast<int32_t*>(smem + (size_t)cfg.cap * 16);   // [cap]
+  __shared__ double qrow[128];
+  __shared__ int32_t wsum[4];
+  __shared__ int32_t s_take;
+  __shared__ double s_max;
+
+  const int h = blockIdx.y, i = blockIdx.x, tid = threadIdx.x;
+  const int d = cfg.d;
+  const int kc = k_count[h];
+  const bool all = full_flag[h] != 0;
+  if (tid < d) qrow[tid] = (double)q_cent[((size_t)h * cfg.Cq + i) * d + tid];
+  __syncthreads();
+
+  // ---- scores
+  for (int j = tid; j < kc; j += 256) {
+    const int nj = k_sizes[(size_t)h * cfg.cap + j];
+    double s;
+    if (nj == 0) {
+      s = -INFINITY;
+    } else if (all) {
+      s = 0.0;
+    } else if (cfg.score_mode == ADACLUSTER_SCORE_DOT) {
+      const float* cr = k_cent + ((size_t)h * cfg.cap + j) * d;
+      s = 0.0;
+      for (int t = 0; t < d; ++t) s = s + qrow[t] * (double)cr[t];
+    } else {
+      const float* rpos = (cfg.score_mode == ADACLUSTER_SCORE_BOX ? k_bmax : k_cent) + ((size_t)h * cfg.cap + j) * d;
+      const float* rneg = (cfg.score_mode == ADACLUSTER_SCORE_BOX ? k_bmin : k_cent) + ((size_t)h * cfg.cap + j) * d;
+      const bool clampk = cfg.score_mode == ADACLUSTER_SCORE_TQ;
+      double sp = 0.0, sn = 0.0;
+      for (int t = 0; t < d; ++t) {
+        const double q = qrow[t];
+        double kp = (double)rpos[t], kn = (double)rneg[t];
+        if (clampk) { kp = fmax(kp, 0.0); kn = fmin(kn, 0.0); }
+        sp = sp + fmax(q, 0.0) * kp;
+        sn = sn + fmin(q, 0.0) * kn;
+      }
+      s = sp + sn;
+    }
+    sval[j] = s;
+  }
+  __syncthreads();
+
+  const bool topp = cfg.select_mode == ADACLUSTER_SELECT_TOPP;
+  if (all || (topp && cfg.top_p >= 1.0)) {
+    for (int j = tid; j < kc; j += 256) sflag[j] = sval[j] > -INFINITY;
+  } else if (!topp) {
+    // rank by (score desc, index asc); keep rank < topk
+    for (int j = tid; j < kc; j += 256) skey[j] = order_key(sval[j]);
+    __syncthreads();
+    for (int j = tid; j < kc; j += 256) {
+      const uint64_t kj = skey[j];
+      int rank = 0;
+      for (int t = 0; t < kc; ++t) {
+        const uint64_t kt = skey[t];
+        rank += (kt > kj) || (kt == kj && t < j);
+      }
+      sflag[j] = (sval[j] > -INFINITY) && rank < cfg.topk;
+    }
+  } else {
+    // weights w_j = n_j exp(alpha (S_j - max S)); order by (w desc, j asc); shortest prefix
+    // whose running sum reaches top_p * total
+    if (tid == 0) {
+      double mx = -INFINITY;
+      for (int j = 0; j < kc; ++j) mx = fmax(mx, sval[j]);
+      s_max = mx;
+    }
+    __syncthreads();
+    const double alpha = (double)q_mean_norm[(size_t)h * cfg.Cq + i] * cfg.scale;
+    const double mx = s_max;
+    for (int j = tid; j < kc; j += 256) {
+      const int nj = k_sizes[(size_t)h * cfg.cap + j];
+      double w = 0.0;
+      if (nj > 0) w = (double)nj * exp_det(alpha * (sval[j] - mx));
+      const bool valid = sval[j] > -INFINITY;
+      sval[j] = w;
+      // invalid (empty) clusters sort after everything else
+      skey[j] = valid ? order_key(w) : 0ull;
+      sflag[j] = valid;
+    }
+    __syncthreads();
+    // rank of every valid cluster, stored in place of the flag: sflag = rank+1, 0 = invalid
+    for (int j = tid; j < kc; j += 256) {
+      if (!sflag[j]) continue;
+      const uint64_t kj = skey[j];
+      int rank = 0;
+      for (int t = 0; t < kc; ++t) {
+        const uint64_t kt = skey[t];
+        rank += (kt > kj) || (kt == kj && t < j);
+      }
+      sflag[j] = rank + 1;
+    }
+    __syncthreads();
+    // inverse permutation into skey (as ints), then the sequential prefix by one thread
+    int32_t* order = reinterpret_cast<int32_t*>(skey);
+    __syncthreads();
+    int nvalid_local = 0;
+    for (int j = tid; j < kc; j += 256) if (sflag[j]) ++nvalid_local;
+    // (skey is dead after the ranks are known; every thread finished reading it at the barrier)
+    for (int j = tid; j < kc; j += 256) if (sflag[j]) order[sflag[j] - 1] = j;
+    __syncthreads();
+    if (tid == 0) {
+      int nvalid = 0;
+      double total = 0.0;
+      for (int j = 0; j < kc; ++j) { total = total + sval[j]; nvalid += sflag[j] != 0; }
+      const double target = cfg.top_p * total;
+      double cum = 0.0;
+      int take = nvalid;
+      for (int r = 0; r < nvalid; ++r) {
+        cum = cum + sval[order[r]];
+        if (cum >= target) { take = r + 1; break; }
+      }
+      s_take = take;
+    }
+    __syncthreads();
+    const int take = s_take;
+    for (int j = tid; j < kc; j += 256) sflag[j] = sflag[j] != 0 && sflag[j] <= take;
+    (void)nvalid_local;
+  }
+  __syncthreads();
+
+  // ---- ascending compaction of the flagged indices
+  int32_t* out = sel_idx + ((size_t)h * cfg.Cq + i) * cfg.cap;
+  int run = 0;
+  const int lane = tid & 63, wave = tid >> 6;
+  const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  for (int j0 = 0; j0 < kc; j0 += 256) {
+    const int j = j0 + tid;
+    const bool f = j < kc && sflag[j] != 0;
+    const uint64_t bal = __ballot(f);
+    __syncthreads();
+    if (lane == 0) wsum[wave] = __popcll(bal);
+    __syncthreads();
+    int before = 0;
+    for (int w = 0; w < wave; ++w) before += wsum[w];
+    if (f) out[run + before + __popcll(bal & lt_mask)] = j;
+    run += wsum[0] + wsum[1] + wsum[2] + wsum[3];
+  }
+  if (tid == 0) sel_cnt[(size_t)h * cfg.Cq + i] = run;
+}
+
+int launch_select(hipStream_t s, int H, int Cq, int cap, int d, int score_mode, int select_mode, int topk,
+                  float top_p, float scale, const float* q_cent, const float* q_mean_norm, const float* k_cent,
+                  const float* k_bmin, const float* k_bmax, const int32_t* k_sizes, const int32_t* k_count,
+                  const int32_t* full_flag, int32_t* sel_idx, int32_t* sel_cnt) {
+  SelectCfg c{Cq, cap, d, score_mode, select_mode, topk, (double)top_p, (double)scale};
+  const size_t shm = (size_t)cap * 20;
+  if (shm > 150 * 1024) return ADACLUSTER_E_BADSHAPE;
+  hipError_t e = hipFuncSetAttribute((const void*)select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
+  if (e != hipSuccess) return ADACLUSTER_E_INTERNAL;
+  select_kernel<<<dim3(Cq, H), 256, shm, s>>>(c, q_cent, q_mean_norm, k_cent, k_bmin, k_bmax, k_sizes, k_count,
+                                              full_flag, sel_idx, sel_cnt);
+  return hipGetLastError() == hipSuccess ? 0 : ADACLUSTER_E_INTERNAL;
+}
+
+}  // namespace adac

@@ -1,0 +1,152 @@
+// Stable label sort (LSD radix, 7-bit digits) and CSR offsets.
+//
+// The permutation that groups tokens by cluster label is what makes the centroid
+// reduction atomic-free and the K/V gathers cluster-contiguous.  It must be
+// deterministic, so ranks inside a segment are taken in item order (wave-wide
+// match on the digit, never "who won the atomic").  All passes are bound by HBM
+// traffic of 4-byte labels and indices.
+#include "common.h"
+#include "launch.h"
+
+namespace adac {
+
+static constexpr int SEG = 1024;     // items per single-wave block
+static constexpr int RBITS = 7;
+static constexpr int RBINS = 1 << RBITS;
+
+struct SortArgs {
+  const int32_t* n_dev;  int n_stride;  int n_const;
+  const int32_t* active_dev; int active_stride;
+};
+
+__device__ __forceinline__ int head_items(const SortArgs& a, int h) {
+  if (a.active_dev && !a.active_dev[(size_t)h * a.active_stride]) return 0;   // head not active
+  return a.n_dev ? a.n_dev[(size_t)h * a.n_stride] : a.n_const;
+}
+
+// histogram of one digit per segment
+__global__ __launch_bounds__(64) void radix_count(const int32_t* __restrict__ labels, int N, int shift,
+                                                  SortArgs a, int nseg, int32_t* __restrict__ hist) {
+  const int h = blockIdx.y, seg = blockIdx.x, lane = threadIdx.x;
+  const int n = head_items(a, h);
+  __shared__ int32_t cnt[RBINS];
+  cnt[lane] = 0; cnt[lane + 64] = 0;
+  __syncthreads();
+  const int beg = seg * SEG;
+  if (beg < n) {
+    const int end = min(beg + SEG, n);
+    const int32_t* lab = labels + (size_t)h * N;
+    for (int p = beg + lane; p < end; p += 64) atomicAdd(&cnt[(lab[p] >> shift) & (RBINS - 1)], 1);
+  }
+  __syncthreads();
+  int32_t* out = hist + ((size_t)h * nseg + seg) * RBINS;
+  out[lane] = cnt[lane]; out[lane + 64] = cnt[lane + 64];
+}
+
+// exclusive scan: bins major, segments minor -> first output position per (segment, bin)
+__global__ __launch_bounds__(RBINS) void radix_scan(int nseg, int32_t* __restrict__ hist) {
+  const int h = blockIdx.x, b = threadIdx.x;
+  int32_t* hh = hist + (size_t)h * nseg * RBINS;
+  int run = 0;
+  for (int s = 0; s < nseg; ++s) { int c = hh[s * RBINS + b]; hh[s * RBINS + b] = run; run += c; }
+  __shared__ int32_t tot[RBINS];
+  tot[b] = run;
+  __syncthreads();
+  int base = 0;
+  for (int i = 0; i < b; ++i) base += tot[i];
+  for (int s = 0; s < nseg; ++s) hh[s * RBINS + b] += base;
+}
+
+// scatter one pass: (label, value) pairs move to their stable sorted position
+__global__ __launch_bounds__(64) void radix_scatter(const int32_t* __restrict__ labels_in,
+                                                    const int32_t* __restrict__ vals_in, int N, int shift,
+                                                    SortArgs a, int nseg, const int32_t* __restrict__ hist,
+                                                    int32_t* __restrict__ labels_out,
+                                                    int32_t* __restrict__ vals_out) {
+  const int h = blockIdx.y, seg = blockIdx.x, lane = threadIdx.x;
+  const int n = head_items(a, h);
+  const int beg = seg * SEG;
+  if (beg >= n) return;
+  const int end = min(beg + SEG, n);
+  __shared__ int32_t base[RBINS];
+  const int32_t* hb = hist + ((size_t)h * nseg + seg) * RBINS;
+  base[lane] = hb[lane]; base[lane + 64] = hb[lane + 64];
+  __syncthreads();
+  const int32_t* lab = labels_in + (size_t)h * N;
+  const int32_t* val = vals_in ? vals_in + (size_t)h * N : nullptr;
+  int32_t* lo = labels_out + (size_t)h * N;
+  int32_t* vo = vals_out + (size_t)h * N;
+  const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  for (int p0 = beg; p0 < end; p0 += 64) {
+    const int p = p0 + lane;
+    const bool valid = p < end;
+    const int l = valid ? lab[p] : 0;
+    const int v = valid ? (val ? val[p] : p) : 0;
+    const int dig = (l >> shift) & (RBINS - 1);
+    uint64_t remaining = __ballot(valid);
+    int rank = 0, cnt = 0; bool leader = false;
+    while (remaining) {
+      const int lead = __ffsll((unsigned long long)remaining) - 1;
+      const int dl = __shfl(dig, lead);
+      const uint64_t same = __ballot(valid && dig == dl);
+      if (valid && dig == dl) {
+        rank = __popcll(same & lt_mask);
+        cnt = __popcll(same);
+        leader = (lane == lead);
+      }
+      remaining &= ~same;
+    }
+    int pos = 0;
+    if (valid) pos = base[dig] + rank;
+    __syncthreads();
+    if (valid && leader) base[dig] += cnt;
+    __syncthreads();
+    if (valid) { lo[pos] = l; vo[pos] = v; }
+  }
+}
+
+// offs[j] = number of sorted labels < j (j = 0..m), by binary search in the sorted labels
+__global__ void label_offsets(const int32_t* __restrict__ sorted, int N, SortArgs a,
+                              const int32_t* __restrict__ m_dev, int m_stride, int m_const,
+                              int32_t* __restrict__ offs, int offs_stride) {
+  const int h = blockIdx.y;
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (a.active_dev && !a.active_dev[(size_t)h * a.active_stride]) return;
+  const int m = m_dev ? m_dev[(size_t)h * m_stride] : m_const;
+  if (j > m) return;
+  const int n = head_items(a, h);
+  const int32_t* s = sorted + (size_t)h * N;
+  int lo = 0, hi = n;
+  while (lo < hi) { int mid = (lo + hi) >> 1; if (s[mid] < j) lo = mid + 1; else hi = mid; }
+  offs[(size_t)h * offs_stride + j] = lo;
+}
+
+int launch_sort(hipStream_t st, int H, int N, int n_bound, int m_bound,
+                const int32_t* labels, const int32_t* ulist,
+                const int32_t* n_dev, int n_stride, const int32_t* m_dev, int m_stride,
+                const int32_t* active_dev, int active_stride,
+                int32_t* perm, int32_t* offs, int offs_stride, const SortScratch& sc) {
+  SortArgs a{n_dev, n_stride, n_bound, active_dev, active_stride};
+  const int nseg = (n_bound + SEG - 1) / SEG;
+  int bits = 1;
+  while ((1 << bits) < m_bound) ++bits;
+  const int passes = (bits + RBITS - 1) / RBITS;
+  dim3 g(nseg, H);
+  const int32_t* lin = labels;
+  const int32_t* vin = ulist;
+  for (int ps = 0; ps < passes; ++ps) {
+    const bool last = (ps == passes - 1);
+    // ping-pong: the last pass writes sorted labels to lab_b and values to perm
+    int32_t* lout = last ? sc.lab_b : sc.lab_a;
+    int32_t* vout = last ? perm : sc.val_a;
+    radix_count<<<g, 64, 0, st>>>(lin, N, ps * RBITS, a, nseg, sc.hist);
+    radix_scan<<<H, RBINS, 0, st>>>(nseg, sc.hist);
+    radix_scatter<<<g, 64, 0, st>>>(lin, vin, N, ps * RBITS, a, nseg, sc.hist, lout, vout);
+    lin = lout; vin = vout;
+  }
+  dim3 go((m_bound + 1 + 255) / 256, H);
+  label_offsets<<<go, 256, 0, st>>>(sc.lab_b, N, a, m_dev, m_stride, m_bound, offs, offs_stride);
+  return hipGetLastError() == hipSuccess ? 0 : ADACLUSTER_E_INTERNAL;
+}
+
+}  // namespace adac

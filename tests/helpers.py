@@ -1,0 +1,74 @@
+"""Shared helpers of the GPU parity tests (marshalling and near-tie accounting only)."""
+import numpy as np
+import torch
+
+from paper_2604_18348_amd import binding as B
+
+
+def to_dev(a, dtype):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype == B.BF16:
+        t = t.to(torch.bfloat16)
+    return t.cuda().contiguous()
+
+
+def to_np(t):
+    return t.detach().float().cpu().numpy().astype(np.float64) if t.is_floating_point() else t.detach().cpu().numpy()
+
+
+def sel_to_dev(sel_lists_per_head, Cq, cap):
+    H = len(sel_lists_per_head)
+    idx = np.zeros((H, Cq, cap), dtype=np.int32)
+    cnt = np.zeros((H, Cq), dtype=np.int32)
+    for h, lists in enumerate(sel_lists_per_head):
+        for i, s in enumerate(lists):
+            idx[h, i, :len(s)] = s
+            cnt[h, i] = len(s)
+    return torch.from_numpy(idx).cuda(), torch.from_numpy(cnt).cuda()
+
+
+def sel_from_dev(sel_idx, sel_cnt):
+    idx, cnt = sel_idx.cpu().numpy(), sel_cnt.cpu().numpy()
+    return [[idx[h, i, :cnt[h, i]].astype(np.int64) for i in range(idx.shape[1])] for h in range(idx.shape[0])]
+
+
+def attn_errors(got, ref):
+    diff = got - ref
+    rel_l2 = float(np.linalg.norm(diff) / max(np.linalg.norm(ref), 1e-30))
+    return rel_l2, float(np.max(np.abs(diff)))
+
+
+REL_TIE = 1e-5
+
+
+def euclid_label_mismatches(X, C, labels_gpu):
+    """labels must be the arg-min of ||x-c||^2 over C.  Returns (#mismatches, #mismatches that are
+    NOT near-ties).  A near-tie: the GPU's choice is within REL_TIE * (||x||^2 + ||c||^2) of the best."""
+    X = np.asarray(X, np.float64)
+    C = np.asarray(C, np.float64)
+    cn = (C * C).sum(1)
+    xn = (X * X).sum(1)
+    G = cn[None, :] - 2.0 * (X @ C.T)
+    ref = G.argmin(1)
+    bad = np.flatnonzero(ref != labels_gpu)
+    if bad.size == 0:
+        return 0, 0
+    gap = G[bad, labels_gpu[bad]] - G[bad, ref[bad]]
+    scale = xn[bad] + cn[labels_gpu[bad]]
+    hard = int((gap > REL_TIE * scale).sum())
+    return int(bad.size), hard
+
+
+def cosine_label_mismatches(Q, C, labels_gpu):
+    """labels must be the arg-max of q^.c over unit centres C; near-tie margin REL_TIE (cosines)."""
+    Q = np.asarray(Q, np.float64)
+    n = np.sqrt((Q * Q).sum(1))
+    Xn = Q / np.maximum(n, 1e-12)[:, None]
+    S = Xn @ np.asarray(C, np.float64).T
+    ref = S.argmax(1)
+    bad = np.flatnonzero(ref != labels_gpu)
+    if bad.size == 0:
+        return 0, 0
+    gap = S[bad, ref[bad]] - S[bad, labels_gpu[bad]]
+    hard = int((gap > REL_TIE).sum())
+    return int(bad.size), hard
