@@ -93,7 +93,7 @@ def load_library():
     lib.adacluster_workspace_bytes.argtypes = [P, ctypes.POINTER(sz)]
     lib.adacluster_last_error.argtypes = [ctypes.c_char_p, sz]
     lib.adacluster_qcluster.argtypes = [P] + [vp] * 6 + [vp, sz, vp]
-    lib.adacluster_kcluster.argtypes = [P] + [vp] * 13 + [vp, sz, vp]
+    lib.adacluster_kcluster.argtypes = [P] + [vp] * 12 + [vp, sz, vp]
     lib.adacluster_select.argtypes = [P] + [vp] * 10 + [vp, sz, vp]
     lib.adacluster_sparse_attn.argtypes = [P] + [vp] * 9 + [vp, sz, vp]
     lib.adacluster_attn.argtypes = [P] + [vp] * 4 + [ctypes.POINTER(COutputs), vp, sz, vp]

@@ -1,0 +1,205 @@
+"""Chained GPU parity of the clustering entry points against the oracle.
+
+k-means trajectories are chaotic, so each GPU intermediate is handed to the oracle and the next
+step is checked from there: labels must be the arg-min / arg-max to the centres the GPU reports
+(exact except near-ties below 1e-5 relative margin), centroids must be the (normalised) member
+means of the GPU labels, and Algorithm 1's structure (stage counts, threshold filter, flag F)
+must hold for the GPU's own unassigned sets."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import adacluster_oracle as orc
+from paper_2604_18348_amd import binding as B
+from paper_2604_18348_amd import workloads as wl
+from tests.helpers import cosine_label_mismatches, euclid_label_mismatches, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def dt_name(dtype):
+    return "bf16" if dtype == B.BF16 else "f32"
+
+
+@pytest.mark.parametrize("dtype,d,N,Cq", [(B.BF16, 64, 3000, 17), (B.BF16, 128, 2511, 65), (B.F32, 64, 1500, 9),
+                                          (B.F32, 128, 700, 5), (B.BF16, 64, 70, 65)])
+def test_qcluster_chained(dtype, d, N, Cq):
+    H = 2
+    Q, _, _ = wl.make_small(11, N, d, 10, dtype=dt_name(dtype), H=H)
+    Q[1, 5] = 0.0                                     # a zero query goes to cluster 0
+    p = B.Params(H=H, N=N, d=d, dtype=dtype, q_clusters=Cq, q_iters=3, k_m0=4, k_m_min=1, k_max_clusters=8)
+    out = B.adacluster_qcluster(p, to_dev(Q, dtype))
+    torch.cuda.synchronize()
+    lab = out["q_labels"].cpu().numpy()
+    ca = to_np(out["q_assign_centroids"])
+    cen = to_np(out["q_centroids"])
+    sizes = out["q_sizes"].cpu().numpy()
+    mn = to_np(out["q_mean_norm"])
+    assert lab[1, 5] == 0
+    for h in range(H):
+        assert lab[h].min() >= 0 and lab[h].max() < Cq
+        if dtype == B.BF16:
+            assert np.array_equal(ca[h], orc.round_to_bf16(ca[h]))
+        total, hard = cosine_label_mismatches(Q[h], ca[h], lab[h])
+        print("qcluster", dt_name(dtype), d, N, "mismatches", total, "hard", hard)
+        assert hard == 0 and total <= max(2, N // 500)
+        assert np.array_equal(sizes[h], np.bincount(lab[h], minlength=Cq))
+        Xn = orc.normalize_rows(Q[h])
+        qn = np.linalg.norm(Q[h].astype(np.float64), axis=1)
+        for j in range(Cq):
+            if sizes[h, j] == 0:
+                assert mn[h, j] == 0
+                continue
+            s = Xn[lab[h] == j].sum(0)
+            if np.linalg.norm(s) < 1e-12:                 # degenerate sum: the previous centre is kept
+                continue
+            assert np.allclose(cen[h, j], s / np.linalg.norm(s), atol=2e-6, rtol=1e-5)
+            assert math.isclose(mn[h, j], qn[lab[h] == j].mean(), rel_tol=1e-5)
+
+
+def test_qcluster_free_running_fp32_matches_oracle_trajectory():
+    H, N, d, Cq = 1, 2000, 64, 12
+    Q, _, _ = wl.make_small(12, N, d, 12, dtype="f32", H=H)
+    p = B.Params(H=H, N=N, d=d, dtype=B.F32, q_clusters=Cq, q_iters=3, k_m0=4, k_m_min=1, k_max_clusters=8)
+    out = B.adacluster_qcluster(p, to_dev(Q, B.F32))
+    ref = orc.query_kmeans(Q[0], Cq, 3)
+    lab = out["q_labels"].cpu().numpy()[0]
+    agree = float((lab == ref["labels"]).mean())
+    print("free-running q labels agree", agree)
+    assert agree > 0.999
+    if agree == 1.0:
+        assert np.allclose(to_np(out["q_centroids"])[0], ref["centroids"], atol=1e-5)
+    # warm start from given centres reproduces the same thing as the oracle's init_centroids
+    init = ref["centroids"].astype(np.float32)[None]
+    p2 = B.Params(H=H, N=N, d=d, dtype=B.F32, q_clusters=Cq, q_iters=1, q_init_mode=1, k_m0=4, k_m_min=1,
+                  k_max_clusters=8)
+    out2 = B.adacluster_qcluster(p2, to_dev(Q, B.F32), q_centroids_init=torch.from_numpy(init).cuda())
+    ref2 = orc.query_kmeans(Q[0], Cq, 1, init_centroids=init[0])
+    assert float((out2["q_labels"].cpu().numpy()[0] == ref2["labels"]).mean()) > 0.999
+
+
+def check_kcluster(K, p, out, dtype):
+    H, N, d = K.shape
+    lab = out["k_labels"].cpu().numpy()
+    ca = to_np(out["k_assign_centroids"])
+    cen = to_np(out["k_centroids"])
+    bmin, bmax = to_np(out["k_box_min"]), to_np(out["k_box_max"])
+    sizes = out["k_sizes"].cpu().numpy()
+    kc = out["k_count"].cpu().numpy()
+    full = out["full_flag"].cpu().numpy()
+    offs = out["k_stage_offs"].cpu().numpy()
+    stage_of = out["k_stage_of"].cpu().numpy()
+    tau = float(out["tau_used"].cpu().numpy()[0])
+    u_min = orc.min_unassigned_count(p.min_unassigned_frac, N)
+    for h in range(H):
+        Kh = K[h].astype(np.float64)
+        C = ca[h, :kc[h]]
+        if dtype == B.BF16:
+            assert np.array_equal(C, orc.round_to_bf16(C))
+        n_stage = int(np.searchsorted(offs[h], kc[h]))            # first index where offs == k_count
+        assert offs[h, 0] == 0 and offs[h, n_stage] == kc[h] and np.all(offs[h, n_stage:] == kc[h])
+        in_U = np.ones(N, dtype=bool)
+        near = 0
+        for t in range(n_stage):
+            m_t = offs[h, t + 1] - offs[h, t]
+            assert m_t == orc.stage_cluster_count(in_U.sum(), N, p.k_m0, p.k_m_min), (h, t)
+            Ct = C[offs[h, t]:offs[h, t + 1]]
+            idx = np.flatnonzero(in_U)
+            X = Kh[idx]
+            G = (Ct * Ct).sum(1)[None] - 2 * X @ Ct.T
+            d2 = np.maximum(G.min(1) + (X * X).sum(1), 0)
+            removed_ref = d2 < tau * tau
+            removed_gpu = stage_of[h, idx] == t
+            diff = np.flatnonzero(removed_ref != removed_gpu)
+            # a differing decision must sit on the threshold (fp32 evaluation of ||x||^2-2x.c+||c||^2)
+            scale = (X[diff] * X[diff]).sum(1) + (Ct * Ct).sum(1).max()
+            assert np.all(np.abs(d2[diff] - tau * tau) <= 1e-5 * scale), (h, t, diff.size)
+            near += diff.size
+            assert np.all((stage_of[h, idx] == t) | (stage_of[h, idx] > t) | (stage_of[h, idx] == -1))
+            in_U[idx[removed_gpu]] = False
+        u_left = int(in_U.sum())
+        assert np.all(stage_of[h][in_U] == -1)
+        if full[h]:
+            assert u_left > 0 and kc[h] >= p.k_max_clusters
+        else:
+            assert u_left == 0 or n_stage >= p.k_max_stages or u_left <= u_min
+            if u_left > 0:
+                assert kc[h] < p.k_max_clusters
+        total, hard = euclid_label_mismatches(Kh, C, lab[h])
+        print("kcluster head", h, "stages", n_stage, "k_count", kc[h], "full", full[h], "left", u_left,
+              "label mismatches", total, "hard", hard, "threshold near-ties", near)
+        assert hard == 0 and total <= max(2, N // 500)
+        assert np.array_equal(sizes[h, :kc[h]], np.bincount(lab[h], minlength=kc[h]))
+        assert np.all(sizes[h, kc[h]:] == 0)
+        cref, sref, mnref, mxref = orc.finalize_key_clusters(Kh, lab[h], C)
+        assert np.allclose(cen[h, :kc[h]], cref, atol=2e-5, rtol=1e-5)
+        assert np.array_equal(bmin[h, :kc[h]], mnref) and np.array_equal(bmax[h, :kc[h]], mxref)
+    return tau
+
+
+@pytest.mark.parametrize("dtype,d,N,M", [(B.BF16, 64, 4000, 16), (B.BF16, 128, 2600, 16), (B.F32, 64, 1800, 12)])
+def test_kcluster_chained(dtype, d, N, M):
+    H = 3
+    _, K, _ = wl.make_small(21, N, d, M, dtype=dt_name(dtype), H=H)
+    rng = np.random.default_rng(3)
+    K[2] = wl.round_bf16_f32(rng.standard_normal((N, d)).astype(np.float32))       # a diffuse head
+    out_mask = rng.random(N) < 0.02
+    K[0][out_mask] = wl.round_bf16_f32(rng.standard_normal((int(out_mask.sum()), d)).astype(np.float32))
+    p = B.Params(H=H, N=N, d=d, dtype=dtype, q_clusters=8, k_iters=3, k_m0=24, k_m_min=4, k_max_clusters=96,
+                 tau_factor=1.5, min_unassigned_frac=0.03)
+    out = B.adacluster_kcluster(p, to_dev(K, dtype))
+    torch.cuda.synchronize()
+    tau = check_kcluster(K, p, out, dtype)
+    full = out["full_flag"].cpu().numpy()
+    kc = out["k_count"].cpu().numpy()
+    assert full[2] == 1 and full[1] == 0                         # isotropic head cannot be compressed
+    assert kc[2] > kc[1]
+    # tau = 1.5 x mean stage-0 distance over all heads (oracle, with the I/O-dtype centre rounding)
+    rf = orc.round_to_bf16 if dtype == B.BF16 else None
+    tau_ref = orc.tau_from_factor([K[h] for h in range(H)], 1.5, p.k_m0, p.k_iters, round_fn=rf)
+    print("tau gpu", tau, "oracle", tau_ref)
+    assert math.isclose(tau, tau_ref, rel_tol=2e-3)
+
+
+def test_kcluster_absolute_tau_and_limits():
+    H, N, d = 2, 1500, 64
+    _, K, _ = wl.make_small(22, N, d, 16, dtype="bf16", H=H)
+    # tau so large that one stage absorbs everything = plain k-means with k_m0 centres
+    p = B.Params(H=H, N=N, d=d, dtype=B.BF16, q_clusters=4, k_iters=2, k_m0=16, k_m_min=4, k_max_clusters=64,
+                 tau_abs=1e4)
+    out = B.adacluster_kcluster(p, to_dev(K, B.BF16))
+    assert out["k_count"].cpu().tolist() == [16, 16] and out["full_flag"].cpu().tolist() == [0, 0]
+    assert abs(float(out["tau_used"].cpu()[0]) - 1e4) < 1
+    assert int(out["k_stage_of"].max()) == 0
+    check_kcluster(K, p, out, B.BF16)
+    # tiny tau: nothing is ever removed, the cap is hit, F is set; |C| overshoots by < one stage
+    p = B.Params(H=H, N=N, d=d, dtype=B.BF16, q_clusters=4, k_iters=2, k_m0=16, k_m_min=4, k_max_clusters=40,
+                 tau_abs=1e-6)
+    out = B.adacluster_kcluster(p, to_dev(K, B.BF16))
+    assert out["k_count"].cpu().tolist() == [48, 48] and out["full_flag"].cpu().tolist() == [1, 1]
+    assert int(out["k_stage_of"].max()) == -1
+    check_kcluster(K, p, out, B.BF16)
+    # stage limit without the flag
+    p = B.Params(H=H, N=N, d=d, dtype=B.BF16, q_clusters=4, k_iters=1, k_m0=16, k_m_min=4, k_max_clusters=4096,
+                 k_max_stages=2, tau_abs=1e-6)
+    out = B.adacluster_kcluster(p, to_dev(K, B.BF16))
+    assert out["k_count"].cpu().tolist() == [32, 32] and out["full_flag"].cpu().tolist() == [0, 0]
+    check_kcluster(K, p, out, B.BF16)
+
+
+def test_kcluster_fp32_stage_centres_follow_the_oracle_trajectory():
+    H, N, d = 1, 1600, 64
+    _, K, _ = wl.make_small(23, N, d, 14, dtype="f32", H=H)
+    p = B.Params(H=H, N=N, d=d, dtype=B.F32, q_clusters=4, k_iters=3, k_m0=14, k_m_min=4, k_max_clusters=64,
+                 tau_abs=3.0)
+    out = B.adacluster_kcluster(p, to_dev(K, B.F32))
+    ref = orc.multistage_kmeans(K[0], 3.0, 64, 14, 4, 3)
+    kc = int(out["k_count"][0])
+    print("k_count", kc, "oracle", ref["assign_centroids"].shape[0])
+    assert kc == ref["assign_centroids"].shape[0]
+    assert np.array_equal(out["k_stage_offs"].cpu().numpy()[0][:len(ref["stage_offs"])], ref["stage_offs"])
+    assert np.allclose(to_np(out["k_assign_centroids"])[0, :kc], ref["assign_centroids"], atol=1e-4)
+    assert float((out["k_labels"].cpu().numpy()[0] == ref["labels"]).mean()) > 0.999
+    assert bool(out["full_flag"][0]) == ref["full_flag"]
