@@ -187,6 +187,17 @@ int adacluster_dense_attn(const adacluster_params* p,
                           const void* Q, const void* K, const void* V, void* O,
                           void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * Stage timing for benchmarks.  adacluster_profile_enable(1) creates HIP events; while enabled,
+ * adacluster_attn, adacluster_sparse_attn and adacluster_dense_attn record them on the call's
+ * stream at their stage boundaries.  adacluster_profile_read waits for the last recorded call
+ * and writes, to the HOST array ms[6], the milliseconds of: query clustering, Algorithm 1,
+ * selection (stand-alone sparse_attn: the two label sorts), K/V permutation, planning, and the
+ * attention kernel; -1 for a stage the call did not run.  Not thread-safe.
+ */
+int adacluster_profile_enable(int on);
+int adacluster_profile_read(float* ms);
+
 #ifdef __cplusplus
 }
 #endif

@@ -98,7 +98,9 @@ def load_library():
     lib.adacluster_sparse_attn.argtypes = [P] + [vp] * 9 + [vp, sz, vp]
     lib.adacluster_attn.argtypes = [P] + [vp] * 4 + [ctypes.POINTER(COutputs), vp, sz, vp]
     lib.adacluster_dense_attn.argtypes = [P] + [vp] * 4 + [vp, sz, vp]
-    for n in ("centroid_capacity", "workspace_bytes", "last_error", "qcluster", "kcluster", "select",
+    lib.adacluster_profile_enable.argtypes = [ctypes.c_int]
+    lib.adacluster_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float)]
+    for n in ("profile_enable", "profile_read", "centroid_capacity", "workspace_bytes", "last_error", "qcluster", "kcluster", "select",
               "sparse_attn", "attn", "dense_attn"):
         getattr(lib, "adacluster_" + n).restype = ctypes.c_int
     _lib = lib
@@ -107,7 +109,21 @@ def load_library():
 
 EXPORTED = ["adacluster_centroid_capacity", "adacluster_workspace_bytes", "adacluster_last_error",
             "adacluster_qcluster", "adacluster_kcluster", "adacluster_select",
-            "adacluster_sparse_attn", "adacluster_attn", "adacluster_dense_attn"]
+            "adacluster_sparse_attn", "adacluster_attn", "adacluster_dense_attn",
+            "adacluster_profile_enable", "adacluster_profile_read"]
+
+STAGES = ["qcluster", "kcluster", "select", "permute", "plan", "attention"]
+
+
+def adacluster_profile_enable(on: bool):
+    _check(load_library().adacluster_profile_enable(1 if on else 0), "profile_enable")
+
+
+def adacluster_profile_read():
+    """Stage times (ms) of the last profiled call as a dict; stages that did not run are absent."""
+    arr = (ctypes.c_float * 6)()
+    _check(load_library().adacluster_profile_read(arr), "profile_read")
+    return {n: float(arr[i]) for i, n in enumerate(STAGES) if arr[i] >= 0}
 
 
 class AdaClusterError(RuntimeError):

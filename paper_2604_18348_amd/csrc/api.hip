@@ -14,6 +14,26 @@ namespace {
 
 thread_local char g_err[256] = "";
 
+// Optional stage timing: hipEvents recorded at the stage boundaries of a call.
+enum { EV_START = 0, EV_QCLUSTER, EV_KCLUSTER, EV_SELECT, EV_PERMUTE, EV_PLAN, EV_ATTN, EV_COUNT };
+struct Profiler {
+  bool enabled = false;
+  bool recorded[EV_COUNT] = {};
+  hipEvent_t ev[EV_COUNT] = {};
+} g_prof;
+
+void prof_begin(hipStream_t st) {
+  if (!g_prof.enabled) return;
+  for (int i = 0; i < EV_COUNT; ++i) g_prof.recorded[i] = false;
+  (void)hipEventRecord(g_prof.ev[EV_START], st);
+  g_prof.recorded[EV_START] = true;
+}
+void prof_mark(int which, hipStream_t st) {
+  if (!g_prof.enabled) return;
+  (void)hipEventRecord(g_prof.ev[which], st);
+  g_prof.recorded[which] = true;
+}
+
 int fail(int code, const char* fmt, ...) {
   va_list ap;
   va_start(ap, fmt);
@@ -261,10 +281,13 @@ int run_attention(const adacluster_params* p, const WS& w, hipStream_t st, const
   const Dims D = dims_of(p);
   const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)D.d);
   RET_IF(launch_permute_kv(st, D.H, D.N, D.d * (int)esize(p), K, V, w.perm_k, w.Kp, w.Vp));
+  prof_mark(EV_PERMUTE, st);
   RET_IF(launch_plan_sparse(st, D.H, D.Cq, D.cap, D.maxr, D.maxtiles, D.BM, w.offs_q, D.Cq + 1, w.offs_k, D.cap + 1,
                             k_count, sel_idx, sel_cnt, w.rng_start, w.rng_pre, w.rng_cnt, w.tiles, w.ntiles));
+  prof_mark(EV_PLAN, st);
   RET_IF(launch_attention(st, p->dtype, D.d, D.H, D.N, D.Cq, D.maxtiles, D.maxr, scale, Q, w.Kp, w.Vp, O, w.perm_q,
                           w.tiles, w.ntiles, w.rng_start, w.rng_pre, w.rng_cnt));
+  prof_mark(EV_ATTN, st);
   return 0;
 }
 
@@ -353,10 +376,12 @@ int adacluster_sparse_attn(const adacluster_params* p, const void* Q, const void
   if ((rc = check_ws(p, ws, ws_bytes, &w))) return rc;
   const Dims D = dims_of(p);
   hipStream_t st = (hipStream_t)stream;
+  prof_begin(st);
   RET_IF(launch_sort(st, D.H, D.N, D.N, D.Cq, q_labels, nullptr, nullptr, 0, nullptr, 0, nullptr, 0, w.perm_q, w.offs_q,
                      D.Cq + 1, w.sort));
   RET_IF(launch_sort(st, D.H, D.N, D.N, D.cap, k_labels, nullptr, nullptr, 0, k_count, 1, nullptr, 0, w.perm_k, w.offs_k,
                      D.cap + 1, w.sort));
+  prof_mark(EV_SELECT, st);   // (time of the two label sorts when called stand-alone)
   return run_attention(p, w, st, Q, K, V, O, k_count, sel_idx, sel_cnt);
 }
 
@@ -386,14 +411,18 @@ int adacluster_attn(const adacluster_params* p, const void* Q, const void* K, co
   hipStream_t st = (hipStream_t)stream;
   if (p->q_init_mode == 1 && !o.q_centroids)
     return fail(ADACLUSTER_E_BADARG, "attn: q_init_mode 1 needs outs->q_centroids");
+  prof_begin(st);
   if ((rc = run_qcluster(p, w, st, Q, q_labels, q_centroids, q_assign_centroids, q_sizes, q_mean_norm))) return rc;
+  prof_mark(EV_QCLUSTER, st);
   if ((rc = run_kcluster(p, w, st, K, k_labels, k_centroids, k_assign_centroids, k_bmin, k_bmax, k_sizes, k_count,
                          full_flag, o.k_stage_offs, o.k_stage_of, tau_used)))
     return rc;
+  prof_mark(EV_KCLUSTER, st);
   const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->d);
   RET_IF(launch_select(st, p->H, p->q_clusters, capacity(p), p->d, p->score_mode, p->select_mode, p->topk, p->top_p,
                        scale, q_centroids, q_mean_norm, k_centroids, k_bmin, k_bmax, k_sizes, k_count, full_flag,
                        sel_idx, sel_cnt));
+  prof_mark(EV_SELECT, st);
   // both label sorts were left in the workspace by the clustering steps
   return run_attention(p, w, st, Q, K, V, O, k_count, sel_idx, sel_cnt);
 }
@@ -408,9 +437,43 @@ int adacluster_dense_attn(const adacluster_params* p, const void* Q, const void*
   const Dims D = dims_of(p);
   hipStream_t st = (hipStream_t)stream;
   const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)D.d);
+  prof_begin(st);
   RET_IF(launch_plan_dense(st, D.H, D.N, D.maxtiles, D.BM, w.rng_start, w.rng_pre, w.rng_cnt, w.tiles, w.ntiles));
+  prof_mark(EV_PLAN, st);
   RET_IF(launch_attention(st, p->dtype, D.d, D.H, D.N, 1, D.maxtiles, 1, scale, Q, K, V, O, nullptr, w.tiles,
                           w.ntiles, w.rng_start, w.rng_pre, w.rng_cnt));
+  prof_mark(EV_ATTN, st);
+  return 0;
+}
+
+int adacluster_profile_enable(int on) {
+  if (on && !g_prof.enabled) {
+    for (int i = 0; i < EV_COUNT; ++i)
+      if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) return fail(ADACLUSTER_E_INTERNAL, "hipEventCreate failed");
+    g_prof.enabled = true;
+  } else if (!on && g_prof.enabled) {
+    for (int i = 0; i < EV_COUNT; ++i) (void)hipEventDestroy(g_prof.ev[i]);
+    g_prof.enabled = false;
+  }
+  return 0;
+}
+
+int adacluster_profile_read(float* ms) {
+  if (!ms) return fail(ADACLUSTER_E_BADARG, "ms is NULL");
+  if (!g_prof.enabled) return fail(ADACLUSTER_E_UNSUPPORTED, "profiling is not enabled");
+  int prev = -1;
+  for (int i = 0; i < EV_COUNT; ++i) {
+    if (i > 0) ms[i - 1] = -1.f;
+    if (!g_prof.recorded[i]) continue;
+    if (hipEventSynchronize(g_prof.ev[i]) != hipSuccess) return fail(ADACLUSTER_E_INTERNAL, "event sync failed");
+    if (prev >= 0 && i > 0) {
+      float t = 0.f;
+      if (hipEventElapsedTime(&t, g_prof.ev[prev], g_prof.ev[i]) != hipSuccess)
+        return fail(ADACLUSTER_E_INTERNAL, "event elapsed failed");
+      ms[i - 1] = t;
+    }
+    prev = i;
+  }
   return 0;
 }
 
