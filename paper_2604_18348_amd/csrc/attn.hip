@@ -11,6 +11,8 @@
 #include "common.h"
 #include "launch.h"
 
+#include <type_traits>
+
 namespace adac {
 
 // ------------------------------------------------------------------------------------------
@@ -142,17 +144,39 @@ struct RangeCursor {
 // ------------------------------------------------------------------------------------------
 // bf16 MFMA kernel
 // ------------------------------------------------------------------------------------------
-template <int D, int QB>
-__global__ __launch_bounds__(256) void attn_mfma(AttnArgs a) {
-  constexpr int BN = 64;
-  constexpr int BM = 128 * QB;
-  constexpr int KLD = D + 8;         // K tile row stride (bf16)
-  constexpr int VLD = BN + 8;        // transposed V tile row stride (bf16)
-  constexpr int KS = D / 16;         // contraction steps of S
-  constexpr int DB = D / 32;         // 32-row blocks of O^T
-  constexpr int KCH = D / 8;         // 16-byte chunks per K row
-  constexpr int KPT = BN * KCH / 256;            // K chunks per thread per tile
-  constexpr int VIT = (BN / 8) * (D / 2) / 256;  // V (8-key group, column pair) items per thread
+// One block = NW waves, each owning QB blocks of 32 queries; all waves share the 64-key K and V
+// tiles.  LDS is double buffered (one barrier per tile); global loads run two tiles ahead.
+template <int D, int QB, int NW>
+struct AttnTile {
+  static constexpr int BN = 64;
+  static constexpr int NT = NW * 64;
+  static constexpr int BM = NW * 32 * QB;
+  static constexpr int LD = D + 8;          // K tile row stride (bf16): conflict-free 16-byte reads
+#ifndef A_VPAD
+#define A_VPAD 16
+#endif
+  static constexpr int VLD = D + A_VPAD;    // V tile row stride: conflict-free transpose reads
+  static constexpr int KS = D / 16;         // contraction steps of S
+  static constexpr int DB = D / 32;         // 32-row blocks of O^T
+  static constexpr int CH = D / 8;          // 16-byte chunks per row
+  static constexpr int ITEMS = BN * CH;
+  static constexpr int PT = (ITEMS + NT - 1) / NT;
+};
+
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4_t;
+typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
+
+// LDS transpose read (16-bit elements): inside each group of 16 lanes, lane r supplies the address
+// of 4 consecutive elements and lane i receives element i%4 of the rows addressed by lanes
+// i/4, i/4+4, i/4+8, i/4+12.
+__device__ __forceinline__ s16x4_t lds_read_tr16(const bf16raw* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)p);
+}
+
+template <int D, int QB, int NW, int MINB>
+__global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
+  using TT = AttnTile<D, QB, NW>;
+  constexpr int BN = TT::BN, NT = TT::NT, LD = TT::LD, VLD = TT::VLD, KS = TT::KS, DB = TT::DB, CH = TT::CH, PT = TT::PT;
 
   const int h = blockIdx.y;
   const int tile = blockIdx.x;
@@ -169,14 +193,14 @@ __global__ __launch_bounds__(256) void attn_mfma(AttnArgs a) {
   const int T = (total + BN - 1) / BN;
 
   const bf16raw* Qh = (const bf16raw*)a.Q + (size_t)h * a.N * D;
-  const bf16raw* Kh = (const bf16raw*)a.Kp + (size_t)h * a.N * D;
-  const bf16raw* Vh = (const bf16raw*)a.Vp + (size_t)h * a.N * D;
+  const char* Kh = (const char*)a.Kp + (size_t)h * a.N * D * 2;
+  const char* Vh = (const char*)a.Vp + (size_t)h * a.N * D * 2;
   bf16raw* Oh = (bf16raw*)a.O + (size_t)h * a.N * D;
   const int32_t* pq = a.perm_q ? a.perm_q + (size_t)h * a.N : nullptr;
 
-  __shared__ __attribute__((aligned(16))) bf16raw Ks[BN * KLD];
-  __shared__ __attribute__((aligned(16))) bf16raw Vt[D * VLD];
-  __shared__ int32_t ridx[2][BN];
+  __shared__ __attribute__((aligned(16))) bf16raw Ks[2][BN * LD];
+  __shared__ __attribute__((aligned(16))) bf16raw Vs[2][BN * VLD];
+  __shared__ int32_t ridx[4][BN];          // byte offset of each key row of a tile (-1: no key)
 
   // query tokens of this lane and the B operand of S
   int qtok[QB];
@@ -206,157 +230,163 @@ __global__ __launch_bounds__(256) void attn_mfma(AttnArgs a) {
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) { mrun[qb] = -INFINITY; lrun[qb] = 0.f; }
 
-  RangeCursor cur;
-  if (tid < BN) {
-    cur.init(rs, rp, nr);
-    ridx[0][tid] = (T > 0) ? cur.row(tid) : -1;
-  }
-  __syncthreads();
-
-  uint4 kreg[KPT];
-  uint32_t vreg[VIT][8];
-  auto issue_loads = [&](int buf) {
+  // K and V rows travel as 16-byte chunks: thread -> (row, chunk) fixed for the whole kernel
+  uint4 kreg[PT], vreg[PT];
+  auto issue_loads = [&](int rb) {
 #pragma unroll
-    for (int i = 0; i < KPT; ++i) {
-      const int item = tid + i * 256;
-      const int r = item / KCH, q = item % KCH;
-      const int row = ridx[buf][r];
-      uint4 v = {0, 0, 0, 0};
-      if (row >= 0) v = *reinterpret_cast<const uint4*>(Kh + (size_t)row * D + q * 8);
-      kreg[i] = v;
+    for (int i = 0; i < PT; ++i) {
+      const int item = tid + i * NT;
+      uint4 kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
+      if (TT::ITEMS % NT == 0 || item < TT::ITEMS) {
+        const int r = item / CH, q = item % CH;
+        const int off = ridx[rb][r];
+        if (off >= 0) {
+          kv = *reinterpret_cast<const uint4*>(Kh + (uint32_t)(off + q * 16));
+          vv = *reinterpret_cast<const uint4*>(Vh + (uint32_t)(off + q * 16));
+        }
+      }
+      kreg[i] = kv; vreg[i] = vv;
     }
+  };
+  auto store_lds = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < VIT; ++i) {
-      const int item = tid + i * 256;
-      const int g = item / (D / 2), dp = item % (D / 2);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const int row = ridx[buf][g * 8 + j];
-        uint32_t v = 0;
-        if (row >= 0) v = *reinterpret_cast<const uint32_t*>(Vh + (size_t)row * D + 2 * dp);
-        vreg[i][j] = v;
+    for (int i = 0; i < PT; ++i) {
+      const int item = tid + i * NT;
+      if (TT::ITEMS % NT == 0 || item < TT::ITEMS) {
+        const int r = item / CH, q = item % CH;
+        *reinterpret_cast<uint4*>(&Ks[buf][r * LD + q * 8]) = kreg[i];
+        *reinterpret_cast<uint4*>(&Vs[buf][r * VLD + q * 8]) = vreg[i];
       }
     }
   };
-  auto store_lds = [&]() {
+
+  // The 8 accumulator values a lane feeds to one P V step are keys 4*hb + {0..3} and
+  // 8 + 4*hb + {0..3} of a 16-key group; the V operand is gathered to match by two transpose reads.
+  // Transpose-read address of this lane inside a V tile: key 4*hb + (lane%16)/4, column
+  // 16*((lane/16)%2) + 4*(lane%4); the lane then receives column (lane%32) of 4 consecutive keys.
+  const int vtr_off = (4 * hb + ((lane & 15) >> 2)) * VLD + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  const bf16x2_t ones2 = {(__bf16)1.0f, (__bf16)1.0f};   // row sums use the rounded probabilities P V uses
+  const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+  auto compute_tile = [&](int buf, int nvalid /* < BN only on a masked tail tile */, auto masked) {
+    constexpr bool MASK = decltype(masked)::value;
+    const bf16raw* ks_ = Ks[buf];
+    const bf16raw* vs_ = Vs[buf] + vtr_off;
+    f32x16_t sacc[2][QB];
 #pragma unroll
-    for (int i = 0; i < KPT; ++i) {
-      const int item = tid + i * 256;
-      const int r = item / KCH, q = item % KCH;
-      *reinterpret_cast<uint4*>(&Ks[r * KLD + q * 8]) = kreg[i];
-    }
+    for (int kb = 0; kb < 2; ++kb) {
+      bf16x8_t ka[KS];
 #pragma unroll
-    for (int i = 0; i < VIT; ++i) {
-      const int item = tid + i * 256;
-      const int g = item / (D / 2), dp = item % (D / 2);
-      uint4 lo, hi;
-      // low halves = column 2dp of keys 0..7, high halves = column 2dp+1
-      lo.x = __builtin_amdgcn_perm(vreg[i][1], vreg[i][0], 0x05040100u);
-      lo.y = __builtin_amdgcn_perm(vreg[i][3], vreg[i][2], 0x05040100u);
-      lo.z = __builtin_amdgcn_perm(vreg[i][5], vreg[i][4], 0x05040100u);
-      lo.w = __builtin_amdgcn_perm(vreg[i][7], vreg[i][6], 0x05040100u);
-      hi.x = __builtin_amdgcn_perm(vreg[i][1], vreg[i][0], 0x07060302u);
-      hi.y = __builtin_amdgcn_perm(vreg[i][3], vreg[i][2], 0x07060302u);
-      hi.z = __builtin_amdgcn_perm(vreg[i][5], vreg[i][4], 0x07060302u);
-      hi.w = __builtin_amdgcn_perm(vreg[i][7], vreg[i][6], 0x07060302u);
-      *reinterpret_cast<uint4*>(&Vt[(2 * dp) * VLD + g * 8]) = lo;
-      *reinterpret_cast<uint4*>(&Vt[(2 * dp + 1) * VLD + g * 8]) = hi;
-    }
-  };
-
-  if (T > 0) issue_loads(0);
-  if (tid < BN && T > 1) ridx[1][tid] = cur.row(BN + tid);
-
-  // MFMA row rho of a 32-key block holds key kappa(rho): bits 2 and 3 swapped, so that the 8
-  // accumulator values a lane feeds to one P V step are 8 consecutive keys.
-  const int kappa = (c & 0x13) | ((c & 4) << 1) | ((c & 8) >> 1);
-
-  for (int t = 0; t < T; ++t) {
-    store_lds();
-    __syncthreads();
-    if (t + 1 < T) issue_loads((t + 1) & 1);
-
-    if (wave_has_rows) {
-      f32x16_t sacc[2][QB];
+      for (int ks = 0; ks < KS; ++ks)
+        ka[ks] = *reinterpret_cast<const bf16x8_t*>(&ks_[(kb * 32 + c) * LD + ks * 16 + hb * 8]);
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+      for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) sacc[kb][qb][v] = 0.f;
+          sacc[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qf[qb][ks], ks == 0 ? zero16 : sacc[kb][qb], 0, 0, 0);
+    }
+    // accumulator value v of block kb is key  kb*32 + 8*(v/4) + 4*hb + v%4
+    if (MASK) {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          const bf16x8_t ka = *reinterpret_cast<const bf16x8_t*>(&Ks[(kb * 32 + kappa) * KLD + ks * 16 + hb * 8]);
+        for (int v = 0; v < 16; ++v) {
+          const int key = kb * 32 + 8 * (v >> 2) + 4 * hb + (v & 3);
+          if (key >= nvalid) {
 #pragma unroll
-          for (int qb = 0; qb < QB; ++qb)
-            sacc[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[qb][ks], sacc[kb][qb], 0, 0, 0);
+            for (int qb = 0; qb < QB; ++qb) sacc[kb][qb][v] = -INFINITY;
+          }
         }
-      // accumulator value v of block kb is key  kb*32 + 16*(v/8) + 8*hb + v%8
-      if (t == T - 1 && (total & (BN - 1))) {
-        const int nvalid = total - t * BN;
+    }
+    bf16x8_t pf[QB][2][2];
+    float alpha[QB];
+    bool need_rescale = false;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+    for (int qb = 0; qb < QB; ++qb) {
+      float tmax = sacc[0][qb][0];
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int key = kb * 32 + 16 * (v >> 3) + 8 * hb + (v & 7);
-            if (key >= nvalid) {
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-              for (int qb = 0; qb < QB; ++qb) sacc[kb][qb][v] = -INFINITY;
-            }
+        for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, sacc[kb][qb][v]);
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+      const float mnew = fmaxf(mrun[qb], tmax);           // finite: every tile holds a valid key
+      alpha[qb] = __builtin_amdgcn_exp2f((mrun[qb] - mnew) * a.scale_log2e);
+      need_rescale = need_rescale || (mnew != mrun[qb]);
+      const float moff = mnew * a.scale_log2e;
+      mrun[qb] = mnew;
+      float rsum = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          uint32_t w[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][qb][8 * s2 + 2 * j], a.scale_log2e, -moff));
+            const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][qb][8 * s2 + 2 * j + 1], a.scale_log2e, -moff));
+            w[j] = pack_bf16x2(p0, p1);
+            rsum = __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<const bf16x2_t*>(&w[j]), ones2, rsum, false);
           }
-      }
-      bf16x8_t pf[QB][2][2];
+          const uint4 pk = {w[0], w[1], w[2], w[3]};
+          pf[qb][kb][s2] = *reinterpret_cast<const bf16x8_t*>(&pk);
+        }
+      lrun[qb] = lrun[qb] * alpha[qb] + rsum;
+    }
+    // the running maximum rarely moves after the first tiles: rescale only when some lane needs it
+    if (__any(need_rescale)) {
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        float tmax = sacc[0][qb][0];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, sacc[kb][qb][v]);
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        const float mnew = fmaxf(mrun[qb], tmax);           // finite: every tile holds a valid key
-        const float alpha = __builtin_amdgcn_exp2f((mrun[qb] - mnew) * a.scale_log2e);
-        const float moff = mnew * a.scale_log2e;
-        mrun[qb] = mnew;
-        float rsum = 0.f;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int s2 = 0; s2 < 2; ++s2) {
-            uint32_t w[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][qb][8 * s2 + 2 * j], a.scale_log2e, -moff));
-              const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][qb][8 * s2 + 2 * j + 1], a.scale_log2e, -moff));
-              rsum += p0 + p1;
-              w[j] = pack_bf16x2(p0, p1);
-            }
-            const uint4 pk = {w[0], w[1], w[2], w[3]};
-            pf[qb][kb][s2] = *reinterpret_cast<const bf16x8_t*>(&pk);
-          }
-        lrun[qb] = lrun[qb] * alpha + rsum;
+      for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) oacc[db][qb][v] *= alpha;
-      }
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int s2 = 0; s2 < 2; ++s2) {
-            const bf16x8_t va = *reinterpret_cast<const bf16x8_t*>(&Vt[(db * 32 + c) * VLD + kb * 32 + 16 * s2 + 8 * hb]);
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
-              oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf[qb][kb][s2], oacc[db][qb], 0, 0, 0);
-          }
+          for (int v = 0; v < 16; ++v) oacc[db][qb][v] *= alpha[qb];
     }
-    __syncthreads();
-    if (tid < BN && t + 2 < T) ridx[t & 1][tid] = cur.row((t + 2) * BN + tid);
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      bf16x8_t va[2][2];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          const bf16raw* vp = vs_ + (kb * 32 + 16 * s2) * VLD + db * 32;
+          const s16x4_t lo = lds_read_tr16(vp), hi = lds_read_tr16(vp + 8 * VLD);
+          const s16x4_t both[2] = {lo, hi};
+          va[kb][s2] = *reinterpret_cast<const bf16x8_t*>(both);
+        }
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb)
+            oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[kb][s2], pf[qb][kb][s2], oacc[db][qb], 0, 0, 0);
+    }
+  };
+
+  // prologue: rows of tiles 0..2, tile 0 into LDS, tile 1 into registers
+  RangeCursor cur;
+  auto row_off = [&](int p) { const int r = cur.row(p); return r < 0 ? -1 : r * (D * 2); };
+  if (tid < BN) {
+    cur.init(rs, rp, nr);
+    ridx[0][tid] = (T > 0) ? row_off(tid) : -1;
+    ridx[1][tid] = (T > 1) ? row_off(BN + tid) : -1;
+    ridx[2][tid] = (T > 2) ? row_off(2 * BN + tid) : -1;
   }
+  __syncthreads();
+  if (T > 0) { issue_loads(0); store_lds(0); }
+  if (T > 1) issue_loads(1);
+  __syncthreads();
+
+  // full tiles in the loop; a ragged tail tile (the only one that needs masking) after it
+  const int Tfull = total / BN;
+  for (int t = 0; t < Tfull; ++t) {
+    if (tid < BN && t + 3 < T) ridx[(t + 3) & 3][tid] = row_off((t + 3) * BN + tid);
+    if (wave_has_rows) compute_tile(t & 1, BN, std::false_type{});
+    if (t + 1 < T) store_lds((t + 1) & 1);
+    if (t + 2 < T) issue_loads((t + 2) & 3);
+    __syncthreads();
+  }
+  if (T > Tfull && wave_has_rows) compute_tile(Tfull & 1, total - Tfull * BN, std::true_type{});
 
   // O^T accumulator value v of block db is column  db*32 + 8*(v/4) + 4*hb + v%4  of query c
 #pragma unroll
@@ -454,7 +484,22 @@ __global__ __launch_bounds__(64) void attn_f32(AttnArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
-int attn_block_rows(int dtype, int d) { return dtype == ADACLUSTER_BF16 ? 256 : 64; }
+// tile shapes of the bf16 kernel: queries per wave = 32*QB, waves per block NW, blocks per CU MINB
+#ifndef A64_QB
+#define A64_QB 2
+#define A64_NW 4
+#define A64_MINB 2
+#endif
+#ifndef A128_QB
+#define A128_QB 1
+#define A128_NW 8
+#define A128_MINB 1
+#endif
+
+int attn_block_rows(int dtype, int d) {
+  if (dtype != ADACLUSTER_BF16) return 64;
+  return d == 64 ? A64_NW * 32 * A64_QB : A128_NW * 32 * A128_QB;
+}
 
 int launch_plan_sparse(hipStream_t s, int H, int Cq, int cap, int maxr, int maxtiles, int BM,
                        const int32_t* q_offs, int q_offs_stride, const int32_t* k_offs, int k_offs_stride,
@@ -480,8 +525,8 @@ int launch_attention(hipStream_t s, int dtype, int d, int H, int N, int Cq, int 
              scale * 1.4426950408889634f};
   dim3 g(maxtiles, H);
   if (dtype == ADACLUSTER_BF16) {
-    if (d == 64) attn_mfma<64, 2><<<g, 256, 0, s>>>(a);
-    else attn_mfma<128, 2><<<g, 256, 0, s>>>(a);
+    if (d == 64) attn_mfma<64, A64_QB, A64_NW, A64_MINB><<<g, A64_NW * 64, 0, s>>>(a);
+    else attn_mfma<128, A128_QB, A128_NW, A128_MINB><<<g, A128_NW * 64, 0, s>>>(a);
   } else {
     if (d == 64) attn_f32<64><<<g, 64, 0, s>>>(a);
     else attn_f32<128><<<g, 64, 0, s>>>(a);
