@@ -179,7 +179,10 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
   constexpr int BN = TT::BN, NT = TT::NT, LD = TT::LD, VLD = TT::VLD, KS = TT::KS, DB = TT::DB, CH = TT::CH, PT = TT::PT;
 
   const int h = blockIdx.y;
-  const int tile = blockIdx.x;
+  // Workgroups go to the 8 XCDs round-robin (gridDim.x is a multiple of 8, so XCD = blockIdx.x % 8).
+  // Give every XCD a contiguous run of query tiles: the tiles of one query cluster stream the
+  // same K/V rows, and this way they do it at the same time behind the same L2.
+  const int tile = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
   if (tile >= a.ntiles[h]) return;
   const int32_t* tl = a.tiles + ((size_t)h * a.maxtiles + tile) * 3;
   const int qc = tl[0], row0 = tl[1], nrows = tl[2];
@@ -278,7 +281,11 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
       bf16x8_t ka[KS];
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
+#ifdef ADBG_NOLDSREAD
+        ka[ks] = qf[0][(ks + kb) % KS];
+#else
         ka[ks] = *reinterpret_cast<const bf16x8_t*>(&ks_[(kb * 32 + c) * LD + ks * 16 + hb * 8]);
+#endif
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
@@ -301,6 +308,21 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
     bf16x8_t pf[QB][2][2];
     float alpha[QB];
     bool need_rescale = false;
+#ifdef ADBG_NOSOFTMAX
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      alpha[qb] = 1.f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          uint4 pk;
+          pk.x = __float_as_uint(sacc[kb][qb][8 * s2]); pk.y = __float_as_uint(sacc[kb][qb][8 * s2 + 2]);
+          pk.z = __float_as_uint(sacc[kb][qb][8 * s2 + 4]); pk.w = __float_as_uint(sacc[kb][qb][8 * s2 + 6]);
+          pf[qb][kb][s2] = *reinterpret_cast<const bf16x8_t*>(&pk);
+        }
+    }
+#else
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
       float tmax = sacc[0][qb][0];
@@ -325,13 +347,18 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
             const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][qb][8 * s2 + 2 * j], a.scale_log2e, -moff));
             const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][qb][8 * s2 + 2 * j + 1], a.scale_log2e, -moff));
             w[j] = pack_bf16x2(p0, p1);
+#ifdef A_ROWSUM_ADD
+            rsum += p0 + p1;
+#else
             rsum = __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<const bf16x2_t*>(&w[j]), ones2, rsum, false);
+#endif
           }
           const uint4 pk = {w[0], w[1], w[2], w[3]};
           pf[qb][kb][s2] = *reinterpret_cast<const bf16x8_t*>(&pk);
         }
       lrun[qb] = lrun[qb] * alpha[qb] + rsum;
     }
+#endif
     // the running maximum rarely moves after the first tiles: rescale only when some lane needs it
     if (__any(need_rescale)) {
 #pragma unroll
@@ -349,9 +376,15 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
           const bf16raw* vp = vs_ + (kb * 32 + 16 * s2) * VLD + db * 32;
+#ifdef ADBG_NOLDSREAD
+          va[kb][s2] = qf[0][(kb * 2 + s2 + db) % KS];
+#elif defined(ADBG_VB128)
+          va[kb][s2] = *reinterpret_cast<const bf16x8_t*>(&Vs[buf][(kb * 32 + c) * LD + (db * 2 + s2) * 16 + hb * 8]);
+#else
           const s16x4_t lo = lds_read_tr16(vp), hi = lds_read_tr16(vp + 8 * VLD);
           const s16x4_t both[2] = {lo, hi};
           va[kb][s2] = *reinterpret_cast<const bf16x8_t*>(both);
+#endif
         }
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
@@ -523,7 +556,7 @@ int launch_attention(hipStream_t s, int dtype, int d, int H, int N, int Cq, int 
                      const int32_t* rng_pre, const int32_t* rng_cnt) {
   AttnArgs a{Q, Kp, Vp, O, perm_q, tiles, ntiles, rng_start, rng_pre, rng_cnt, N, Cq, maxtiles, maxr,
              scale * 1.4426950408889634f};
-  dim3 g(maxtiles, H);
+  dim3 g((maxtiles + 7) / 8 * 8, H);
   if (dtype == ADACLUSTER_BF16) {
     if (d == 64) attn_mfma<64, A64_QB, A64_NW, A64_MINB><<<g, A64_NW * 64, 0, s>>>(a);
     else attn_mfma<128, A128_QB, A128_NW, A128_MINB><<<g, A128_NW * 64, 0, s>>>(a);
