@@ -228,61 +228,109 @@ __device__ __forceinline__ bool reduce_setup(const ReduceCfg& c, int h, int& m) 
   m = s.ccount; return true;
 }
 
-// One wave sums one part of one cluster.  A lane owns two adjacent columns; with D = 64 the two
-// half-waves take alternate rows.  psum [H][m_bound][P][D]; pnorm [H][m_bound][P];
-// pmin/pmax like psum.
+// One wave sums one part of one cluster with 16-byte loads: a row is covered by LPR lanes, the
+// wave takes RPI = 64/LPR rows per step (two steps in flight), and the RPI row slots are merged
+// at the end in a fixed order, so the result does not depend on scheduling.
+// psum [H][m_bound][P][D]; pnorm [H][m_bound][P]; pmin/pmax like psum.
+template <typename T> struct Vec16;
+template <> struct Vec16<bf16raw> {
+  static constexpr int N = 8;
+  static __device__ __forceinline__ void load(const bf16raw* p, float* x) {
+    const uint4 r = *reinterpret_cast<const uint4*>(p);
+    const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { x[2 * i] = __uint_as_float(w[i] << 16); x[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u); }
+  }
+};
+template <> struct Vec16<float> {
+  static constexpr int N = 4;
+  static __device__ __forceinline__ void load(const float* p, float* x) {
+    const float4 r = *reinterpret_cast<const float4*>(p);
+    x[0] = r.x; x[1] = r.y; x[2] = r.z; x[3] = r.w;
+  }
+};
+
 template <typename T, int D>
 __global__ __launch_bounds__(64) void seg_reduce(const T* __restrict__ X, ReduceCfg cfg,
                                                  const int32_t* __restrict__ perm,
                                                  const int32_t* __restrict__ offs, int offs_stride,
                                                  float* __restrict__ psum, float* __restrict__ pnorm,
                                                  float* __restrict__ pmin, float* __restrict__ pmax) {
-  constexpr int LPR = D / 2;          // lanes per row
+  constexpr int EV = Vec16<T>::N;     // elements per 16-byte load
+  constexpr int LPR = D / EV;         // lanes per row
   constexpr int RPI = 64 / LPR;       // rows per wave step
   const int h = blockIdx.y;
   int m;
   if (!reduce_setup(cfg, h, m)) return;
   const int j = blockIdx.x / cfg.P, part = blockIdx.x % cfg.P;
   if (j >= m) return;
-  const int lane = threadIdx.x, sub = lane / LPR, c2 = lane % LPR;
+  const int lane = threadIdx.x, slot = lane / LPR, cl = lane % LPR;
   const int beg = offs[(size_t)h * offs_stride + j], end = offs[(size_t)h * offs_stride + j + 1];
   const int nj = end - beg;
   const int chunk = (nj + cfg.P - 1) / cfg.P;
   const int mb = beg + part * chunk;
   const int me = min(end, mb + chunk);
   const int32_t* pm = perm + (size_t)h * cfg.N;
-  const T* Xh = X + (size_t)h * cfg.N * D;
-  float a0 = 0.f, a1 = 0.f, nsum = 0.f;
-  float mn0 = INFINITY, mn1 = INFINITY, mx0 = -INFINITY, mx1 = -INFINITY;
-  for (int r = mb + sub; r < me; r += RPI) {
-    const int tok = pm[r];
-    const T* row = Xh + (size_t)tok * D + 2 * c2;
-    float x0 = Elem<T>::load(row), x1 = Elem<T>::load(row + 1);
+  const T* Xh = X + (size_t)h * cfg.N * D + cl * EV;
+  float acc[EV], mn[EV], mx[EV];
+#pragma unroll
+  for (int e = 0; e < EV; ++e) { acc[e] = 0.f; mn[e] = INFINITY; mx[e] = -INFINITY; }
+  float nsum = 0.f;
+  auto add_row = [&](const float* x, bool valid) {
+    float xs[EV];
+#pragma unroll
+    for (int e = 0; e < EV; ++e) xs[e] = x[e];
     if (cfg.normalize) {
-      float ss = fmaf(x0, x0, x1 * x1);
+      float ss = 0.f;
+#pragma unroll
+      for (int e = 0; e < EV; ++e) ss = fmaf(xs[e], xs[e], ss);
 #pragma unroll
       for (int o = 1; o < LPR; o <<= 1) ss += __shfl_xor(ss, o);
       const float nrm = sqrtf(ss);
       const float inv = 1.0f / fmaxf(nrm, 1e-12f);
-      x0 *= inv; x1 *= inv;
-      nsum += nrm;
+#pragma unroll
+      for (int e = 0; e < EV; ++e) xs[e] *= inv;
+      if (valid) nsum += nrm;
     }
-    a0 += x0; a1 += x1;
-    if (cfg.want_box) { mn0 = fminf(mn0, x0); mn1 = fminf(mn1, x1); mx0 = fmaxf(mx0, x0); mx1 = fmaxf(mx1, x1); }
+    if (valid) {
+#pragma unroll
+      for (int e = 0; e < EV; ++e) {
+        acc[e] += xs[e];
+        if (cfg.want_box) { mn[e] = fminf(mn[e], xs[e]); mx[e] = fmaxf(mx[e], xs[e]); }
+      }
+    }
+  };
+  // all lanes run the same number of steps (the shuffles above need every lane of a row present)
+  for (int r0 = mb; r0 < me; r0 += 2 * RPI) {
+    const int ra = r0 + slot, rb = r0 + RPI + slot;
+    const bool va = ra < me, vb = rb < me;
+    float xa[EV], xb[EV];
+#pragma unroll
+    for (int e = 0; e < EV; ++e) { xa[e] = 0.f; xb[e] = 0.f; }
+    if (va) Vec16<T>::load(Xh + (size_t)pm[ra] * D, xa);
+    if (vb) Vec16<T>::load(Xh + (size_t)pm[rb] * D, xb);
+    add_row(xa, va);
+    add_row(xb, vb);
   }
-  if (RPI == 2) {
-    a0 += __shfl_xor(a0, 32); a1 += __shfl_xor(a1, 32); nsum += __shfl_xor(nsum, 32);
-    mn0 = fminf(mn0, __shfl_xor(mn0, 32)); mn1 = fminf(mn1, __shfl_xor(mn1, 32));
-    mx0 = fmaxf(mx0, __shfl_xor(mx0, 32)); mx1 = fmaxf(mx1, __shfl_xor(mx1, 32));
+  // merge the row slots: slot s+o into slot s, o = RPI/2 ... 1
+#pragma unroll
+  for (int o = RPI / 2; o >= 1; o >>= 1) {
+#pragma unroll
+    for (int e = 0; e < EV; ++e) {
+      acc[e] += __shfl_down(acc[e], o * LPR);
+      mn[e] = fminf(mn[e], __shfl_down(mn[e], o * LPR));
+      mx[e] = fmaxf(mx[e], __shfl_down(mx[e], o * LPR));
+    }
+    nsum += __shfl_down(nsum, o * LPR);
   }
-  if (sub == 0) {
+  if (slot == 0) {
     const size_t o = (((size_t)h * cfg.m_bound + j) * cfg.P + part);
-    psum[o * D + 2 * c2] = a0; psum[o * D + 2 * c2 + 1] = a1;
-    if (cfg.want_box) {
-      pmin[o * D + 2 * c2] = mn0; pmin[o * D + 2 * c2 + 1] = mn1;
-      pmax[o * D + 2 * c2] = mx0; pmax[o * D + 2 * c2 + 1] = mx1;
+#pragma unroll
+    for (int e = 0; e < EV; ++e) {
+      psum[o * D + cl * EV + e] = acc[e];
+      if (cfg.want_box) { pmin[o * D + cl * EV + e] = mn[e]; pmax[o * D + cl * EV + e] = mx[e]; }
     }
-    if (cfg.normalize && c2 == 0) pnorm[o] = nsum;
+    if (cfg.normalize && cl == 0) pnorm[o] = nsum;
   }
 }
 
@@ -522,14 +570,23 @@ __global__ __launch_bounds__(256) void tau_partial(const float* __restrict__ dis
   if (tid == 0) part[(size_t)h * nblk + b] = (ws[0] + ws[1]) + (ws[2] + ws[3]);
 }
 
-__global__ void tau_final(const double* __restrict__ part, int count, double denom, float factor,
-                          float* __restrict__ tau_out /* [0]=tau, [1]=tau^2 */) {
-  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+__global__ __launch_bounds__(256) void tau_final(const double* __restrict__ part, int count, double denom, float factor,
+                                                 float* __restrict__ tau_out /* [0]=tau, [1]=tau^2 */) {
+  // fixed-order reduction: thread i takes elements i, i+256, ...; then a fixed tree
+  const int tid = threadIdx.x;
   double s = 0.0;
-  for (int i = 0; i < count; ++i) s += part[i];
-  const double tau = (double)factor * s / denom;
-  tau_out[0] = (float)tau;
-  tau_out[1] = (float)tau * (float)tau;
+  for (int i = tid; i < count; i += 256) s += part[i];
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) s += __shfl_xor(s, o);
+  __shared__ double ws[4];
+  if ((tid & 63) == 0) ws[tid >> 6] = s;
+  __syncthreads();
+  if (tid == 0) {
+    const double tot = (ws[0] + ws[1]) + (ws[2] + ws[3]);
+    const double tau = (double)factor * tot / denom;
+    tau_out[0] = (float)tau;
+    tau_out[1] = (float)tau * (float)tau;
+  }
 }
 
 __global__ void tau_set(float tau, float* __restrict__ tau_out) {
@@ -723,7 +780,7 @@ int launch_tau(hipStream_t s, int H, int N, const float* dist2, double* part, fl
   }
   const int nblk = (N + 1023) / 1024;
   tau_partial<<<dim3(nblk, H), 256, 0, s>>>(dist2, N, nblk, part);
-  tau_final<<<1, 64, 0, s>>>(part, nblk * H, (double)H * (double)N, factor, tau_out);
+  tau_final<<<1, 256, 0, s>>>(part, nblk * H, (double)H * (double)N, factor, tau_out);
   return chk();
 }
 
