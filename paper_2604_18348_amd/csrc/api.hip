@@ -107,7 +107,7 @@ Dims dims_of(const adacluster_params* p) {
   D.H = p->H; D.N = p->N; D.d = p->d; D.Cq = p->q_clusters; D.cap = capacity(p);
   D.capmax = D.cap > D.Cq ? D.cap : D.Cq;
   D.nblk = (p->N + 1023) / 1024;
-  D.nseg = (p->N + 1023) / 1024;
+  D.nseg = (p->N + 511) / 512;
   D.BM = attn_block_rows(p->dtype, p->d);
   D.maxtiles = p->N / D.BM + D.Cq + 1;
   D.maxr = D.cap;

@@ -10,7 +10,7 @@
 
 namespace adac {
 
-static constexpr int SEG = 1024;     // items per single-wave block
+static constexpr int SEG = 512;      // items per single-wave block
 static constexpr int RBITS = 7;
 static constexpr int RBINS = 1 << RBITS;
 
@@ -83,19 +83,17 @@ __global__ __launch_bounds__(64) void radix_scatter(const int32_t* __restrict__ 
     const int l = valid ? lab[p] : 0;
     const int v = valid ? (val ? val[p] : p) : 0;
     const int dig = (l >> shift) & (RBINS - 1);
-    uint64_t remaining = __ballot(valid);
-    int rank = 0, cnt = 0; bool leader = false;
-    while (remaining) {
-      const int lead = __ffsll((unsigned long long)remaining) - 1;
-      const int dl = __shfl(dig, lead);
-      const uint64_t same = __ballot(valid && dig == dl);
-      if (valid && dig == dl) {
-        rank = __popcll(same & lt_mask);
-        cnt = __popcll(same);
-        leader = (lane == lead);
-      }
-      remaining &= ~same;
+    // lanes holding my digit: intersect, bit by bit, the ballots of lanes that agree with me
+    uint64_t same = __ballot(valid);
+#pragma unroll
+    for (int b = 0; b < RBITS; ++b) {
+      const bool bit = (dig >> b) & 1;
+      const uint64_t bal = __ballot(bit);
+      same &= bit ? bal : ~bal;
     }
+    const int rank = __popcll(same & lt_mask);
+    const int cnt = __popcll(same);
+    const bool leader = valid && rank == 0;
     int pos = 0;
     if (valid) pos = base[dig] + rank;
     __syncthreads();

@@ -1,0 +1,107 @@
+"""Full-size chained parity on the benchmark configurations, in the launch configuration the
+benchmark times (same H, N, d, parameters), checked on sampled outputs the oracle computes one by
+one: sampled tokens' labels are the arg-min / arg-max to the reported centres, sampled query
+clusters' selections are bit-exact given the GPU's centroids, and sampled output rows equal the
+fp64 softmax over the keys of the selected clusters (1e-2 relative L2 / 2e-2 max-abs for bf16)."""
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import adacluster_oracle as orc
+from paper_2604_18348_amd import binding as B
+from paper_2604_18348_amd import workloads as wl
+from tests.helpers import REL_TIE, sel_from_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def gen(name):
+    cfg = wl.CONFIGS[name]
+    H, N, d = cfg["H"], wl.n_tokens(cfg), cfg["d"]
+    dt = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
+    Q = torch.empty((H, N, d), dtype=dt, device="cuda")
+    K = torch.empty_like(Q)
+    V = torch.empty_like(Q)
+    keep = {}
+    sample_heads = sorted(set([0, H // 2, H - 1]))
+
+    def one(h):
+        return h, wl.make_head(cfg, h)
+
+    with ThreadPoolExecutor(max_workers=min(16, H)) as ex:
+        for h, (q, k, v) in ex.map(one, range(H)):
+            Q[h].copy_(torch.from_numpy(q).to(dt))
+            K[h].copy_(torch.from_numpy(k).to(dt))
+            V[h].copy_(torch.from_numpy(v).to(dt))
+            if h in sample_heads:
+                keep[h] = (q, k, v)
+    return cfg, Q, K, V, keep
+
+
+@pytest.mark.parametrize("name", ["c2", "c3", "c4", "c5"])
+def test_fullsize_sampled_parity(name):
+    cfg, Q, K, V, keep = gen(name)
+    H, N, d = Q.shape
+    p = B.Params(H=H, N=N, d=d, dtype=B.BF16, **cfg["params"])
+    outs = B.alloc_outputs(p, "cuda")
+    O = B.adacluster_attn(p, Q, K, V, outs=outs)
+    torch.cuda.synchronize()
+    kc = outs["k_count"].cpu().numpy()
+    full = outs["full_flag"].cpu().numpy()
+    print(name, "k_count min/mean/max", kc.min(), kc.mean(), kc.max(), "full heads", int(full.sum()),
+          "tau", float(outs["tau_used"][0]))
+    assert np.all(kc >= 1) and np.all(kc <= p.cap)
+    rng = np.random.default_rng(7)
+    scale = float(np.float32(1.0 / np.sqrt(np.float32(d))))
+    for h, (q, k, v) in keep.items():
+        q64, k64, v64 = q.astype(np.float64), k.astype(np.float64), v.astype(np.float64)
+        ql = outs["q_labels"][h].cpu().numpy()
+        kl = outs["k_labels"][h].cpu().numpy()
+        qa = to_np(outs["q_assign_centroids"][h])
+        ka = to_np(outs["k_assign_centroids"][h])[:kc[h]]
+        sizes = outs["k_sizes"][h].cpu().numpy()[:kc[h]]
+        assert np.array_equal(sizes, np.bincount(kl, minlength=kc[h]))
+        assert np.array_equal(outs["q_sizes"][h].cpu().numpy(), np.bincount(ql, minlength=p.q_clusters))
+        # labels of sampled tokens
+        toks = rng.choice(N, size=256, replace=False)
+        Xn = orc.normalize_rows(q64[toks])
+        S = Xn @ qa.T
+        bad = np.flatnonzero(S.argmax(1) != ql[toks])
+        assert np.all(S[bad].max(1) - S[bad, ql[toks][bad]] <= REL_TIE), "query label off a near-tie"
+        G = (ka * ka).sum(1)[None] - 2 * k64[toks] @ ka.T
+        bad = np.flatnonzero(G.argmin(1) != kl[toks])
+        sc_ = (k64[toks][bad] ** 2).sum(1) + (ka[kl[toks][bad]] ** 2).sum(1)
+        assert np.all(G[bad, kl[toks][bad]] - G[bad].min(1) <= REL_TIE * sc_), "key label off a near-tie"
+        # centroids of a few clusters are the member means of the GPU labels
+        kcen = to_np(outs["k_centroids"][h])
+        for j in rng.choice(kc[h], size=4, replace=False):
+            if sizes[j]:
+                assert np.allclose(kcen[j], k64[kl == j].mean(0), atol=2e-5, rtol=1e-5)
+        # selection of sampled query clusters from the GPU's centroids: bit-exact
+        sel = sel_from_dev(outs["sel_idx"][h:h + 1], outs["sel_cnt"][h:h + 1])[0]
+        Ssc = orc.cluster_scores(p.score_mode, to_np(outs["q_centroids"][h]), kcen[:kc[h]], None, None, sizes)
+        if full[h]:
+            ref_sel = [np.flatnonzero(sizes > 0)] * p.q_clusters
+        elif p.select_mode == 0:
+            ref_sel = orc.select_topk(Ssc, p.topk)
+        else:
+            ref_sel = orc.select_topp(Ssc, sizes, to_np(outs["q_mean_norm"][h]) * scale, p.top_p)
+        for i in range(p.q_clusters):
+            assert np.array_equal(sel[i], ref_sel[i]), (h, i)
+        # sampled output rows
+        rows = rng.choice(N, size=24, replace=False)
+        got = O[h][torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
+        order = np.argsort(kl, kind="stable")
+        bounds = np.searchsorted(kl[order], np.arange(kc[h] + 1))
+        ref = np.zeros_like(got)
+        for n_, r in enumerate(rows):
+            s_ = sel[ql[r]]
+            kidx = np.concatenate([order[bounds[j]:bounds[j + 1]] for j in s_]) if len(s_) else np.zeros(0, int)
+            if kidx.size:
+                ref[n_] = orc.dense_attention(q64[r:r + 1], k64[kidx], v64[kidx], scale)[0]
+        rel = float(np.linalg.norm(got - ref) / np.linalg.norm(ref))
+        mx = float(np.abs(got - ref).max())
+        print(name, "head", h, "k_count", kc[h], "full", full[h], "rows rel", rel, "max", mx)
+        assert rel < 1e-2 and mx < 2e-2
