@@ -14,7 +14,7 @@ from dataclasses import dataclass, asdict
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "_lib", "libadacluster.so")
+LIB_PATH = os.environ.get("ADACLUSTER_LIB") or os.path.join(_HERE, "_lib", "libadacluster.so")
 MAX_STAGES = 16
 
 F32, BF16 = 0, 1

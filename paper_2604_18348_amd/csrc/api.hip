@@ -70,10 +70,8 @@ int check_params(const adacluster_params* p) {
 
 inline int capacity(const adacluster_params* p) { return p->k_max_clusters + p->k_m0; }
 inline size_t esize(const adacluster_params* p) { return p->dtype == ADACLUSTER_BF16 ? 2 : 4; }
-inline int parts_for(int n, int m) {
-  long long P = ((long long)n + (long long)m * 128 - 1) / ((long long)m * 128);
-  return (int)(P < 1 ? 1 : (P > 32 ? 32 : P));
-}
+// upper bound of the number of 128-row parts of n rows in m clusters
+inline int parts_for(int n, int m) { return m + (n + 127) / 128 + 1; }
 
 // ---- workspace layout ----------------------------------------------------------------------
 struct Layout {
@@ -86,7 +84,7 @@ struct WS {
   KState* kstate; int32_t* summary; float* tau; int32_t* u_prev;
   void* cent_lp; float* bias; float* master;
   int32_t* labels_tmp; float* dist2; int32_t* ulist[2]; int32_t* blockcnt; double* tau_part;
-  SortScratch sort; int32_t* perm_tmp; int32_t* offs_tmp;
+  SortScratch sort; int32_t* perm_tmp; int32_t* offs_tmp; int32_t* poff;
   float* psum; float* pnorm; float* pmin; float* pmax;
   int32_t* perm_q; int32_t* offs_q; int32_t* perm_k; int32_t* offs_k;
   void* Kp; void* Vp;
@@ -139,6 +137,7 @@ size_t layout(const adacluster_params* p, WS* w, unsigned char* base) {
   TAKE(sort.lab_b, int32_t*, H * N * 4);
   TAKE(perm_tmp, int32_t*, H * N * 4);
   TAKE(offs_tmp, int32_t*, H * (size_t)(D.capmax + 1) * 4);
+  TAKE(poff, int32_t*, H * (size_t)(D.capmax + 1) * 4);
   TAKE(psum, float*, H * (size_t)D.prow * d * 4);
   TAKE(pnorm, float*, H * (size_t)D.prow * 4);
   TAKE(pmin, float*, H * (size_t)D.prow * d * 4);
@@ -199,15 +198,15 @@ int run_qcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
     RET_IF(launch_sort(st, D.H, D.N, D.N, D.Cq, q_labels, nullptr, nullptr, 0, nullptr, 0, nullptr, 0, w.perm_q,
                        w.offs_q, D.Cq + 1, w.sort));
     RET_IF(launch_seg_reduce(st, p->dtype, D.d, D.H, D.N, 0, D.Cq, D.Cq, P, nullptr, 1, 0, Q, w.perm_q, w.offs_q,
-                             D.Cq + 1, w.psum, w.pnorm, w.pmin, w.pmax));
+                             D.Cq + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax));
     const bool last = it == p->q_iters - 1;
     if (!last) {
       RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 0, D.Cq, D.Cq, P, D.Cq, D.Cq, nullptr, 1, 1, 0, w.offs_q,
-                             D.Cq + 1, w.psum, w.pnorm, w.pmin, w.pmax, q_centroids, w.cent_lp, q_assign, w.bias,
+                             D.Cq + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax, q_centroids, w.cent_lp, q_assign, w.bias,
                              nullptr, nullptr, nullptr, nullptr, nullptr, nullptr));
     } else {
       RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 0, D.Cq, D.Cq, P, D.Cq, D.Cq, nullptr, 1, 0, 0, w.offs_q,
-                             D.Cq + 1, w.psum, w.pnorm, w.pmin, w.pmax, nullptr, nullptr, nullptr, nullptr,
+                             D.Cq + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax, nullptr, nullptr, nullptr, nullptr,
                              q_centroids, nullptr, q_sizes, q_mean_norm, nullptr, nullptr));
     }
   }
@@ -246,9 +245,9 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
                            sizeof(KState) / 4, &w.kstate->m_t, sizeof(KState) / 4, &w.kstate->active,
                            sizeof(KState) / 4, w.perm_tmp, w.offs_tmp, D.capmax + 1, w.sort));
         RET_IF(launch_seg_reduce(st, p->dtype, D.d, D.H, D.N, 1, 0, m_bound, P, w.kstate, 0, 0, K, w.perm_tmp,
-                                 w.offs_tmp, D.capmax + 1, w.psum, w.pnorm, w.pmin, w.pmax));
+                                 w.offs_tmp, D.capmax + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax));
         RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 1, 0, m_bound, P, D.cap, p->k_m0, w.kstate, 0, 1, 0,
-                               w.offs_tmp, D.capmax + 1, w.psum, w.pnorm, w.pmin, w.pmax, w.master, w.cent_lp,
+                               w.offs_tmp, D.capmax + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax, w.master, w.cent_lp,
                                k_assign, w.bias, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr));
       }
     }
@@ -268,9 +267,9 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
   const int want_box = (k_bmin && k_bmax) ? 1 : 0;
   const int P = parts_for(D.N, D.cap);
   RET_IF(launch_seg_reduce(st, p->dtype, D.d, D.H, D.N, 2, 0, D.cap, P, w.kstate, 0, want_box, K, w.perm_k, w.offs_k,
-                           D.cap + 1, w.psum, w.pnorm, w.pmin, w.pmax));
+                           D.cap + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax));
   RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 2, 0, D.cap, P, D.cap, D.cap, w.kstate, 0, 0, want_box, w.offs_k,
-                         D.cap + 1, w.psum, w.pnorm, w.pmin, w.pmax, nullptr, nullptr, nullptr, nullptr, k_centroids,
+                         D.cap + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax, nullptr, nullptr, nullptr, nullptr, k_centroids,
                          k_assign, k_sizes, nullptr, k_bmin, k_bmax));
   return 0;
 }

@@ -122,7 +122,16 @@ struct AttnArgs {
   const int32_t* rng_start; const int32_t* rng_pre; const int32_t* rng_cnt;
   int N, Cq, maxtiles, maxr;
   float scale_log2e;            // softmax scale x log2(e)
+  unsigned long long* dbg;
 };
+
+#ifdef ADBG_TIMING
+static unsigned long long* g_dbg_host_ptr = nullptr;
+extern "C" int adacluster_debug_set(void* p) { g_dbg_host_ptr = (unsigned long long*)p; return 0; }
+#define DBG_T(var) const long long var = __builtin_readcyclecounter()
+#else
+#define DBG_T(var)
+#endif
 
 // position in the concatenation of ranges -> permuted key row; a cursor that only moves forward
 struct RangeCursor {
@@ -146,37 +155,26 @@ struct RangeCursor {
 // ------------------------------------------------------------------------------------------
 // One block = NW waves, each owning QB blocks of 32 queries; all waves share the 64-key K and V
 // tiles.  LDS is double buffered (one barrier per tile); global loads run two tiles ahead.
-template <int D, int QB, int NW>
-struct AttnTile {
-  static constexpr int BN = 64;
-  static constexpr int NT = NW * 64;
-  static constexpr int BM = NW * 32 * QB;
-  static constexpr int LD = D + 8;          // K tile row stride (bf16): conflict-free 16-byte reads
-#ifndef A_VPAD
-#define A_VPAD 16
-#endif
-  static constexpr int VLD = D + A_VPAD;    // V tile row stride: conflict-free transpose reads
-  static constexpr int KS = D / 16;         // contraction steps of S
-  static constexpr int DB = D / 32;         // 32-row blocks of O^T
-  static constexpr int CH = D / 8;          // 16-byte chunks per row
-  static constexpr int ITEMS = BN * CH;
-  static constexpr int PT = (ITEMS + NT - 1) / NT;
-};
-
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4_t;
 typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
+typedef __attribute__((address_space(3))) void lds_void_t;
 
 // LDS transpose read (16-bit elements): inside each group of 16 lanes, lane r supplies the address
 // of 4 consecutive elements and lane i receives element i%4 of the rows addressed by lanes
 // i/4, i/4+4, i/4+8, i/4+12.
-__device__ __forceinline__ s16x4_t lds_read_tr16(const bf16raw* p) {
+__device__ __forceinline__ s16x4_t lds_read_tr16(const char* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)p);
 }
 
+// One workgroup = NW waves, each owning QB blocks of 32 queries; all waves share 64-key K and V
+// tiles.  Tiles go global -> LDS directly (no register staging) as 16-byte chunks, one tile
+// ahead, double buffered.  A tile row is unpadded; chunk g of row r sits in slot g ^ (r & 7), which
+// keeps the 16-byte operand reads and the transpose reads free of bank conflicts.
 template <int D, int QB, int NW, int MINB>
 __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
-  using TT = AttnTile<D, QB, NW>;
-  constexpr int BN = TT::BN, NT = TT::NT, LD = TT::LD, VLD = TT::VLD, KS = TT::KS, DB = TT::DB, CH = TT::CH, PT = TT::PT;
+  constexpr int BN = 64, NT = NW * 64, KS = D / 16, DB = D / 32, CH = D / 8, ROWB = D * 2;
+  constexpr int ITEMS = BN * CH, PT = ITEMS / NT, TILEB = BN * ROWB;
+  static_assert(ITEMS % NT == 0, "tile chunks must divide evenly over the threads");
 
   const int h = blockIdx.y;
   // Workgroups go to the 8 XCDs round-robin (gridDim.x is a multiple of 8, so XCD = blockIdx.x % 8).
@@ -196,14 +194,14 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
   const int T = (total + BN - 1) / BN;
 
   const bf16raw* Qh = (const bf16raw*)a.Q + (size_t)h * a.N * D;
-  const char* Kh = (const char*)a.Kp + (size_t)h * a.N * D * 2;
-  const char* Vh = (const char*)a.Vp + (size_t)h * a.N * D * 2;
+  const char* Kh = (const char*)a.Kp + (size_t)h * a.N * ROWB;
+  const char* Vh = (const char*)a.Vp + (size_t)h * a.N * ROWB;
   bf16raw* Oh = (bf16raw*)a.O + (size_t)h * a.N * D;
   const int32_t* pq = a.perm_q ? a.perm_q + (size_t)h * a.N : nullptr;
 
-  __shared__ __attribute__((aligned(16))) bf16raw Ks[2][BN * LD];
-  __shared__ __attribute__((aligned(16))) bf16raw Vs[2][BN * VLD];
-  __shared__ int32_t ridx[4][BN];          // byte offset of each key row of a tile (-1: no key)
+  __shared__ __attribute__((aligned(16))) char Ks[2][TILEB];
+  __shared__ __attribute__((aligned(16))) char Vs[2][TILEB];
+  __shared__ int32_t ridx[4][BN];          // byte offset of each key row of a tile
 
   // query tokens of this lane and the B operand of S
   int qtok[QB];
@@ -233,59 +231,53 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) { mrun[qb] = -INFINITY; lrun[qb] = 0.f; }
 
-  // K and V rows travel as 16-byte chunks: thread -> (row, chunk) fixed for the whole kernel
-  uint4 kreg[PT], vreg[PT];
-  auto issue_loads = [&](int rb) {
+  // thread -> (row, slot) of its PT chunks; the slot holds global chunk slot ^ (row & 7)
+  auto issue_loads = [&](int buf, int rb) {
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
       const int item = tid + i * NT;
-      uint4 kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
-      if (TT::ITEMS % NT == 0 || item < TT::ITEMS) {
-        const int r = item / CH, q = item % CH;
-        const int off = ridx[rb][r];
-        if (off >= 0) {
-          kv = *reinterpret_cast<const uint4*>(Kh + (uint32_t)(off + q * 16));
-          vv = *reinterpret_cast<const uint4*>(Vh + (uint32_t)(off + q * 16));
-        }
-      }
-      kreg[i] = kv; vreg[i] = vv;
-    }
-  };
-  auto store_lds = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < PT; ++i) {
-      const int item = tid + i * NT;
-      if (TT::ITEMS % NT == 0 || item < TT::ITEMS) {
-        const int r = item / CH, q = item % CH;
-        *reinterpret_cast<uint4*>(&Ks[buf][r * LD + q * 8]) = kreg[i];
-        *reinterpret_cast<uint4*>(&Vs[buf][r * VLD + q * 8]) = vreg[i];
-      }
+      const int r = item / CH, q = item % CH;
+      const uint32_t off = (uint32_t)ridx[rb][r] + (uint32_t)((q ^ (r & 7)) * 16);
+      const int dst = (wave * 64 + i * NT) * 16;     // wave-uniform; the lane offset is implicit
+      __builtin_amdgcn_global_load_lds(Kh + off, (lds_void_t*)(Ks[buf] + dst), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(Vh + off, (lds_void_t*)(Vs[buf] + dst), 16, 0, 0);
     }
   };
 
+  // operand addresses inside a tile (bytes), fixed for the whole kernel
+  int kaddr[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) kaddr[ks] = c * ROWB + (((ks * 2 + hb) ^ (c & 7)) * 16);
   // The 8 accumulator values a lane feeds to one P V step are keys 4*hb + {0..3} and
-  // 8 + 4*hb + {0..3} of a 16-key group; the V operand is gathered to match by two transpose reads.
-  // Transpose-read address of this lane inside a V tile: key 4*hb + (lane%16)/4, column
-  // 16*((lane/16)%2) + 4*(lane%4); the lane then receives column (lane%32) of 4 consecutive keys.
-  const int vtr_off = (4 * hb + ((lane & 15) >> 2)) * VLD + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  // 8 + 4*hb + {0..3} of a 16-key group; the V operand is gathered to match by two transpose
+  // reads: this lane addresses key 4*hb + (lane%16)/4, columns 16*((lane/16)%2) + 4*(lane%4) .. +3
+  // and receives column lane%32 of the four keys.
+  int vaddr[DB];
+  {
+    const int i16 = lane & 15, blk = lane >> 4;
+    const int vrow = 4 * hb + (i16 >> 2);
+    const int gl = 2 * (blk & 1) + ((i16 & 3) >> 1);
+#pragma unroll
+    for (int db = 0; db < DB; ++db) vaddr[db] = vrow * ROWB + (((db * 4 + gl) ^ (vrow & 7)) * 16) + 8 * (i16 & 1);
+  }
   const bf16x2_t ones2 = {(__bf16)1.0f, (__bf16)1.0f};   // row sums use the rounded probabilities P V uses
   const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
+#ifdef ADBG_TIMING
+  long long dbg_s = 0, dbg_sm = 0, dbg_pv = 0, dbg_ld = 0, dbg_bar = 0;
+#endif
   auto compute_tile = [&](int buf, int nvalid /* < BN only on a masked tail tile */, auto masked) {
     constexpr bool MASK = decltype(masked)::value;
-    const bf16raw* ks_ = Ks[buf];
-    const bf16raw* vs_ = Vs[buf] + vtr_off;
+    const char* ks_ = Ks[buf];
+    const char* vs_ = Vs[buf];
+    DBG_T(t_a);
     f32x16_t sacc[2][QB];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       bf16x8_t ka[KS];
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
-#ifdef ADBG_NOLDSREAD
-        ka[ks] = qf[0][(ks + kb) % KS];
-#else
-        ka[ks] = *reinterpret_cast<const bf16x8_t*>(&ks_[(kb * 32 + c) * LD + ks * 16 + hb * 8]);
-#endif
+        ka[ks] = *reinterpret_cast<const bf16x8_t*>(ks_ + kb * 32 * ROWB + kaddr[ks]);
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
@@ -305,24 +297,13 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
           }
         }
     }
+#ifdef ADBG_TIMING
+    asm volatile("s_nop 0" :: "v"(sacc[1][QB - 1][15]));
+#endif
+    DBG_T(t_b);
     bf16x8_t pf[QB][2][2];
     float alpha[QB];
     bool need_rescale = false;
-#ifdef ADBG_NOSOFTMAX
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      alpha[qb] = 1.f;
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-          uint4 pk;
-          pk.x = __float_as_uint(sacc[kb][qb][8 * s2]); pk.y = __float_as_uint(sacc[kb][qb][8 * s2 + 2]);
-          pk.z = __float_as_uint(sacc[kb][qb][8 * s2 + 4]); pk.w = __float_as_uint(sacc[kb][qb][8 * s2 + 6]);
-          pf[qb][kb][s2] = *reinterpret_cast<const bf16x8_t*>(&pk);
-        }
-    }
-#else
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
       float tmax = sacc[0][qb][0];
@@ -347,18 +328,13 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
             const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][qb][8 * s2 + 2 * j], a.scale_log2e, -moff));
             const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][qb][8 * s2 + 2 * j + 1], a.scale_log2e, -moff));
             w[j] = pack_bf16x2(p0, p1);
-#ifdef A_ROWSUM_ADD
-            rsum += p0 + p1;
-#else
             rsum = __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<const bf16x2_t*>(&w[j]), ones2, rsum, false);
-#endif
           }
           const uint4 pk = {w[0], w[1], w[2], w[3]};
           pf[qb][kb][s2] = *reinterpret_cast<const bf16x8_t*>(&pk);
         }
       lrun[qb] = lrun[qb] * alpha[qb] + rsum;
     }
-#endif
     // the running maximum rarely moves after the first tiles: rescale only when some lane needs it
     if (__any(need_rescale)) {
 #pragma unroll
@@ -368,6 +344,10 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
 #pragma unroll
           for (int v = 0; v < 16; ++v) oacc[db][qb][v] *= alpha[qb];
     }
+#ifdef ADBG_TIMING
+    asm volatile("s_nop 0" :: "v"(pf[QB - 1][1][1]));
+#endif
+    DBG_T(t_c);
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
       bf16x8_t va[2][2];
@@ -375,16 +355,10 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
-          const bf16raw* vp = vs_ + (kb * 32 + 16 * s2) * VLD + db * 32;
-#ifdef ADBG_NOLDSREAD
-          va[kb][s2] = qf[0][(kb * 2 + s2 + db) % KS];
-#elif defined(ADBG_VB128)
-          va[kb][s2] = *reinterpret_cast<const bf16x8_t*>(&Vs[buf][(kb * 32 + c) * LD + (db * 2 + s2) * 16 + hb * 8]);
-#else
-          const s16x4_t lo = lds_read_tr16(vp), hi = lds_read_tr16(vp + 8 * VLD);
+          const char* vp = vs_ + (kb * 32 + 16 * s2) * ROWB + vaddr[db];
+          const s16x4_t lo = lds_read_tr16(vp), hi = lds_read_tr16(vp + 8 * ROWB);
           const s16x4_t both[2] = {lo, hi};
           va[kb][s2] = *reinterpret_cast<const bf16x8_t*>(both);
-#endif
         }
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
@@ -394,31 +368,56 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
           for (int qb = 0; qb < QB; ++qb)
             oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[kb][s2], pf[qb][kb][s2], oacc[db][qb], 0, 0, 0);
     }
+#ifdef ADBG_TIMING
+    asm volatile("s_nop 0" :: "v"(oacc[DB - 1][QB - 1][15]));
+    DBG_T(t_d);
+    dbg_s += t_b - t_a; dbg_sm += t_c - t_b; dbg_pv += t_d - t_c;
+#endif
   };
 
-  // prologue: rows of tiles 0..2, tile 0 into LDS, tile 1 into registers
+  // prologue: row offsets of tiles 0..2 (a slot past the end repeats the first row: it is loaded
+  // but masked), tile 0 into LDS
   RangeCursor cur;
-  auto row_off = [&](int p) { const int r = cur.row(p); return r < 0 ? -1 : r * (D * 2); };
+  const int first_off = nr > 0 ? rs[0] * ROWB : 0;
+  auto row_off = [&](int p) { const int r = cur.row(p); return r < 0 ? first_off : r * ROWB; };
   if (tid < BN) {
     cur.init(rs, rp, nr);
-    ridx[0][tid] = (T > 0) ? row_off(tid) : -1;
-    ridx[1][tid] = (T > 1) ? row_off(BN + tid) : -1;
-    ridx[2][tid] = (T > 2) ? row_off(2 * BN + tid) : -1;
+    ridx[0][tid] = row_off(tid);
+    ridx[1][tid] = row_off(BN + tid);
+    ridx[2][tid] = row_off(2 * BN + tid);
   }
   __syncthreads();
-  if (T > 0) { issue_loads(0); store_lds(0); }
-  if (T > 1) issue_loads(1);
+  if (T > 0) issue_loads(0, 0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's tile chunks have landed in LDS
   __syncthreads();
 
   // full tiles in the loop; a ragged tail tile (the only one that needs masking) after it
   const int Tfull = total / BN;
   for (int t = 0; t < Tfull; ++t) {
+    DBG_T(t_e);
+#ifndef ADBG_NOLOAD
+    if (t + 1 < T) issue_loads((t + 1) & 1, (t + 1) & 3);
+#endif
     if (tid < BN && t + 3 < T) ridx[(t + 3) & 3][tid] = row_off((t + 3) * BN + tid);
+    DBG_T(t_f);
     if (wave_has_rows) compute_tile(t & 1, BN, std::false_type{});
-    if (t + 1 < T) store_lds((t + 1) & 1);
-    if (t + 2 < T) issue_loads((t + 2) & 3);
+    DBG_T(t_g);
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+#ifndef ADBG_NOSYNC
     __syncthreads();
+#endif
+#ifdef ADBG_TIMING
+    DBG_T(t_h);
+    dbg_ld += t_f - t_e; dbg_bar += t_h - t_g;
+#endif
   }
+#ifdef ADBG_TIMING
+  if (lane == 0 && wave == 1 && a.dbg) {
+    atomicAdd(&a.dbg[0], (unsigned long long)dbg_s); atomicAdd(&a.dbg[1], (unsigned long long)dbg_sm);
+    atomicAdd(&a.dbg[2], (unsigned long long)dbg_pv); atomicAdd(&a.dbg[3], (unsigned long long)dbg_ld);
+    atomicAdd(&a.dbg[4], (unsigned long long)dbg_bar); atomicAdd(&a.dbg[5], (unsigned long long)Tfull);
+  }
+#endif
   if (T > Tfull && wave_has_rows) compute_tile(Tfull & 1, total - Tfull * BN, std::true_type{});
 
   // O^T accumulator value v of block db is column  db*32 + 8*(v/4) + 4*hb + v%4  of query c
@@ -555,7 +554,10 @@ int launch_attention(hipStream_t s, int dtype, int d, int H, int N, int Cq, int 
                      const int32_t* tiles, const int32_t* ntiles, const int32_t* rng_start,
                      const int32_t* rng_pre, const int32_t* rng_cnt) {
   AttnArgs a{Q, Kp, Vp, O, perm_q, tiles, ntiles, rng_start, rng_pre, rng_cnt, N, Cq, maxtiles, maxr,
-             scale * 1.4426950408889634f};
+             scale * 1.4426950408889634f, nullptr};
+#ifdef ADBG_TIMING
+  a.dbg = g_dbg_host_ptr;
+#endif
   dim3 g((maxtiles + 7) / 8 * 8, H);
   if (dtype == ADACLUSTER_BF16) {
     if (d == 64) attn_mfma<64, A64_QB, A64_NW, A64_MINB><<<g, A64_NW * 64, 0, s>>>(a);

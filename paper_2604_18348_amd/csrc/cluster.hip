@@ -215,7 +215,7 @@ __global__ __launch_bounds__(128) void assign_f32(const float* __restrict__ X, A
 // ------------------------------------------------------------------------------------------
 struct ReduceCfg {
   int mode;            // same meaning as AssignCfg::mode (where m and activity come from)
-  int m_const; int N; int P; int m_bound;
+  int m_const; int N; int P /* upper bound of parts per head = grid.x */; int m_bound;
   const KState* st;
   int normalize;       // rows are scaled to unit length before summing (query clustering)
   int want_box;
@@ -232,6 +232,35 @@ __device__ __forceinline__ bool reduce_setup(const ReduceCfg& c, int h, int& m) 
 // wave takes RPI = 64/LPR rows per step (two steps in flight), and the RPI row slots are merged
 // at the end in a fixed order, so the result does not depend on scheduling.
 // psum [H][m_bound][P][D]; pnorm [H][m_bound][P]; pmin/pmax like psum.
+static constexpr int REDUCE_ROWS = 128;   // rows summed by one wave
+
+// poff[j] = number of parts of the clusters before j (a cluster of n rows has ceil(n/REDUCE_ROWS)
+// parts), j = 0..m.  One block per head.
+__global__ __launch_bounds__(1024) void part_scan(ReduceCfg cfg, const int32_t* __restrict__ offs, int offs_stride,
+                                                  int32_t* __restrict__ poff) {
+  const int h = blockIdx.x, tid = threadIdx.x;
+  int m;
+  if (!reduce_setup(cfg, h, m)) return;
+  const int32_t* of = offs + (size_t)h * offs_stride;
+  int32_t* po = poff + (size_t)h * offs_stride;
+  const int per = (m + 1023) / 1024;
+  const int j0 = tid * per, j1 = min(m, j0 + per);
+  int run = 0;
+  for (int j = j0; j < j1; ++j) run += (of[j + 1] - of[j] + REDUCE_ROWS - 1) / REDUCE_ROWS;
+  __shared__ int32_t sc[1024];
+  sc[tid] = run;
+  __syncthreads();
+  for (int o = 1; o < 1024; o <<= 1) {
+    const int v = tid >= o ? sc[tid - o] : 0;
+    __syncthreads();
+    sc[tid] += v;
+    __syncthreads();
+  }
+  int base = sc[tid] - run;
+  for (int j = j0; j < j1; ++j) { po[j] = base; base += (of[j + 1] - of[j] + REDUCE_ROWS - 1) / REDUCE_ROWS; }
+  if (tid == 1023) po[m] = sc[1023];
+}
+
 template <typename T> struct Vec16;
 template <> struct Vec16<bf16raw> {
   static constexpr int N = 8;
@@ -254,6 +283,7 @@ template <typename T, int D>
 __global__ __launch_bounds__(64) void seg_reduce(const T* __restrict__ X, ReduceCfg cfg,
                                                  const int32_t* __restrict__ perm,
                                                  const int32_t* __restrict__ offs, int offs_stride,
+                                                 const int32_t* __restrict__ poff,
                                                  float* __restrict__ psum, float* __restrict__ pnorm,
                                                  float* __restrict__ pmin, float* __restrict__ pmax) {
   constexpr int EV = Vec16<T>::N;     // elements per 16-byte load
@@ -262,14 +292,17 @@ __global__ __launch_bounds__(64) void seg_reduce(const T* __restrict__ X, Reduce
   const int h = blockIdx.y;
   int m;
   if (!reduce_setup(cfg, h, m)) return;
-  const int j = blockIdx.x / cfg.P, part = blockIdx.x % cfg.P;
-  if (j >= m) return;
+  // part b of this head -> (cluster j, part index): parts of REDUCE_ROWS rows, clusters in order
+  const int32_t* po = poff + (size_t)h * offs_stride;
+  const int b = blockIdx.x;
+  if (b >= po[m]) return;
+  int lo = 0, hi = m - 1;
+  while (lo < hi) { const int mid = (lo + hi + 1) >> 1; if (po[mid] <= b) lo = mid; else hi = mid - 1; }
+  const int j = lo, part = b - po[j];
   const int lane = threadIdx.x, slot = lane / LPR, cl = lane % LPR;
   const int beg = offs[(size_t)h * offs_stride + j], end = offs[(size_t)h * offs_stride + j + 1];
-  const int nj = end - beg;
-  const int chunk = (nj + cfg.P - 1) / cfg.P;
-  const int mb = beg + part * chunk;
-  const int me = min(end, mb + chunk);
+  const int mb = beg + part * REDUCE_ROWS;
+  const int me = min(end, mb + REDUCE_ROWS);
   const int32_t* pm = perm + (size_t)h * cfg.N;
   const T* Xh = X + (size_t)h * cfg.N * D + cl * EV;
   float acc[EV], mn[EV], mx[EV];
@@ -300,17 +333,29 @@ __global__ __launch_bounds__(64) void seg_reduce(const T* __restrict__ X, Reduce
       }
     }
   };
-  // all lanes run the same number of steps (the shuffles above need every lane of a row present)
-  for (int r0 = mb; r0 < me; r0 += 2 * RPI) {
-    const int ra = r0 + slot, rb = r0 + RPI + slot;
-    const bool va = ra < me, vb = rb < me;
-    float xa[EV], xb[EV];
+  // The wave first fetches up to 64 row indices with one coalesced load, then keeps UNR row
+  // gathers in flight per lane.  Every lane runs the same number of steps (the shuffles in
+  // add_row need all lanes of a row present); rows past the end contribute nothing.
+  constexpr int UNR = 4;
+  for (int r0 = mb; r0 < me; r0 += 64) {
+    const int my = r0 + lane;
+    const int idx = my < me ? pm[my] : 0;
+    const int nhere = min(64, me - r0);
+    for (int k0 = 0; k0 < nhere; k0 += UNR * RPI) {
+      float x[UNR][EV];
+      bool valid[UNR];
 #pragma unroll
-    for (int e = 0; e < EV; ++e) { xa[e] = 0.f; xb[e] = 0.f; }
-    if (va) Vec16<T>::load(Xh + (size_t)pm[ra] * D, xa);
-    if (vb) Vec16<T>::load(Xh + (size_t)pm[rb] * D, xb);
-    add_row(xa, va);
-    add_row(xb, vb);
+      for (int u = 0; u < UNR; ++u) {
+        const int k = k0 + u * RPI + slot;            // < 64 + RPI*UNR, but only k < nhere is used
+        valid[u] = k < nhere;
+        const int tok = __shfl(idx, k & 63);
+#pragma unroll
+        for (int e = 0; e < EV; ++e) x[u][e] = 0.f;
+        if (valid[u]) Vec16<T>::load(Xh + (size_t)tok * D, x[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) add_row(x[u], valid[u]);
+    }
   }
   // merge the row slots: slot s+o into slot s, o = RPI/2 ... 1
 #pragma unroll
@@ -324,7 +369,7 @@ __global__ __launch_bounds__(64) void seg_reduce(const T* __restrict__ X, Reduce
     nsum += __shfl_down(nsum, o * LPR);
   }
   if (slot == 0) {
-    const size_t o = (((size_t)h * cfg.m_bound + j) * cfg.P + part);
+    const size_t o = (size_t)h * cfg.P + b;
 #pragma unroll
     for (int e = 0; e < EV; ++e) {
       psum[o * D + cl * EV + e] = acc[e];
@@ -347,7 +392,8 @@ struct FinalizeCfg {
 
 template <int D>
 __global__ __launch_bounds__(64) void finalize_centroids(FinalizeCfg cfg, const int32_t* __restrict__ offs,
-                                                         int offs_stride, const float* __restrict__ psum,
+                                                         int offs_stride, const int32_t* __restrict__ poff,
+                                                         const float* __restrict__ psum,
                                                          const float* __restrict__ pnorm,
                                                          const float* __restrict__ pmin,
                                                          const float* __restrict__ pmax,
@@ -370,12 +416,13 @@ __global__ __launch_bounds__(64) void finalize_centroids(FinalizeCfg cfg, const 
     return;
   }
   const int nj = offs[(size_t)h * offs_stride + j + 1] - offs[(size_t)h * offs_stride + j];
-  const size_t pbase = ((size_t)h * cfg.m_bound + j) * cfg.P;
+  const size_t pbase = (size_t)h * cfg.P;
+  const int p_beg = poff[(size_t)h * offs_stride + j], p_end = poff[(size_t)h * offs_stride + j + 1];
   float s[CPL], mn[CPL], mx[CPL];
 #pragma unroll
   for (int q = 0; q < CPL; ++q) { s[q] = 0.f; mn[q] = INFINITY; mx[q] = -INFINITY; }
   float ns = 0.f;
-  for (int p = 0; p < cfg.P; ++p) {
+  for (int p = p_beg; p < p_end; ++p) {
 #pragma unroll
     for (int q = 0; q < CPL; ++q) {
       s[q] += psum[(pbase + p) * D + lane + 64 * q];
@@ -711,22 +758,24 @@ int launch_assign(hipStream_t s, int dtype, int d, int H, int N, int n_bound, in
 
 int launch_seg_reduce(hipStream_t s, int dtype, int d, int H, int N, int mode, int m_const, int m_bound, int P,
                       const KState* st, int normalize, int want_box, const void* X, const int32_t* perm,
-                      const int32_t* offs, int offs_stride, float* psum, float* pnorm, float* pmin, float* pmax) {
+                      const int32_t* offs, int offs_stride, int32_t* poff, float* psum, float* pnorm, float* pmin,
+                      float* pmax) {
   ReduceCfg c{mode, m_const, N, P, m_bound, st, normalize, want_box};
-  dim3 g(m_bound * P, H);
+  part_scan<<<H, 1024, 0, s>>>(c, offs, offs_stride, poff);
+  dim3 g(P, H);
   if (dtype == ADACLUSTER_BF16) {
-    if (d == 64) seg_reduce<bf16raw, 64><<<g, 64, 0, s>>>((const bf16raw*)X, c, perm, offs, offs_stride, psum, pnorm, pmin, pmax);
-    else seg_reduce<bf16raw, 128><<<g, 64, 0, s>>>((const bf16raw*)X, c, perm, offs, offs_stride, psum, pnorm, pmin, pmax);
+    if (d == 64) seg_reduce<bf16raw, 64><<<g, 64, 0, s>>>((const bf16raw*)X, c, perm, offs, offs_stride, poff, psum, pnorm, pmin, pmax);
+    else seg_reduce<bf16raw, 128><<<g, 64, 0, s>>>((const bf16raw*)X, c, perm, offs, offs_stride, poff, psum, pnorm, pmin, pmax);
   } else {
-    if (d == 64) seg_reduce<float, 64><<<g, 64, 0, s>>>((const float*)X, c, perm, offs, offs_stride, psum, pnorm, pmin, pmax);
-    else seg_reduce<float, 128><<<g, 64, 0, s>>>((const float*)X, c, perm, offs, offs_stride, psum, pnorm, pmin, pmax);
+    if (d == 64) seg_reduce<float, 64><<<g, 64, 0, s>>>((const float*)X, c, perm, offs, offs_stride, poff, psum, pnorm, pmin, pmax);
+    else seg_reduce<float, 128><<<g, 64, 0, s>>>((const float*)X, c, perm, offs, offs_stride, poff, psum, pnorm, pmin, pmax);
   }
   return chk();
 }
 
 int launch_finalize(hipStream_t s, int dtype, int d, int H, int mode, int m_const, int m_bound, int P, int cap,
                     int master_stride, const KState* st, int spherical, int update_assign, int want_box,
-                    const int32_t* offs, int offs_stride, const float* psum, const float* pnorm,
+                    const int32_t* offs, int offs_stride, const int32_t* poff, const float* psum, const float* pnorm,
                     const float* pmin, const float* pmax, float* master, void* assign_lp, float* assign_f32,
                     float* bias, float* out_cent, const float* fallback, int32_t* out_sizes,
                     float* out_mean_norm, float* out_bmin, float* out_bmax) {
@@ -735,11 +784,11 @@ int launch_finalize(hipStream_t s, int dtype, int d, int H, int mode, int m_cons
   // in final mode every row of the output (up to cap) gets a size, so cover cap rows
   dim3 g(update_assign ? m_bound : cap, H);
   if (d == 64)
-    finalize_centroids<64><<<g, 64, 0, s>>>(c, offs, offs_stride, psum, pnorm, pmin, pmax, master, assign_lp,
+    finalize_centroids<64><<<g, 64, 0, s>>>(c, offs, offs_stride, poff, psum, pnorm, pmin, pmax, master, assign_lp,
                                             assign_f32, bias, out_cent, fallback, out_sizes, out_mean_norm,
                                             out_bmin, out_bmax);
   else
-    finalize_centroids<128><<<g, 64, 0, s>>>(c, offs, offs_stride, psum, pnorm, pmin, pmax, master, assign_lp,
+    finalize_centroids<128><<<g, 64, 0, s>>>(c, offs, offs_stride, poff, psum, pnorm, pmin, pmax, master, assign_lp,
                                              assign_f32, bias, out_cent, fallback, out_sizes, out_mean_norm,
                                              out_bmin, out_bmax);
   return chk();

@@ -27,10 +27,10 @@ int launch_assign(hipStream_t s, int dtype, int d, int H, int N, int n_bound, in
                   int32_t* labels, float* dist2);
 int launch_seg_reduce(hipStream_t s, int dtype, int d, int H, int N, int mode, int m_const, int m_bound, int P,
                       const KState* st, int normalize, int want_box, const void* X, const int32_t* perm,
-                      const int32_t* offs, int offs_stride, float* psum, float* pnorm, float* pmin, float* pmax);
+                      const int32_t* offs, int offs_stride, int32_t* poff, float* psum, float* pnorm, float* pmin, float* pmax);
 int launch_finalize(hipStream_t s, int dtype, int d, int H, int mode, int m_const, int m_bound, int P, int cap,
                     int master_stride, const KState* st, int spherical, int update_assign, int want_box,
-                    const int32_t* offs, int offs_stride, const float* psum, const float* pnorm,
+                    const int32_t* offs, int offs_stride, const int32_t* poff, const float* psum, const float* pnorm,
                     const float* pmin, const float* pmax, float* master, void* assign_lp, float* assign_f32,
                     float* bias, float* out_cent, const float* fallback, int32_t* out_sizes,
                     float* out_mean_norm, float* out_bmin, float* out_bmax);

@@ -43,18 +43,26 @@ __global__ __launch_bounds__(64) void radix_count(const int32_t* __restrict__ la
   out[lane] = cnt[lane]; out[lane + 64] = cnt[lane + 64];
 }
 
-// exclusive scan: bins major, segments minor -> first output position per (segment, bin)
-__global__ __launch_bounds__(RBINS) void radix_scan(int nseg, int32_t* __restrict__ hist) {
-  const int h = blockIdx.x, b = threadIdx.x;
+// exclusive scan: bins major, segments minor -> first output position per (segment, bin).
+// 8 groups of 128 threads each scan a contiguous eighth of the segments, then the groups are chained.
+__global__ __launch_bounds__(8 * RBINS) void radix_scan(int nseg, int32_t* __restrict__ hist) {
+  const int h = blockIdx.x, b = threadIdx.x & (RBINS - 1), g = threadIdx.x >> RBITS;
   int32_t* hh = hist + (size_t)h * nseg * RBINS;
+  const int per = (nseg + 7) / 8;
+  const int s0 = g * per, s1 = min(nseg, s0 + per);
   int run = 0;
-  for (int s = 0; s < nseg; ++s) { int c = hh[s * RBINS + b]; hh[s * RBINS + b] = run; run += c; }
+  for (int s = s0; s < s1; ++s) { const int c = hh[s * RBINS + b]; hh[s * RBINS + b] = run; run += c; }
+  __shared__ int32_t gsum[8][RBINS];
   __shared__ int32_t tot[RBINS];
-  tot[b] = run;
+  gsum[g][b] = run;
   __syncthreads();
-  int base = 0;
+  int before = 0, all = 0;
+  for (int i = 0; i < 8; ++i) { const int v = gsum[i][b]; if (i < g) before += v; all += v; }
+  if (g == 0) tot[b] = all;
+  __syncthreads();
+  int base = before;
   for (int i = 0; i < b; ++i) base += tot[i];
-  for (int s = 0; s < nseg; ++s) hh[s * RBINS + b] += base;
+  for (int s = s0; s < s1; ++s) hh[s * RBINS + b] += base;
 }
 
 // scatter one pass: (label, value) pairs move to their stable sorted position
@@ -138,7 +146,7 @@ int launch_sort(hipStream_t st, int H, int N, int n_bound, int m_bound,
     int32_t* lout = last ? sc.lab_b : sc.lab_a;
     int32_t* vout = last ? perm : sc.val_a;
     radix_count<<<g, 64, 0, st>>>(lin, N, ps * RBITS, a, nseg, sc.hist);
-    radix_scan<<<H, RBINS, 0, st>>>(nseg, sc.hist);
+    radix_scan<<<H, 8 * RBINS, 0, st>>>(nseg, sc.hist);
     radix_scatter<<<g, 64, 0, st>>>(lin, vin, N, ps * RBITS, a, nseg, sc.hist, lout, vout);
     lin = lout; vin = vout;
   }
