@@ -84,9 +84,12 @@ __global__ __launch_bounds__(256) void assign_mfma(const bf16raw* __restrict__ X
     xn2[pb] = ss + __shfl_xor(ss, 32);
   }
 
-  float best[PB]; int bidx[PB];
+  // Running arg-max with the position inside a 32x32 accumulator tile carried in the low 4
+  // mantissa bits of the score (a 2^-19 relative perturbation, far below the near-tie margin):
+  // one and-or per value, then a max3 tree, then one compare per tile.
+  float best[PB]; int btile[PB];
 #pragma unroll
-  for (int pb = 0; pb < PB; ++pb) { best[pb] = -INFINITY; bidx[pb] = 0; }
+  for (int pb = 0; pb < PB; ++pb) { best[pb] = -INFINITY; btile[pb] = 0; }
 
   const bf16raw* ch = cent + ((size_t)h * cfg.cap + row_off) * D;
   const float* bh = bias + (size_t)h * cfg.cap + row_off;
@@ -101,7 +104,7 @@ __global__ __launch_bounds__(256) void assign_mfma(const bf16raw* __restrict__ X
       if (c0 + r < m) v = *reinterpret_cast<const uint4*>(ch + (size_t)(c0 + r) * D + q * 8);
       *reinterpret_cast<uint4*>(&cs[r * LDW + q * 8]) = v;
     }
-    if (tid < CB) bs[tid] = (c0 + tid < m) ? bh[c0 + tid] : -INFINITY;
+    if (tid < CB) bs[tid] = (c0 + tid < m) ? bh[c0 + tid] : -3.0e38f;   // finite: survives the bit packing
     __syncthreads();
     const int rbmax = min(CB / 32, (m - c0 + 31) / 32);
     for (int rb = 0; rb < rbmax; ++rb) {
@@ -122,26 +125,32 @@ __global__ __launch_bounds__(256) void assign_mfma(const bf16raw* __restrict__ X
         for (int pb = 0; pb < PB; ++pb)
           acc[pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xf[pb][ks], acc[pb], 0, 0, 0);
       }
-      const int idx0 = c0 + rb * 32 + 4 * hb;
+      const int tile_id = (c0 >> 5) + rb;
 #pragma unroll
       for (int pb = 0; pb < PB; ++pb) {
+        float pk[16];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const float val = acc[pb][v];
-          const int idx = idx0 + 8 * (v >> 2) + (v & 3);
-          if (val > best[pb]) { best[pb] = val; bidx[pb] = idx; }
-        }
+        for (int v = 0; v < 16; ++v) pk[v] = __uint_as_float((__float_as_uint(acc[pb][v]) & 0xFFFFFFF0u) | (uint32_t)(15 - v));
+        float tm = fmaxf(fmaxf(pk[0], pk[1]), pk[2]);
+#pragma unroll
+        for (int v = 3; v < 15; v += 2) tm = fmaxf(fmaxf(tm, pk[v]), pk[v + 1]);
+        tm = fmaxf(tm, pk[15]);
+        if (tm > best[pb]) { best[pb] = tm; btile[pb] = tile_id; }
       }
     }
   }
 #pragma unroll
   for (int pb = 0; pb < PB; ++pb) {
-    const float ob = __shfl_xor(best[pb], 32);
-    const int oi = __shfl_xor(bidx[pb], 32);
-    if (ob > best[pb] || (ob == best[pb] && oi < bidx[pb])) { best[pb] = ob; bidx[pb] = oi; }
+    // accumulator value v of a tile is centre  32*tile + 8*(v/4) + 4*hb + v%4
+    const int v = 15 - (int)(__float_as_uint(best[pb]) & 15u);   // 15-v was packed: equal scores >= 0 go to the lowest centre
+    int bidx = btile[pb] * 32 + 8 * (v >> 2) + 4 * hb + (v & 3);
+    float bv = __uint_as_float(__float_as_uint(best[pb]) & 0xFFFFFFF0u);
+    const float ob = __shfl_xor(bv, 32);
+    const int oi = __shfl_xor(bidx, 32);
+    if (ob > bv || (ob == bv && oi < bidx)) { bv = ob; bidx = oi; }
     if (hb == 0 && pos[pb] < n) {
-      labels[(size_t)h * cfg.N + pos[pb]] = bidx[pb];
-      if (dist2) dist2[(size_t)h * cfg.N + pos[pb]] = fmaxf(xn2[pb] - 2.f * best[pb], 0.f);
+      labels[(size_t)h * cfg.N + pos[pb]] = bidx;
+      if (dist2) dist2[(size_t)h * cfg.N + pos[pb]] = fmaxf(xn2[pb] - 2.f * bv, 0.f);
     }
   }
 }

@@ -56,7 +56,9 @@ def euclid_label_mismatches(X, C, labels_gpu):
     gap = G[bad, labels_gpu[bad]] - G[bad, ref[bad]]
     scale = xn[bad] + cn[labels_gpu[bad]]
     hard = int((gap > REL_TIE * scale).sum())
-    return int(bad.size), hard
+    # exact ties (duplicate centres) may go either way: they are not counted as mismatches
+    exact = int((gap <= 1e-12 * scale).sum())
+    return int(bad.size) - exact, hard
 
 
 def cosine_label_mismatches(Q, C, labels_gpu):
