@@ -524,8 +524,8 @@ __global__ __launch_bounds__(64) void attn_f32(AttnArgs a) {
 #endif
 #ifndef A128_QB
 #define A128_QB 1
-#define A128_NW 8
-#define A128_MINB 1
+#define A128_NW 4
+#define A128_MINB 2
 #endif
 
 int attn_block_rows(int dtype, int d) {
