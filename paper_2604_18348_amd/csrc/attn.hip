@@ -518,7 +518,7 @@ __global__ __launch_bounds__(64) void attn_f32(AttnArgs a) {
 // ------------------------------------------------------------------------------------------
 // tile shapes of the bf16 kernel: queries per wave = 32*QB, waves per block NW, blocks per CU MINB
 #ifndef A64_QB
-#define A64_QB 2
+#define A64_QB 1
 #define A64_NW 4
 #define A64_MINB 2
 #endif
