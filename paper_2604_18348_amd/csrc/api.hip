@@ -217,8 +217,9 @@ int run_qcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
 int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const void* K, int32_t* k_labels,
                  float* k_centroids, float* k_assign, float* k_bmin, float* k_bmax, int32_t* k_sizes,
                  int32_t* k_count, int32_t* full_flag, int32_t* k_stage_offs, int32_t* k_stage_of,
-                 float* tau_used) {
+                 float* tau_used, int* kc_bound_out) {
   const Dims D = dims_of(p);
+  int kc_bound = 0;   // sum over stages of the largest stage centre count: an upper bound of every |C|
   const int u_min = (int)floor((double)p->min_unassigned_frac * (double)p->N);
   RET_IF(launch_kstate_init(st, w.kstate, D.H, D.N));
   if (k_stage_of) RET_IF(launch_fill_i32(st, k_stage_of, (size_t)D.H * D.N, -1));
@@ -232,6 +233,7 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
       return fail(ADACLUSTER_E_INTERNAL, "stage read-back failed: %s", hipGetErrorString(hipGetLastError()));
     const int n_active = summ[0], n_bound = summ[1], m_bound = summ[2];
     if (n_active == 0) break;
+    kc_bound += m_bound;
     const int32_t* ul = (t == 0) ? nullptr : w.ulist[t & 1];
     int32_t* ul_next = w.ulist[(t + 1) & 1];
     RET_IF(launch_init_centroids(st, p->dtype, D.d, D.H, D.N, 1, 0, m_bound, w.kstate, ul, 0, 0, D.cap, p->k_m0, K,
@@ -256,6 +258,7 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
     RET_IF(launch_filter(st, w.kstate, D.H, D.N, n_bound, w.dist2, w.tau, w.blockcnt, w.u_prev, ul, ul_next,
                          k_stage_of, t));
   }
+  if (kc_bound_out) *kc_bound_out = kc_bound < D.cap ? kc_bound : D.cap;
   RET_IF(launch_kstate_export(st, w.kstate, D.H, k_count, full_flag, k_stage_offs));
   if (tau_used && hipMemcpyAsync(tau_used, w.tau, 4, hipMemcpyDeviceToDevice, st) != hipSuccess)
     return fail(ADACLUSTER_E_INTERNAL, "tau copy failed");
@@ -341,7 +344,7 @@ int adacluster_kcluster(const adacluster_params* p, const void* K, int32_t* k_la
   WS w;
   if ((rc = check_ws(p, ws, ws_bytes, &w))) return rc;
   return run_kcluster(p, w, (hipStream_t)stream, K, k_labels, k_centroids, k_assign_centroids, k_box_min, k_box_max,
-                      k_sizes, k_count, full_flag, k_stage_offs, k_stage_of, tau_used);
+                      k_sizes, k_count, full_flag, k_stage_offs, k_stage_of, tau_used, nullptr);
 }
 
 int adacluster_select(const adacluster_params* p, const float* q_centroids, const float* q_mean_norm,
@@ -359,7 +362,7 @@ int adacluster_select(const adacluster_params* p, const float* q_centroids, cons
   const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->d);
   RET_IF(launch_select((hipStream_t)stream, p->H, p->q_clusters, capacity(p), p->d, p->score_mode, p->select_mode,
                        p->topk, p->top_p, scale, q_centroids, q_mean_norm, k_centroids, k_box_min, k_box_max, k_sizes,
-                       k_count, full_flag, sel_idx, sel_cnt));
+                       k_count, full_flag, sel_idx, sel_cnt, capacity(p)));
   return 0;
 }
 
@@ -413,14 +416,15 @@ int adacluster_attn(const adacluster_params* p, const void* Q, const void* K, co
   prof_begin(st);
   if ((rc = run_qcluster(p, w, st, Q, q_labels, q_centroids, q_assign_centroids, q_sizes, q_mean_norm))) return rc;
   prof_mark(EV_QCLUSTER, st);
+  int kc_bound = capacity(p);
   if ((rc = run_kcluster(p, w, st, K, k_labels, k_centroids, k_assign_centroids, k_bmin, k_bmax, k_sizes, k_count,
-                         full_flag, o.k_stage_offs, o.k_stage_of, tau_used)))
+                         full_flag, o.k_stage_offs, o.k_stage_of, tau_used, &kc_bound)))
     return rc;
   prof_mark(EV_KCLUSTER, st);
   const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->d);
   RET_IF(launch_select(st, p->H, p->q_clusters, capacity(p), p->d, p->score_mode, p->select_mode, p->topk, p->top_p,
                        scale, q_centroids, q_mean_norm, k_centroids, k_bmin, k_bmax, k_sizes, k_count, full_flag,
-                       sel_idx, sel_cnt));
+                       sel_idx, sel_cnt, kc_bound));
   prof_mark(EV_SELECT, st);
   // both label sorts were left in the workspace by the clustering steps
   return run_attention(p, w, st, Q, K, V, O, k_count, sel_idx, sel_cnt);

@@ -13,7 +13,7 @@
 namespace adac {
 
 struct SelectCfg {
-  int Cq, cap, d;
+  int Cq, cap, d, lds_cap;
   int score_mode, select_mode, topk;
   double top_p, scale;
 };
@@ -53,8 +53,8 @@ __global__ __launch_bounds__(256) void select_kernel(SelectCfg cfg, const float*
 #pragma clang fp contract(off)
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   double* sval = reinterpret_cast<double*>(smem);                        // [cap] score, then weight
-  uint64_t* skey = reinterpret_cast<uint64_t*>(smem + (size_t)cfg.cap * 8);   // [cap]
-  int32_t* sflag = reinterpret_cast<int32_t*>(smem + (size_t)cfg.cap * 16);   // [cap]
+  uint64_t* skey = reinterpret_cast<uint64_t*>(smem + (size_t)cfg.lds_cap * 8);   // [lds_cap]
+  int32_t* sflag = reinterpret_cast<int32_t*>(smem + (size_t)cfg.lds_cap * 16);   // [lds_cap]
   __shared__ double qrow[128];
   __shared__ int32_t wsum[4];
   __shared__ int32_t s_take;
@@ -62,7 +62,7 @@ __global__ __launch_bounds__(256) void select_kernel(SelectCfg cfg, const float*
 
   const int h = blockIdx.y, i = blockIdx.x, tid = threadIdx.x;
   const int d = cfg.d;
-  const int kc = k_count[h];
+  const int kc = min(k_count[h], cfg.lds_cap);
   const bool all = full_flag[h] != 0;
   if (tid < d) qrow[tid] = (double)q_cent[((size_t)h * cfg.Cq + i) * d + tid];
   __syncthreads();
@@ -198,9 +198,12 @@ __global__ __launch_bounds__(256) void select_kernel(SelectCfg cfg, const float*
 int launch_select(hipStream_t s, int H, int Cq, int cap, int d, int score_mode, int select_mode, int topk,
                   float top_p, float scale, const float* q_cent, const float* q_mean_norm, const float* k_cent,
                   const float* k_bmin, const float* k_bmax, const int32_t* k_sizes, const int32_t* k_count,
-                  const int32_t* full_flag, int32_t* sel_idx, int32_t* sel_cnt) {
-  SelectCfg c{Cq, cap, d, score_mode, select_mode, topk, (double)top_p, (double)scale};
-  const size_t shm = (size_t)cap * 20;
+                  const int32_t* full_flag, int32_t* sel_idx, int32_t* sel_cnt, int kc_max) {
+  // kc_max: an upper bound of k_count[h] known to the host; it sizes the LDS arrays (and with
+  // them the number of workgroups a CU can hold)
+  const int lds_cap = kc_max < cap ? (kc_max + 63) / 64 * 64 : cap;
+  SelectCfg c{Cq, cap, d, lds_cap, score_mode, select_mode, topk, (double)top_p, (double)scale};
+  const size_t shm = (size_t)lds_cap * 20;
   if (shm > 150 * 1024) return ADACLUSTER_E_BADSHAPE;
   hipError_t e = hipFuncSetAttribute((const void*)select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
   if (e != hipSuccess) return ADACLUSTER_E_INTERNAL;
