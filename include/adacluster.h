@@ -65,6 +65,9 @@ typedef struct adacluster_params {
   int32_t q_iters;              /* assignment passes of the query k-means (>= 1)                */
   int32_t k_iters;              /* assignment passes of each key k-means stage (>= 1)           */
   int32_t q_init_mode;          /* 0: strided sample of the queries; 1: q_centroids passed in   */
+  int32_t k_init_mode;          /* 0: Algorithm 1 from scratch; 1: warm start (Sec. 3.2.2,
+                                   "Efficient initialization"): cluster count fixed, previous centres
+                                   passed in k_centroids / k_count / full_flag, k_iters passes    */
   int32_t k_m0;                 /* key centres of the first stage ("Initial K", paper: 100)     */
   int32_t k_m_min;              /* floor for the centre count of later stages                   */
   int32_t k_max_clusters;       /* N_max of Alg. 1.  Centre buffers hold cap = N_max + k_m0 rows */
@@ -121,6 +124,10 @@ int adacluster_qcluster(const adacluster_params* p, const void* Q,
  *                                 unused entries = k_count; may be NULL
  *   k_stage_of         [H,N]      out  stage at which a token fell within tau (-1: never); may be NULL
  *   tau_used           [1]        out  the threshold applied (tau_abs, or the derived value)
+ * Warm start (k_init_mode 1): k_centroids (rows < k_count), k_count and full_flag are INPUTS as left
+ * by a previous call; the centre count stays fixed, k_iters assignment passes start from those
+ * centres, no token is staged (k_stage_of = 0 everywhere, one stage), full_flag and tau_used are
+ * passed through unchanged; every other output is produced as above.
  */
 int adacluster_kcluster(const adacluster_params* p, const void* K,
                         int32_t* k_labels, float* k_centroids, float* k_assign_centroids,

@@ -273,6 +273,17 @@ def multistage_kmeans(K, tau, n_max, m0, m_min=1, n_iters=3, max_stages=10,
                 stage_of=stage_of, n_unassigned=np.asarray(n_un, dtype=np.int64))
 
 
+def warm_key_clustering(K, prev_centroids, n_iters, round_fn=None):
+    """Later denoising steps (Sec. 3.2.2, "Efficient initialization"): the number of clusters is
+    fixed, the previous step's centres initialise k-means, `n_iters` assignment passes are run.
+    Returns the same fields as multistage_kmeans (one stage, nothing staged)."""
+    K = np.asarray(K, dtype=F64)
+    prev = np.asarray(prev_centroids, dtype=F64)
+    labels, Ca, _ = euclid_kmeans(K, prev.shape[0], n_iters, init_centroids=prev, round_fn=round_fn)
+    cent, sizes, bmin, bmax = finalize_key_clusters(K, labels, Ca)
+    return dict(labels=labels, assign_centroids=Ca, centroids=cent, sizes=sizes, box_min=bmin, box_max=bmax)
+
+
 def finalize_key_clusters(K, labels, assign_centroids):
     """Member means, sizes and boxes for given labels (second half of Alg. 1's output)."""
     K = np.asarray(K, dtype=F64)

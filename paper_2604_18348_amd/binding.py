@@ -26,7 +26,7 @@ class CParams(ctypes.Structure):
     _fields_ = [("H", ctypes.c_int32), ("N", ctypes.c_int32), ("d", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("q_clusters", ctypes.c_int32),
                 ("q_iters", ctypes.c_int32), ("k_iters", ctypes.c_int32),
-                ("q_init_mode", ctypes.c_int32), ("k_m0", ctypes.c_int32),
+                ("q_init_mode", ctypes.c_int32), ("k_init_mode", ctypes.c_int32), ("k_m0", ctypes.c_int32),
                 ("k_m_min", ctypes.c_int32), ("k_max_clusters", ctypes.c_int32),
                 ("k_max_stages", ctypes.c_int32), ("tau_abs", ctypes.c_float),
                 ("tau_factor", ctypes.c_float), ("min_unassigned_frac", ctypes.c_float),
@@ -53,6 +53,7 @@ class Params:
     q_iters: int = 3
     k_iters: int = 3
     q_init_mode: int = 0
+    k_init_mode: int = 0
     k_m0: int = 100
     k_m_min: int = 16
     k_max_clusters: int = 1024
@@ -197,7 +198,8 @@ def adacluster_qcluster(p: Params, Q, q_centroids_init=None, ws=None):
     return out
 
 
-def adacluster_kcluster(p: Params, K, want_box=True, ws=None):
+def adacluster_kcluster(p: Params, K, want_box=True, ws=None, prev=None):
+    """`prev` (warm start, k_init_mode 1): dict with k_centroids, k_count, full_flag of an earlier call."""
     _check_qkv(p, K)
     dev = K.device
     ws = workspace(p, dev) if ws is None else ws
@@ -214,7 +216,11 @@ def adacluster_kcluster(p: Params, K, want_box=True, ws=None):
         full_flag=torch.empty((p.H,), dtype=i32, device=dev),
         k_stage_offs=torch.empty((p.H, MAX_STAGES + 1), dtype=i32, device=dev),
         k_stage_of=torch.empty((p.H, p.N), dtype=i32, device=dev),
-        tau_used=torch.empty((1,), dtype=f32, device=dev))
+        tau_used=torch.zeros((1,), dtype=f32, device=dev))
+    if prev is not None:
+        out["k_centroids"] = prev["k_centroids"].clone()
+        out["k_count"] = prev["k_count"].clone()
+        out["full_flag"] = prev["full_flag"].clone()
     cp = p.c()
     _check(load_library().adacluster_kcluster(
         ctypes.byref(cp), _ptr(K), _ptr(out["k_labels"]), _ptr(out["k_centroids"]),

@@ -53,6 +53,7 @@ int check_params(const adacluster_params* p) {
   if (p->q_clusters > 4096) return fail(ADACLUSTER_E_BADSHAPE, "q_clusters must be <= 4096");
   if (p->q_iters < 1 || p->k_iters < 1) return fail(ADACLUSTER_E_BADARG, "q_iters and k_iters must be >= 1");
   if (p->q_init_mode != 0 && p->q_init_mode != 1) return fail(ADACLUSTER_E_BADARG, "q_init_mode must be 0 or 1");
+  if (p->k_init_mode != 0 && p->k_init_mode != 1) return fail(ADACLUSTER_E_BADARG, "k_init_mode must be 0 or 1");
   if (p->k_m0 < 1 || p->k_m0 > p->N) return fail(ADACLUSTER_E_BADSHAPE, "k_m0 must be in [1,N]");
   if (p->k_m_min < 1 || p->k_m_min > p->k_m0) return fail(ADACLUSTER_E_BADARG, "k_m_min must be in [1,k_m0]");
   if (p->k_max_clusters < 1) return fail(ADACLUSTER_E_BADARG, "k_max_clusters must be >= 1");
@@ -220,6 +221,30 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
                  float* tau_used, int* kc_bound_out) {
   const Dims D = dims_of(p);
   int kc_bound = 0;   // sum over stages of the largest stage centre count: an upper bound of every |C|
+  if (p->k_init_mode == 1) {
+    // warm start: one pseudo-stage over all tokens with the previous centres, count fixed
+    RET_IF(launch_kstate_warm(st, w.kstate, D.H, D.N, D.cap, k_count, full_flag));
+    if (k_stage_of) RET_IF(launch_fill_i32(st, k_stage_of, (size_t)D.H * D.N, 0));
+    RET_IF(launch_init_centroids(st, p->dtype, D.d, D.H, D.N, 1, 0, D.cap, w.kstate, nullptr, 0, 1, D.cap, D.cap, K,
+                                 k_centroids, w.cent_lp, k_assign, w.bias));
+    const int Pw = parts_for(D.N, D.cap);
+    for (int it = 0; it < p->k_iters; ++it) {
+      RET_IF(launch_assign(st, p->dtype, D.d, D.H, D.N, D.N, 1, 0, D.cap, w.kstate, nullptr, K, w.cent_lp, w.bias,
+                           k_labels, nullptr));
+      if (it < p->k_iters - 1) {
+        RET_IF(launch_sort(st, D.H, D.N, D.N, D.cap, k_labels, nullptr, nullptr, 0, &w.kstate->m_t, sizeof(KState) / 4,
+                           nullptr, 0, w.perm_tmp, w.offs_tmp, D.capmax + 1, w.sort));
+        RET_IF(launch_seg_reduce(st, p->dtype, D.d, D.H, D.N, 1, 0, D.cap, Pw, w.kstate, 0, 0, K, w.perm_tmp,
+                                 w.offs_tmp, D.capmax + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax));
+        RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 1, 0, D.cap, Pw, D.cap, D.cap, w.kstate, 0, 1, 0, w.offs_tmp,
+                               D.capmax + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax, k_centroids, w.cent_lp,
+                               k_assign, w.bias, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr));
+      }
+    }
+    RET_IF(launch_kstate_commit(st, w.kstate, D.H));
+    if (kc_bound_out) *kc_bound_out = D.cap;
+    RET_IF(launch_kstate_export(st, w.kstate, D.H, k_count, full_flag, k_stage_offs));
+  } else {
   const int u_min = (int)floor((double)p->min_unassigned_frac * (double)p->N);
   RET_IF(launch_kstate_init(st, w.kstate, D.H, D.N));
   if (k_stage_of) RET_IF(launch_fill_i32(st, k_stage_of, (size_t)D.H * D.N, -1));
@@ -265,6 +290,7 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
   // last step of Algorithm 1: nearest centre among all stage centres, then member statistics
   RET_IF(launch_assign(st, p->dtype, D.d, D.H, D.N, D.N, 2, 0, D.cap, w.kstate, nullptr, K, w.cent_lp, w.bias,
                        k_labels, nullptr));
+  }
   RET_IF(launch_sort(st, D.H, D.N, D.N, D.cap, k_labels, nullptr, nullptr, 0, &w.kstate->ccount, sizeof(KState) / 4,
                      nullptr, 0, w.perm_k, w.offs_k, D.cap + 1, w.sort));
   const int want_box = (k_bmin && k_bmax) ? 1 : 0;
@@ -413,6 +439,8 @@ int adacluster_attn(const adacluster_params* p, const void* Q, const void* K, co
   hipStream_t st = (hipStream_t)stream;
   if (p->q_init_mode == 1 && !o.q_centroids)
     return fail(ADACLUSTER_E_BADARG, "attn: q_init_mode 1 needs outs->q_centroids");
+  if (p->k_init_mode == 1 && (!o.k_centroids || !o.k_count || !o.full_flag))
+    return fail(ADACLUSTER_E_BADARG, "attn: k_init_mode 1 needs outs->k_centroids, k_count and full_flag");
   prof_begin(st);
   if ((rc = run_qcluster(p, w, st, Q, q_labels, q_centroids, q_assign_centroids, q_sizes, q_mean_norm))) return rc;
   prof_mark(EV_QCLUSTER, st);

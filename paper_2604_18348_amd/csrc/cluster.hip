@@ -577,6 +577,25 @@ __global__ void kstate_init(KState* st, int H, int N) {
   st[h] = s;
 }
 
+// Warm start (Sec. 3.2.2, "Efficient initialization"): one stage over all tokens, centre count given.
+__global__ void kstate_warm(KState* st, int H, int N, int cap, const int32_t* __restrict__ k_count,
+                            const int32_t* __restrict__ full_flag) {
+  const int h = blockIdx.x * blockDim.x + threadIdx.x;
+  if (h >= H) return;
+  KState s;
+  s.ucount = N; s.ccount = 0; s.m_t = max(1, min(min(k_count[h], cap), N)); s.stage = 0; s.done = 0;
+  s.full = full_flag[h] != 0; s.active = 1; s.pad = 0;
+  for (int i = 0; i <= ADACLUSTER_MAX_STAGES; ++i) s.stage_offs[i] = 0;
+  st[h] = s;
+}
+__global__ void kstate_commit(KState* st, int H) {
+  const int h = blockIdx.x * blockDim.x + threadIdx.x;
+  if (h >= H) return;
+  KState s = st[h];
+  s.ccount = s.m_t; s.stage = 1; s.stage_offs[1] = s.ccount; s.ucount = 0; s.active = 0; s.done = 1;
+  st[h] = s;
+}
+
 // Head of the while-loop of Algorithm 1: U empty? |C| >= N_max (flag F)?  stage / leftover limits?
 // then the centre count m_t of the next stage.  summary = {active heads, max |U|, max m_t}.
 __global__ void kstage_begin(KState* st, int H, int N, int n_max, int m0, int m_min, int max_stages,
@@ -821,6 +840,17 @@ int launch_init_centroids(hipStream_t s, int dtype, int d, int H, int N, int mod
 
 int launch_kstate_init(hipStream_t s, KState* st, int H, int N) {
   kstate_init<<<(H + 63) / 64, 64, 0, s>>>(st, H, N);
+  return chk();
+}
+
+int launch_kstate_warm(hipStream_t s, KState* st, int H, int N, int cap, const int32_t* k_count,
+                       const int32_t* full_flag) {
+  kstate_warm<<<(H + 63) / 64, 64, 0, s>>>(st, H, N, cap, k_count, full_flag);
+  return chk();
+}
+
+int launch_kstate_commit(hipStream_t s, KState* st, int H) {
+  kstate_commit<<<(H + 63) / 64, 64, 0, s>>>(st, H);
   return chk();
 }
 

@@ -39,6 +39,8 @@ int launch_init_centroids(hipStream_t s, int dtype, int d, int H, int N, int mod
                           int master_stride, const void* X, float* master, void* assign_lp, float* assign_f32,
                           float* bias);
 int launch_kstate_init(hipStream_t s, KState* st, int H, int N);
+int launch_kstate_warm(hipStream_t s, KState* st, int H, int N, int cap, const int32_t* k_count, const int32_t* full_flag);
+int launch_kstate_commit(hipStream_t s, KState* st, int H);
 int launch_kstage_begin(hipStream_t s, KState* st, int H, int N, int n_max, int m0, int m_min, int max_stages,
                         int u_min, int32_t* summary);
 int launch_tau(hipStream_t s, int H, int N, const float* dist2, double* part, float factor, float tau_abs,

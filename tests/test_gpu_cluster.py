@@ -203,3 +203,45 @@ def test_kcluster_fp32_stage_centres_follow_the_oracle_trajectory():
     assert np.allclose(to_np(out["k_assign_centroids"])[0, :kc], ref["assign_centroids"], atol=1e-4)
     assert float((out["k_labels"].cpu().numpy()[0] == ref["labels"]).mean()) > 0.999
     assert bool(out["full_flag"][0]) == ref["full_flag"]
+
+
+@pytest.mark.parametrize("dtype,d", [(B.BF16, 64), (B.BF16, 128), (B.F32, 64)])
+def test_kcluster_warm_start_chained(dtype, d):
+    """Warm start: count fixed, previous centres as the start, k_iters passes; labels are the
+    arg-min to the reported centres, centroids the member means, and the centres follow the
+    oracle's Lloyd trajectory from the same start."""
+    H, N = 2, 2500
+    _, K, _ = wl.make_small(41, N, d, 14, dtype=dt_name(dtype), H=H)
+    p = B.Params(H=H, N=N, d=d, dtype=dtype, q_clusters=8, k_iters=3, k_m0=20, k_m_min=4, k_max_clusters=80,
+                 tau_factor=1.5, min_unassigned_frac=0.03)
+    cold = B.adacluster_kcluster(p, to_dev(K, dtype))
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    K2 = K + 0.05 * rng.standard_normal(K.shape).astype(np.float32)          # the next denoising step
+    if dtype == B.BF16:
+        K2 = wl.round_bf16_f32(K2)
+    pw = B.Params(**{**p.__dict__, "k_init_mode": 1, "k_iters": 2})
+    warm = B.adacluster_kcluster(pw, to_dev(K2, dtype), prev=cold)
+    torch.cuda.synchronize()
+    kc = cold["k_count"].cpu().numpy()
+    assert np.array_equal(warm["k_count"].cpu().numpy(), kc)
+    assert np.array_equal(warm["full_flag"].cpu().numpy(), cold["full_flag"].cpu().numpy())
+    assert int(warm["k_stage_of"].max()) == 0 and int(warm["k_stage_of"].min()) == 0
+    rf = orc.round_to_bf16 if dtype == B.BF16 else None
+    for h in range(H):
+        Kh = K2[h].astype(np.float64)
+        C = to_np(warm["k_assign_centroids"])[h, :kc[h]]
+        lab = warm["k_labels"].cpu().numpy()[h]
+        total, hard = euclid_label_mismatches(Kh, C, lab)
+        assert hard == 0 and total <= 3
+        cref, sref, mnref, mxref = orc.finalize_key_clusters(Kh, lab, C)
+        assert np.array_equal(warm["k_sizes"].cpu().numpy()[h, :kc[h]], sref)
+        assert np.allclose(to_np(warm["k_centroids"])[h, :kc[h]], cref, atol=2e-5, rtol=1e-5)
+        assert np.array_equal(to_np(warm["k_box_min"])[h, :kc[h]], mnref)
+        ref = orc.warm_key_clustering(Kh, to_np(cold["k_centroids"])[h, :kc[h]], 2, round_fn=rf)
+        agree = float((ref["labels"] == lab).mean())
+        close = float(np.isclose(ref["assign_centroids"], C, atol=2e-2 if dtype == B.BF16 else 1e-4).mean())
+        print("warm", dt_name(dtype), d, "head", h, "label agreement", agree, "centres close", close)
+        # free-running comparison: bf16 centre rounding can flip near-tied tokens between
+        # neighbouring centres, so only broad agreement is required here (the chained checks above are exact)
+        assert agree > (0.95 if dtype == B.BF16 else 0.999) and close > (0.95 if dtype == B.BF16 else 0.999)

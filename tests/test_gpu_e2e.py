@@ -115,3 +115,29 @@ def test_stagewise_calls_equal_the_fused_call():
     O_steps = B.adacluster_sparse_attn(p, Qd, Kd, Vd, q["q_labels"], k["k_labels"], k["k_count"], si, sc)
     torch.cuda.synchronize()
     assert torch.equal(O_fused, O_steps)
+
+
+def test_fused_warm_start_call_chained():
+    """A second call with q_init_mode = k_init_mode = 1 reuses the first call's centres."""
+    H, N, d = 2, 2400, 64
+    Q, K, V = wl.make_small(33, N, d, 16, dtype="bf16", H=H)
+    p = B.Params(H=H, N=N, d=d, dtype=B.BF16, q_clusters=11, k_m0=20, k_m_min=4, k_max_clusters=80, topk=5,
+                 min_unassigned_frac=0.03)
+    outs = B.alloc_outputs(p, "cuda")
+    B.adacluster_attn(p, to_dev(Q, B.BF16), to_dev(K, B.BF16), to_dev(V, B.BF16), outs=outs)
+    kc0 = outs["k_count"].cpu().numpy().copy()
+    rng = np.random.default_rng(2)
+    Q2 = wl.round_bf16_f32(Q + 0.05 * rng.standard_normal(Q.shape).astype(np.float32))
+    K2 = wl.round_bf16_f32(K + 0.05 * rng.standard_normal(K.shape).astype(np.float32))
+    pw = B.Params(**{**p.__dict__, "q_init_mode": 1, "k_init_mode": 1, "q_iters": 2, "k_iters": 2})
+    O = to_np(B.adacluster_attn(pw, to_dev(Q2, B.BF16), to_dev(K2, B.BF16), to_dev(V, B.BF16), outs=outs))
+    torch.cuda.synchronize()
+    assert np.array_equal(outs["k_count"].cpu().numpy(), kc0)
+    chained = oracle_from_gpu_intermediates(Q2, K2, V, outs, pw)
+    sel_gpu = sel_from_dev(outs["sel_idx"], outs["sel_cnt"])
+    for h in range(H):
+        rel, mx = attn_errors(O[h], chained[h])
+        assert rel < 1e-2 and mx < 2e-2
+        sel_ref = oracle_selection_from_gpu_centroids(outs, pw, h)
+        for i in range(p.q_clusters):
+            assert np.array_equal(sel_gpu[h][i], sel_ref[i])

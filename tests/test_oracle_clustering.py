@@ -288,3 +288,23 @@ def test_round_fn_is_applied_to_assignment_centres():
     labels, C, _ = orc.euclid_kmeans(X, 5, 3, round_fn=orc.round_to_bf16)
     assert np.array_equal(C, orc.round_to_bf16(C))
     assert np.array_equal(labels, loops_argmin(X, C))
+
+
+def test_warm_start_keeps_count_and_follows_lloyd_from_given_centres():
+    """Sec. 3.2.2 "Efficient initialization": fixed cluster count, previous centres as the start."""
+    X, comp, mu = separated_mixture(20, n_per=25, m=5, d=6)
+    true_means = np.stack([X[comp == j].mean(axis=0) for j in range(5)])
+    out = orc.warm_key_clustering(X, true_means + 0.01, 2)
+    assert np.array_equal(out["labels"], comp)                       # a fixed point of Lloyd
+    assert np.allclose(out["centroids"], true_means, atol=1e-12)
+    assert out["assign_centroids"].shape == (5, 6)
+    # one pass = plain nearest-centre assignment to the centres given
+    rng = np.random.default_rng(21)
+    prev = rng.standard_normal((7, 6))
+    out1 = orc.warm_key_clustering(X, prev, 1)
+    assert np.array_equal(out1["assign_centroids"], prev)
+    assert np.array_equal(out1["labels"], loops_argmin(X, prev))
+    # an empty cluster keeps the centre it was given
+    far = np.concatenate([true_means, np.full((1, 6), 100.0)])
+    out2 = orc.warm_key_clustering(X, far, 3)
+    assert out2["sizes"][5] == 0 and np.array_equal(out2["assign_centroids"][5], far[5])
