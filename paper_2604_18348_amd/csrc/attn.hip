@@ -122,16 +122,8 @@ struct AttnArgs {
   const int32_t* rng_start; const int32_t* rng_pre; const int32_t* rng_cnt;
   int N, Cq, maxtiles, maxr;
   float scale_log2e;            // softmax scale x log2(e)
-  unsigned long long* dbg;
+  int head_major;               // workgroup -> (head, tile) mapping, see attn_mfma
 };
-
-#ifdef ADBG_TIMING
-static unsigned long long* g_dbg_host_ptr = nullptr;
-extern "C" int adacluster_debug_set(void* p) { g_dbg_host_ptr = (unsigned long long*)p; return 0; }
-#define DBG_T(var) const long long var = __builtin_readcyclecounter()
-#else
-#define DBG_T(var)
-#endif
 
 // position in the concatenation of ranges -> permuted key row; a cursor that only moves forward
 struct RangeCursor {
@@ -176,11 +168,23 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
   constexpr int ITEMS = BN * CH, PT = ITEMS / NT, TILEB = BN * ROWB;
   static_assert(ITEMS % NT == 0, "tile chunks must divide evenly over the threads");
 
-  const int h = blockIdx.y;
-  // Workgroups go to the 8 XCDs round-robin (gridDim.x is a multiple of 8, so XCD = blockIdx.x % 8).
-  // Give every XCD a contiguous run of query tiles: the tiles of one query cluster stream the
-  // same K/V rows, and this way they do it at the same time behind the same L2.
-  const int tile = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+  // Workgroups go to the 8 XCDs round-robin in launch order (gridDim.x is a multiple of 8, so
+  // XCD = blockIdx.x % 8), and each XCD has its own L2.
+  int h, tile;
+  if (a.head_major) {
+    // Heads are dealt to XCDs whole, eight at a time: all query tiles of a head then stream that
+    // head's K/V rows behind one L2.  The H % 8 heads left over are split eight ways by tile.
+    const int gx = gridDim.x, gx8 = gx >> 3;
+    const int xcd = blockIdx.x & 7, slot = (blockIdx.y * gx + blockIdx.x) >> 3;
+    const int Hfull = (gridDim.y >> 3) << 3, full_slots = (Hfull >> 3) * gx;
+    if (slot < full_slots) { h = (slot / gx) * 8 + xcd; tile = slot % gx; }
+    else { const int r = slot - full_slots; h = Hfull + r / gx8; tile = xcd * gx8 + r % gx8; }
+  } else {
+    // Every head is split eight ways: an XCD takes a contiguous run of its query tiles (the tiles
+    // of one query cluster stream the same K/V rows, and so do it behind the same L2).
+    h = blockIdx.y;
+    tile = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+  }
   if (tile >= a.ntiles[h]) return;
   const int32_t* tl = a.tiles + ((size_t)h * a.maxtiles + tile) * 3;
   const int qc = tl[0], row0 = tl[1], nrows = tl[2];
@@ -263,14 +267,10 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
   const bf16x2_t ones2 = {(__bf16)1.0f, (__bf16)1.0f};   // row sums use the rounded probabilities P V uses
   const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-#ifdef ADBG_TIMING
-  long long dbg_s = 0, dbg_sm = 0, dbg_pv = 0, dbg_ld = 0, dbg_bar = 0;
-#endif
   auto compute_tile = [&](int buf, int nvalid /* < BN only on a masked tail tile */, auto masked) {
     constexpr bool MASK = decltype(masked)::value;
     const char* ks_ = Ks[buf];
     const char* vs_ = Vs[buf];
-    DBG_T(t_a);
     f32x16_t sacc[2][QB];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
@@ -297,10 +297,6 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
           }
         }
     }
-#ifdef ADBG_TIMING
-    asm volatile("s_nop 0" :: "v"(sacc[1][QB - 1][15]));
-#endif
-    DBG_T(t_b);
     bf16x8_t pf[QB][2][2];
     float alpha[QB];
     bool need_rescale = false;
@@ -344,10 +340,6 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
 #pragma unroll
           for (int v = 0; v < 16; ++v) oacc[db][qb][v] *= alpha[qb];
     }
-#ifdef ADBG_TIMING
-    asm volatile("s_nop 0" :: "v"(pf[QB - 1][1][1]));
-#endif
-    DBG_T(t_c);
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
       bf16x8_t va[2][2];
@@ -368,11 +360,6 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
           for (int qb = 0; qb < QB; ++qb)
             oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[kb][s2], pf[qb][kb][s2], oacc[db][qb], 0, 0, 0);
     }
-#ifdef ADBG_TIMING
-    asm volatile("s_nop 0" :: "v"(oacc[DB - 1][QB - 1][15]));
-    DBG_T(t_d);
-    dbg_s += t_b - t_a; dbg_sm += t_c - t_b; dbg_pv += t_d - t_c;
-#endif
   };
 
   // prologue: row offsets of tiles 0..2 (a slot past the end repeats the first row: it is loaded
@@ -394,30 +381,12 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
   // full tiles in the loop; a ragged tail tile (the only one that needs masking) after it
   const int Tfull = total / BN;
   for (int t = 0; t < Tfull; ++t) {
-    DBG_T(t_e);
-#ifndef ADBG_NOLOAD
     if (t + 1 < T) issue_loads((t + 1) & 1, (t + 1) & 3);
-#endif
     if (tid < BN && t + 3 < T) ridx[(t + 3) & 3][tid] = row_off((t + 3) * BN + tid);
-    DBG_T(t_f);
     if (wave_has_rows) compute_tile(t & 1, BN, std::false_type{});
-    DBG_T(t_g);
     __builtin_amdgcn_s_waitcnt(0x0F70);
-#ifndef ADBG_NOSYNC
     __syncthreads();
-#endif
-#ifdef ADBG_TIMING
-    DBG_T(t_h);
-    dbg_ld += t_f - t_e; dbg_bar += t_h - t_g;
-#endif
   }
-#ifdef ADBG_TIMING
-  if (lane == 0 && wave == 1 && a.dbg) {
-    atomicAdd(&a.dbg[0], (unsigned long long)dbg_s); atomicAdd(&a.dbg[1], (unsigned long long)dbg_sm);
-    atomicAdd(&a.dbg[2], (unsigned long long)dbg_pv); atomicAdd(&a.dbg[3], (unsigned long long)dbg_ld);
-    atomicAdd(&a.dbg[4], (unsigned long long)dbg_bar); atomicAdd(&a.dbg[5], (unsigned long long)Tfull);
-  }
-#endif
   if (T > Tfull && wave_has_rows) compute_tile(Tfull & 1, total - Tfull * BN, std::true_type{});
 
   // O^T accumulator value v of block db is column  db*32 + 8*(v/4) + 4*hb + v%4  of query c
@@ -554,10 +523,8 @@ int launch_attention(hipStream_t s, int dtype, int d, int H, int N, int Cq, int 
                      const int32_t* tiles, const int32_t* ntiles, const int32_t* rng_start,
                      const int32_t* rng_pre, const int32_t* rng_cnt) {
   AttnArgs a{Q, Kp, Vp, O, perm_q, tiles, ntiles, rng_start, rng_pre, rng_cnt, N, Cq, maxtiles, maxr,
-             scale * 1.4426950408889634f, nullptr};
-#ifdef ADBG_TIMING
-  a.dbg = g_dbg_host_ptr;
-#endif
+             scale * 1.4426950408889634f,
+             (Cq == 1 || (size_t)4 * N * d <= ((size_t)8 << 20)) ? 1 : 0};
   dim3 g((maxtiles + 7) / 8 * 8, H);
   if (dtype == ADACLUSTER_BF16) {
     if (d == 64) attn_mfma<64, A64_QB, A64_NW, A64_MINB><<<g, A64_NW * 64, 0, s>>>(a);
