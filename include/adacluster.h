@@ -15,11 +15,15 @@
  *     scratch lives in the caller's workspace `ws` of at least
  *     adacluster_workspace_bytes() bytes, 256-byte aligned.  Workspace contents
  *     are undefined after a call.  Output buffers are fully overwritten.
- *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
- *     the default stream).  Calls are asynchronous except adacluster_kcluster and
- *     adacluster_attn, which synchronise the stream once per clustering stage to
- *     read a few integers back (the stage loop of Algorithm 1 has a data-dependent
- *     trip count).
+ *   - All work is ordered by `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream): it is enqueued there, except that adacluster_attn puts
+ *     the query clustering on a second, library-owned stream per device (created
+ *     on first use, default priority), forked from `stream` at the start of the
+ *     call and joined back to it before the selection step, so work queued on
+ *     `stream` after the call still waits for all of it.  Calls are asynchronous
+ *     except adacluster_kcluster and adacluster_attn, which synchronise the stream
+ *     once per clustering stage to read a few integers back (the stage loop of
+ *     Algorithm 1 has a data-dependent trip count).
  *   - Every function returns 0 on success or a negative ADACLUSTER_E_* code.  On
  *     an argument error nothing is launched.  adacluster_last_error() returns a
  *     message for the calling thread's last failure.  No function throws, aborts
@@ -200,7 +204,9 @@ int adacluster_dense_attn(const adacluster_params* p,
  * stream at their stage boundaries.  adacluster_profile_read waits for the last recorded call
  * and writes, to the HOST array ms[6], the milliseconds of: query clustering, Algorithm 1,
  * selection (stand-alone sparse_attn: the two label sorts), K/V permutation, planning, and the
- * attention kernel; -1 for a stage the call did not run.  Not thread-safe.
+ * attention kernel; -1 for a stage the call did not run.  In adacluster_attn the two clusterings
+ * run side by side and each is timed from the start of the call, so their sum exceeds the time
+ * the pair takes.  Not thread-safe.
  */
 int adacluster_profile_enable(int on);
 int adacluster_profile_read(float* ms);

@@ -14,24 +14,52 @@ namespace {
 
 thread_local char g_err[256] = "";
 
-// Optional stage timing: hipEvents recorded at the stage boundaries of a call.
-enum { EV_START = 0, EV_QCLUSTER, EV_KCLUSTER, EV_SELECT, EV_PERMUTE, EV_PLAN, EV_ATTN, EV_COUNT };
+// Optional stage timing: hipEvents recorded at the stage boundaries of a call.  A stage is timed
+// from the event in from[] (default: the previous recorded stage boundary); the fused call runs
+// the two clusterings side by side, so both of those are timed from the start of the call.
+enum { EV_START = 0, EV_QCLUSTER, EV_KCLUSTER, EV_SELECT, EV_PERMUTE, EV_PLAN, EV_ATTN, EV_STAGES,
+       EV_JOIN = EV_STAGES, EV_COUNT };
 struct Profiler {
   bool enabled = false;
   bool recorded[EV_COUNT] = {};
+  int from[EV_COUNT] = {};
   hipEvent_t ev[EV_COUNT] = {};
 } g_prof;
 
 void prof_begin(hipStream_t st) {
   if (!g_prof.enabled) return;
-  for (int i = 0; i < EV_COUNT; ++i) g_prof.recorded[i] = false;
+  for (int i = 0; i < EV_COUNT; ++i) { g_prof.recorded[i] = false; g_prof.from[i] = -1; }
   (void)hipEventRecord(g_prof.ev[EV_START], st);
   g_prof.recorded[EV_START] = true;
 }
-void prof_mark(int which, hipStream_t st) {
+void prof_mark(int which, hipStream_t st, int from = -1) {
   if (!g_prof.enabled) return;
   (void)hipEventRecord(g_prof.ev[which], st);
   g_prof.recorded[which] = true;
+  g_prof.from[which] = from;
+}
+
+// A second stream per device, for work of a call that does not depend on what the caller's
+// stream is doing (default priority, like every stream here), and the two events that fork it
+// from and join it to the caller's stream.
+struct AuxStream {
+  bool ready = false;
+  hipStream_t s = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr;
+};
+AuxStream g_aux[64];
+
+AuxStream* aux_stream() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  AuxStream& a = g_aux[dev];
+  if (!a.ready) {
+    if (hipStreamCreateWithFlags(&a.s, hipStreamNonBlocking) != hipSuccess) return nullptr;
+    if (hipEventCreateWithFlags(&a.fork, hipEventDisableTiming) != hipSuccess) return nullptr;
+    if (hipEventCreateWithFlags(&a.join, hipEventDisableTiming) != hipSuccess) return nullptr;
+    a.ready = true;
+  }
+  return &a;
 }
 
 int fail(int code, const char* fmt, ...) {
@@ -88,6 +116,8 @@ struct WS {
   SortScratch sort; int32_t* perm_tmp; int32_t* offs_tmp; int32_t* poff;
   float* psum; float* pnorm; float* pmin; float* pmax;
   int32_t* perm_q; int32_t* offs_q; int32_t* perm_k; int32_t* offs_k;
+  // scratch of the query clustering (its own set: it runs beside the key clustering)
+  void* q_cent_lp; float* q_bias; SortScratch q_sort; int32_t* q_poff; float* q_psum; float* q_pnorm;
   void* Kp; void* Vp;
   int32_t* rng_start; int32_t* rng_pre; int32_t* rng_cnt; int32_t* tiles; int32_t* ntiles;
   // homes for outputs of the fused call the caller did not ask for
@@ -143,6 +173,15 @@ size_t layout(const adacluster_params* p, WS* w, unsigned char* base) {
   TAKE(pnorm, float*, H * (size_t)D.prow * 4);
   TAKE(pmin, float*, H * (size_t)D.prow * d * 4);
   TAKE(pmax, float*, H * (size_t)D.prow * d * 4);
+  TAKE(q_cent_lp, void*, H * (size_t)D.Cq * d * es);
+  TAKE(q_bias, float*, H * (size_t)D.Cq * 4);
+  TAKE(q_sort.hist, int32_t*, H * D.nseg * 128 * 4);
+  TAKE(q_sort.lab_a, int32_t*, H * N * 4);
+  TAKE(q_sort.val_a, int32_t*, H * N * 4);
+  TAKE(q_sort.lab_b, int32_t*, H * N * 4);
+  TAKE(q_poff, int32_t*, H * (size_t)(D.Cq + 1) * 4);
+  TAKE(q_psum, float*, H * (size_t)(N / 128 + D.Cq + 34) * d * 4);
+  TAKE(q_pnorm, float*, H * (size_t)(N / 128 + D.Cq + 34) * 4);
   TAKE(perm_q, int32_t*, H * N * 4);
   TAKE(offs_q, int32_t*, H * (size_t)(D.Cq + 1) * 4);
   TAKE(perm_k, int32_t*, H * N * 4);
@@ -192,22 +231,22 @@ int run_qcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
   const Dims D = dims_of(p);
   const int P = parts_for(D.N, D.Cq);
   RET_IF(launch_init_centroids(st, p->dtype, D.d, D.H, D.N, 0, D.Cq, D.Cq, nullptr, nullptr, 1, p->q_init_mode,
-                               D.Cq, D.Cq, Q, q_centroids, w.cent_lp, q_assign, w.bias));
+                               D.Cq, D.Cq, Q, q_centroids, w.q_cent_lp, q_assign, w.q_bias));
   for (int it = 0; it < p->q_iters; ++it) {
-    RET_IF(launch_assign(st, p->dtype, D.d, D.H, D.N, D.N, 0, D.Cq, D.Cq, nullptr, nullptr, Q, w.cent_lp, w.bias,
+    RET_IF(launch_assign(st, p->dtype, D.d, D.H, D.N, D.N, 0, D.Cq, D.Cq, nullptr, nullptr, Q, w.q_cent_lp, w.q_bias,
                          q_labels, nullptr));
     RET_IF(launch_sort(st, D.H, D.N, D.N, D.Cq, q_labels, nullptr, nullptr, 0, nullptr, 0, nullptr, 0, w.perm_q,
-                       w.offs_q, D.Cq + 1, w.sort));
+                       w.offs_q, D.Cq + 1, w.q_sort));
     RET_IF(launch_seg_reduce(st, p->dtype, D.d, D.H, D.N, 0, D.Cq, D.Cq, P, nullptr, 1, 0, Q, w.perm_q, w.offs_q,
-                             D.Cq + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax));
+                             D.Cq + 1, w.q_poff, w.q_psum, w.q_pnorm, nullptr, nullptr));
     const bool last = it == p->q_iters - 1;
     if (!last) {
       RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 0, D.Cq, D.Cq, P, D.Cq, D.Cq, nullptr, 1, 1, 0, w.offs_q,
-                             D.Cq + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax, q_centroids, w.cent_lp, q_assign, w.bias,
+                             D.Cq + 1, w.q_poff, w.q_psum, w.q_pnorm, nullptr, nullptr, q_centroids, w.q_cent_lp, q_assign, w.q_bias,
                              nullptr, nullptr, nullptr, nullptr, nullptr, nullptr));
     } else {
       RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 0, D.Cq, D.Cq, P, D.Cq, D.Cq, nullptr, 1, 0, 0, w.offs_q,
-                             D.Cq + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax, nullptr, nullptr, nullptr, nullptr,
+                             D.Cq + 1, w.q_poff, w.q_psum, w.q_pnorm, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
                              q_centroids, nullptr, q_sizes, q_mean_norm, nullptr, nullptr));
     }
   }
@@ -441,19 +480,30 @@ int adacluster_attn(const adacluster_params* p, const void* Q, const void* K, co
     return fail(ADACLUSTER_E_BADARG, "attn: q_init_mode 1 needs outs->q_centroids");
   if (p->k_init_mode == 1 && (!o.k_centroids || !o.k_count || !o.full_flag))
     return fail(ADACLUSTER_E_BADARG, "attn: k_init_mode 1 needs outs->k_centroids, k_count and full_flag");
+  // The two clusterings do not depend on each other and both are chains of small kernels: the
+  // query clustering goes to a second stream, forked from and joined back to the caller's.
+  AuxStream* aux = aux_stream();
+  if (!aux) return fail(ADACLUSTER_E_INTERNAL, "could not create the second stream: %s", hipGetErrorString(hipGetLastError()));
   prof_begin(st);
-  if ((rc = run_qcluster(p, w, st, Q, q_labels, q_centroids, q_assign_centroids, q_sizes, q_mean_norm))) return rc;
-  prof_mark(EV_QCLUSTER, st);
+  if (hipEventRecord(aux->fork, st) != hipSuccess || hipStreamWaitEvent(aux->s, aux->fork, 0) != hipSuccess)
+    return fail(ADACLUSTER_E_INTERNAL, "stream fork failed: %s", hipGetErrorString(hipGetLastError()));
+  rc = run_qcluster(p, w, aux->s, Q, q_labels, q_centroids, q_assign_centroids, q_sizes, q_mean_norm);
+  prof_mark(EV_QCLUSTER, aux->s, EV_START);
+  // join before any return: the caller's stream must not run ahead of work queued on the second one
+  if (hipEventRecord(aux->join, aux->s) != hipSuccess) return fail(ADACLUSTER_E_INTERNAL, "stream join failed");
   int kc_bound = capacity(p);
-  if ((rc = run_kcluster(p, w, st, K, k_labels, k_centroids, k_assign_centroids, k_bmin, k_bmax, k_sizes, k_count,
-                         full_flag, o.k_stage_offs, o.k_stage_of, tau_used, &kc_bound)))
-    return rc;
-  prof_mark(EV_KCLUSTER, st);
+  int rck = rc ? 0 : run_kcluster(p, w, st, K, k_labels, k_centroids, k_assign_centroids, k_bmin, k_bmax, k_sizes,
+                                   k_count, full_flag, o.k_stage_offs, o.k_stage_of, tau_used, &kc_bound);
+  prof_mark(EV_KCLUSTER, st, EV_START);
+  if (hipStreamWaitEvent(st, aux->join, 0) != hipSuccess) return fail(ADACLUSTER_E_INTERNAL, "stream join failed");
+  if (rc) return rc;
+  if (rck) return rck;
+  prof_mark(EV_JOIN, st);
   const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->d);
   RET_IF(launch_select(st, p->H, p->q_clusters, capacity(p), p->d, p->score_mode, p->select_mode, p->topk, p->top_p,
                        scale, q_centroids, q_mean_norm, k_centroids, k_bmin, k_bmax, k_sizes, k_count, full_flag,
                        sel_idx, sel_cnt, kc_bound));
-  prof_mark(EV_SELECT, st);
+  prof_mark(EV_SELECT, st, EV_JOIN);
   // both label sorts were left in the workspace by the clustering steps
   return run_attention(p, w, st, Q, K, V, O, k_count, sel_idx, sel_cnt);
 }
@@ -493,13 +543,15 @@ int adacluster_profile_read(float* ms) {
   if (!ms) return fail(ADACLUSTER_E_BADARG, "ms is NULL");
   if (!g_prof.enabled) return fail(ADACLUSTER_E_UNSUPPORTED, "profiling is not enabled");
   int prev = -1;
-  for (int i = 0; i < EV_COUNT; ++i) {
+  for (int i = 0; i < EV_STAGES; ++i) {
     if (i > 0) ms[i - 1] = -1.f;
     if (!g_prof.recorded[i]) continue;
     if (hipEventSynchronize(g_prof.ev[i]) != hipSuccess) return fail(ADACLUSTER_E_INTERNAL, "event sync failed");
-    if (prev >= 0 && i > 0) {
+    const int from = g_prof.from[i] >= 0 ? g_prof.from[i] : prev;
+    if (from >= 0 && i > 0) {
+      if (hipEventSynchronize(g_prof.ev[from]) != hipSuccess) return fail(ADACLUSTER_E_INTERNAL, "event sync failed");
       float t = 0.f;
-      if (hipEventElapsedTime(&t, g_prof.ev[prev], g_prof.ev[i]) != hipSuccess)
+      if (hipEventElapsedTime(&t, g_prof.ev[from], g_prof.ev[i]) != hipSuccess)
         return fail(ADACLUSTER_E_INTERNAL, "event elapsed failed");
       ms[i - 1] = t;
     }
