@@ -21,9 +21,11 @@
  *     on first use, default priority), forked from `stream` at the start of the
  *     call and joined back to it before the selection step, so work queued on
  *     `stream` after the call still waits for all of it.  Calls are asynchronous
- *     except adacluster_kcluster and adacluster_attn, which synchronise the stream
- *     once per clustering stage to read a few integers back (the stage loop of
- *     Algorithm 1 has a data-dependent trip count).
+ *     except adacluster_kcluster and adacluster_attn with k_init_mode 0, which block
+ *     the calling thread once per clustering stage on an event, to read a few
+ *     integers back through pinned host memory the library keeps per thread (the
+ *     stage loop of Algorithm 1 has a data-dependent trip count; the host runs one
+ *     stage behind the device, so the stream is not drained).
  *   - Every function returns 0 on success or a negative ADACLUSTER_E_* code.  On
  *     an argument error nothing is launched.  adacluster_last_error() returns a
  *     message for the calling thread's last failure.  No function throws, aborts

@@ -49,6 +49,34 @@ struct AuxStream {
 };
 AuxStream g_aux[64];
 
+// Pinned host slots for the per-stage report of Algorithm 1 and two events to wait on, per thread.
+struct StageReadback {
+  bool ready = false;
+  int device = -1;
+  int32_t* host = nullptr;     // [ADACLUSTER_MAX_STAGES + 2][4]
+  hipEvent_t ev[2] = {nullptr, nullptr};
+};
+thread_local StageReadback t_readback;
+
+StageReadback* stage_readback() {
+  StageReadback& r = t_readback;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return nullptr;
+  if (r.ready && r.device != dev) {        // events belong to the device they were created on
+    for (int i = 0; i < 2; ++i) (void)hipEventDestroy(r.ev[i]);
+    (void)hipHostFree(r.host);
+    r.ready = false;
+  }
+  if (!r.ready) {
+    r.device = dev;
+    if (hipHostMalloc((void**)&r.host, (ADACLUSTER_MAX_STAGES + 2) * 4 * sizeof(int32_t), hipHostMallocDefault) != hipSuccess) return nullptr;
+    for (int i = 0; i < 2; ++i)
+      if (hipEventCreateWithFlags(&r.ev[i], hipEventDisableTiming) != hipSuccess) return nullptr;
+    r.ready = true;
+  }
+  return &r;
+}
+
 AuxStream* aux_stream() {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
@@ -260,6 +288,7 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
                  float* tau_used, int* kc_bound_out) {
   const Dims D = dims_of(p);
   int kc_bound = 0;   // sum over stages of the largest stage centre count: an upper bound of every |C|
+  hipEvent_t pending_ev = nullptr;   // the last report copy may still be in flight when the stage loop ends
   if (p->k_init_mode == 1) {
     // warm start: one pseudo-stage over all tokens with the previous centres, count fixed
     RET_IF(launch_kstate_warm(st, w.kstate, D.H, D.N, D.cap, k_count, full_flag));
@@ -288,16 +317,31 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
   RET_IF(launch_kstate_init(st, w.kstate, D.H, D.N));
   if (k_stage_of) RET_IF(launch_fill_i32(st, k_stage_of, (size_t)D.H * D.N, -1));
   if (p->tau_abs > 0.f) RET_IF(launch_tau(st, D.H, D.N, nullptr, nullptr, 0.f, p->tau_abs, w.tau));
+  // The stage loop has a data-dependent trip count, and grids are sized by what the stage head
+  // reports: {active heads, max |U|, max m_t}.  Reading that back before enqueuing the stage
+  // would drain the queue once per stage, so the host stays one stage behind: stage t is
+  // enqueued with the report of stage t-1 (|U| and m_t never grow, so the older figures are
+  // valid bounds; every kernel takes the true counts from the device state), and a stage whose
+  // heads all turn out finished runs as empty kernels, once, at the end.
+  StageReadback* rb = stage_readback();
+  if (!rb) return fail(ADACLUSTER_E_INTERNAL, "stage read-back set-up failed: %s", hipGetErrorString(hipGetLastError()));
+  int n_bound = D.N, m_bound = p->k_m0 < D.N ? p->k_m0 : D.N;
   for (int t = 0; t <= p->k_max_stages; ++t) {
+    pending_ev = rb->ev[t & 1];
     RET_IF(launch_kstage_begin(st, w.kstate, D.H, D.N, p->k_max_clusters, p->k_m0, p->k_m_min, p->k_max_stages,
                                u_min, w.summary));
-    int32_t summ[3] = {0, 0, 0};
-    if (hipMemcpyAsync(summ, w.summary, sizeof(summ), hipMemcpyDeviceToHost, st) != hipSuccess ||
-        hipStreamSynchronize(st) != hipSuccess)
+    if (hipMemcpyAsync(rb->host + 4 * t, w.summary, 3 * sizeof(int32_t), hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipEventRecord(rb->ev[t & 1], st) != hipSuccess)
       return fail(ADACLUSTER_E_INTERNAL, "stage read-back failed: %s", hipGetErrorString(hipGetLastError()));
-    const int n_active = summ[0], n_bound = summ[1], m_bound = summ[2];
-    if (n_active == 0) break;
-    kc_bound += m_bound;
+    if (t > 0) {
+      if (hipEventSynchronize(rb->ev[(t - 1) & 1]) != hipSuccess)
+        return fail(ADACLUSTER_E_INTERNAL, "stage read-back failed: %s", hipGetErrorString(hipGetLastError()));
+      const int32_t* summ = rb->host + 4 * (t - 1);
+      if (summ[0] == 0) break;                 // stage t-1 had no active head: the loop ended there
+      n_bound = summ[1]; m_bound = summ[2];
+      kc_bound += m_bound;
+    }
+    if (t == p->k_max_stages) break;           // the stage head has just closed every head
     const int32_t* ul = (t == 0) ? nullptr : w.ulist[t & 1];
     int32_t* ul_next = w.ulist[(t + 1) & 1];
     RET_IF(launch_init_centroids(st, p->dtype, D.d, D.H, D.N, 1, 0, m_bound, w.kstate, ul, 0, 0, D.cap, p->k_m0, K,
@@ -339,6 +383,10 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
   RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 2, 0, D.cap, P, D.cap, D.cap, w.kstate, 0, 0, want_box, w.offs_k,
                          D.cap + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax, nullptr, nullptr, nullptr, nullptr, k_centroids,
                          k_assign, k_sizes, nullptr, k_bmin, k_bmax));
+  // the pinned report slots are reused by the next call of this thread: let the last copy land
+  // (it was queued ahead of everything above, so this does not drain the stream)
+  if (pending_ev && hipEventSynchronize(pending_ev) != hipSuccess)
+    return fail(ADACLUSTER_E_INTERNAL, "stage read-back failed: %s", hipGetErrorString(hipGetLastError()));
   return 0;
 }
 
