@@ -258,15 +258,16 @@ int run_qcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
                  float* q_centroids, float* q_assign, int32_t* q_sizes, float* q_mean_norm) {
   const Dims D = dims_of(p);
   const int P = parts_for(D.N, D.Cq);
+  int poff_done = 0;   // set when the sort has already cut the clusters into reduction parts
   RET_IF(launch_init_centroids(st, p->dtype, D.d, D.H, D.N, 0, D.Cq, D.Cq, nullptr, nullptr, 1, p->q_init_mode,
                                D.Cq, D.Cq, Q, q_centroids, w.q_cent_lp, q_assign, w.q_bias));
   for (int it = 0; it < p->q_iters; ++it) {
     RET_IF(launch_assign(st, p->dtype, D.d, D.H, D.N, D.N, 0, D.Cq, D.Cq, nullptr, nullptr, Q, w.q_cent_lp, w.q_bias,
                          q_labels, nullptr));
     RET_IF(launch_sort(st, D.H, D.N, D.N, D.Cq, q_labels, nullptr, nullptr, 0, nullptr, 0, nullptr, 0, w.perm_q,
-                       w.offs_q, D.Cq + 1, w.q_sort));
+                       w.offs_q, D.Cq + 1, w.q_sort, w.q_poff, reduce_part_rows(), &poff_done));
     RET_IF(launch_seg_reduce(st, p->dtype, D.d, D.H, D.N, 0, D.Cq, D.Cq, P, nullptr, 1, 0, Q, w.perm_q, w.offs_q,
-                             D.Cq + 1, w.q_poff, w.q_psum, w.q_pnorm, nullptr, nullptr));
+                             D.Cq + 1, w.q_poff, w.q_psum, w.q_pnorm, nullptr, nullptr, poff_done));
     const bool last = it == p->q_iters - 1;
     if (!last) {
       RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 0, D.Cq, D.Cq, P, D.Cq, D.Cq, nullptr, 1, 1, 0, w.offs_q,
@@ -289,6 +290,7 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
   const Dims D = dims_of(p);
   int kc_bound = 0;   // sum over stages of the largest stage centre count: an upper bound of every |C|
   hipEvent_t pending_ev = nullptr;   // the last report copy may still be in flight when the stage loop ends
+  int poff_done = 0;                 // set when the sort has already cut the clusters into reduction parts
   if (p->k_init_mode == 1) {
     // warm start: one pseudo-stage over all tokens with the previous centres, count fixed
     RET_IF(launch_kstate_warm(st, w.kstate, D.H, D.N, D.cap, k_count, full_flag));
@@ -301,9 +303,9 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
                            k_labels, nullptr));
       if (it < p->k_iters - 1) {
         RET_IF(launch_sort(st, D.H, D.N, D.N, D.cap, k_labels, nullptr, nullptr, 0, &w.kstate->m_t, sizeof(KState) / 4,
-                           nullptr, 0, w.perm_tmp, w.offs_tmp, D.capmax + 1, w.sort));
+                           nullptr, 0, w.perm_tmp, w.offs_tmp, D.capmax + 1, w.sort, w.poff, reduce_part_rows(), &poff_done));
         RET_IF(launch_seg_reduce(st, p->dtype, D.d, D.H, D.N, 1, 0, D.cap, Pw, w.kstate, 0, 0, K, w.perm_tmp,
-                                 w.offs_tmp, D.capmax + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax));
+                                 w.offs_tmp, D.capmax + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax, poff_done));
         RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 1, 0, D.cap, Pw, D.cap, D.cap, w.kstate, 0, 1, 0, w.offs_tmp,
                                D.capmax + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax, k_centroids, w.cent_lp,
                                k_assign, w.bias, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr));
@@ -353,9 +355,9 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
       if (it < p->k_iters - 1) {
         RET_IF(launch_sort(st, D.H, D.N, n_bound, m_bound, w.labels_tmp, ul, &w.kstate->ucount,
                            sizeof(KState) / 4, &w.kstate->m_t, sizeof(KState) / 4, &w.kstate->active,
-                           sizeof(KState) / 4, w.perm_tmp, w.offs_tmp, D.capmax + 1, w.sort));
+                           sizeof(KState) / 4, w.perm_tmp, w.offs_tmp, D.capmax + 1, w.sort, w.poff, reduce_part_rows(), &poff_done));
         RET_IF(launch_seg_reduce(st, p->dtype, D.d, D.H, D.N, 1, 0, m_bound, P, w.kstate, 0, 0, K, w.perm_tmp,
-                                 w.offs_tmp, D.capmax + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax));
+                                 w.offs_tmp, D.capmax + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax, poff_done));
         RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 1, 0, m_bound, P, D.cap, p->k_m0, w.kstate, 0, 1, 0,
                                w.offs_tmp, D.capmax + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax, w.master, w.cent_lp,
                                k_assign, w.bias, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr));
@@ -375,11 +377,11 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
                        k_labels, nullptr));
   }
   RET_IF(launch_sort(st, D.H, D.N, D.N, D.cap, k_labels, nullptr, nullptr, 0, &w.kstate->ccount, sizeof(KState) / 4,
-                     nullptr, 0, w.perm_k, w.offs_k, D.cap + 1, w.sort));
+                     nullptr, 0, w.perm_k, w.offs_k, D.cap + 1, w.sort, w.poff, reduce_part_rows(), &poff_done));
   const int want_box = (k_bmin && k_bmax) ? 1 : 0;
   const int P = parts_for(D.N, D.cap);
   RET_IF(launch_seg_reduce(st, p->dtype, D.d, D.H, D.N, 2, 0, D.cap, P, w.kstate, 0, want_box, K, w.perm_k, w.offs_k,
-                           D.cap + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax));
+                           D.cap + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax, poff_done));
   RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 2, 0, D.cap, P, D.cap, D.cap, w.kstate, 0, 0, want_box, w.offs_k,
                          D.cap + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax, nullptr, nullptr, nullptr, nullptr, k_centroids,
                          k_assign, k_sizes, nullptr, k_bmin, k_bmax));

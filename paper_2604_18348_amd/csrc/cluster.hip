@@ -745,6 +745,46 @@ __global__ __launch_bounds__(256) void filter_scatter(const KState* __restrict__
   }
 }
 
+// The three filter passes in one workgroup per head, for heads whose |U| is small.
+__global__ __launch_bounds__(1024) void filter_small(KState* __restrict__ st, const float* __restrict__ dist2, int N,
+                                                     const float* __restrict__ tau,
+                                                     const int32_t* __restrict__ ulist_in,
+                                                     int32_t* __restrict__ ulist_out, int32_t* __restrict__ stage_of,
+                                                     int stage) {
+  const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const KState s0 = st[h];
+  if (!s0.active) return;
+  const int n = min(s0.ucount, N);
+  const float t2 = tau[1];
+  __shared__ int32_t ws[16];
+  const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  int run = 0;
+  for (int base = 0; base < n; base += 1024) {
+    const int p = base + tid;
+    const bool valid = p < n;
+    const bool keep = valid && !(dist2[(size_t)h * N + p] < t2);
+    const int tok = valid ? (ulist_in ? ulist_in[(size_t)h * N + p] : p) : 0;
+    const uint64_t bal = __ballot(keep);
+    __syncthreads();
+    if (lane == 0) ws[wave] = __popcll(bal);
+    __syncthreads();
+    int before = 0, total = 0;
+    for (int w = 0; w < 16; ++w) { const int c = ws[w]; if (w < wave) before += c; total += c; }
+    if (keep) ulist_out[(size_t)h * N + run + before + __popcll(bal & lt_mask)] = tok;
+    if (valid && !keep && stage_of) stage_of[(size_t)h * N + tok] = stage;
+    run += total;
+  }
+  __syncthreads();      // every thread has taken its copy of the state
+  if (tid == 0) {
+    KState s = s0;
+    s.ucount = run;
+    s.ccount += s.m_t;
+    s.stage += 1;
+    s.stage_offs[s.stage] = s.ccount;
+    st[h] = s;
+  }
+}
+
 __global__ void fill_i32(int32_t* p, size_t n, int32_t v) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
@@ -768,6 +808,8 @@ __global__ void kstate_export(const KState* __restrict__ st, int H, int32_t* k_c
 // ------------------------------------------------------------------------------------------
 static inline int chk() { return hipGetLastError() == hipSuccess ? 0 : ADACLUSTER_E_INTERNAL; }
 
+int reduce_part_rows() { return REDUCE_ROWS; }
+
 int launch_assign(hipStream_t s, int dtype, int d, int H, int N, int n_bound, int mode, int m_const, int cap,
                   const KState* st, const int32_t* ulist, const void* X, const void* cent_lp, const float* bias,
                   int32_t* labels, float* dist2) {
@@ -787,9 +829,9 @@ int launch_assign(hipStream_t s, int dtype, int d, int H, int N, int n_bound, in
 int launch_seg_reduce(hipStream_t s, int dtype, int d, int H, int N, int mode, int m_const, int m_bound, int P,
                       const KState* st, int normalize, int want_box, const void* X, const int32_t* perm,
                       const int32_t* offs, int offs_stride, int32_t* poff, float* psum, float* pnorm, float* pmin,
-                      float* pmax) {
+                      float* pmax, int poff_ready) {
   ReduceCfg c{mode, m_const, N, P, m_bound, st, normalize, want_box};
-  part_scan<<<H, 1024, 0, s>>>(c, offs, offs_stride, poff);
+  if (!poff_ready) part_scan<<<H, 1024, 0, s>>>(c, offs, offs_stride, poff);
   dim3 g(P, H);
   if (dtype == ADACLUSTER_BF16) {
     if (d == 64) seg_reduce<bf16raw, 64><<<g, 64, 0, s>>>((const bf16raw*)X, c, perm, offs, offs_stride, poff, psum, pnorm, pmin, pmax);
@@ -875,6 +917,13 @@ int launch_tau(hipStream_t s, int H, int N, const float* dist2, double* part, fl
 int launch_filter(hipStream_t s, KState* st, int H, int N, int n_bound, const float* dist2, const float* tau,
                   int32_t* blockcnt, int32_t* u_prev, const int32_t* ulist_in, int32_t* ulist_out,
                   int32_t* stage_of, int stage) {
+#ifndef FILTER_SMALL_LIMIT
+#define FILTER_SMALL_LIMIT 32768
+#endif
+  if (n_bound <= FILTER_SMALL_LIMIT) {
+    filter_small<<<H, 1024, 0, s>>>(st, dist2, N, tau, ulist_in, ulist_out, stage_of, stage);
+    return chk();
+  }
   const int nblk = (N + 1023) / 1024;
   const int nb = (n_bound + 1023) / 1024;
   filter_count<<<dim3(nb, H), 256, 0, s>>>(st, dist2, N, nblk, tau, blockcnt);

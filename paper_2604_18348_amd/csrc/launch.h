@@ -20,14 +20,16 @@ struct SortScratch {
 int launch_sort(hipStream_t st, int H, int N, int n_bound, int m_bound, const int32_t* labels,
                 const int32_t* ulist, const int32_t* n_dev, int n_stride, const int32_t* m_dev, int m_stride,
                 const int32_t* active_dev, int active_stride, int32_t* perm, int32_t* offs, int offs_stride,
-                const SortScratch& sc);
+                const SortScratch& sc, int32_t* poff = nullptr, int part_rows = 0, int* poff_done = nullptr);
 
 int launch_assign(hipStream_t s, int dtype, int d, int H, int N, int n_bound, int mode, int m_const, int cap,
                   const KState* st, const int32_t* ulist, const void* X, const void* cent_lp, const float* bias,
                   int32_t* labels, float* dist2);
 int launch_seg_reduce(hipStream_t s, int dtype, int d, int H, int N, int mode, int m_const, int m_bound, int P,
                       const KState* st, int normalize, int want_box, const void* X, const int32_t* perm,
-                      const int32_t* offs, int offs_stride, int32_t* poff, float* psum, float* pnorm, float* pmin, float* pmax);
+                      const int32_t* offs, int offs_stride, int32_t* poff, float* psum, float* pnorm, float* pmin, float* pmax,
+                      int poff_ready = 0);
+int reduce_part_rows();
 int launch_finalize(hipStream_t s, int dtype, int d, int H, int mode, int m_const, int m_bound, int P, int cap,
                     int master_stride, const KState* st, int spherical, int update_assign, int want_box,
                     const int32_t* offs, int offs_stride, const int32_t* poff, const float* psum, const float* pnorm,

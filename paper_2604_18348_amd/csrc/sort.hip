@@ -127,16 +127,137 @@ __global__ void label_offsets(const int32_t* __restrict__ sorted, int N, SortArg
   offs[(size_t)h * offs_stride + j] = lo;
 }
 
+// The whole sort of one head in ONE workgroup, for heads of at most SMALL_SEGS segments: all radix
+// passes, the label offsets and (optionally) the part offsets of the centroid reduction, which
+// otherwise take five launches per pass of a few microseconds each.  Same arithmetic, same stable
+// order as the kernels above: wave w takes segments w, w+16, ...; the per-(segment, digit) counts
+// live in LDS.
+static constexpr int SMALL_SEGS = 64;
+__global__ __launch_bounds__(1024) void sort_small(const int32_t* __restrict__ labels, const int32_t* __restrict__ vals_in,
+                                                   int N, int passes, SortArgs a, const int32_t* __restrict__ m_dev,
+                                                   int m_stride, int m_const, int32_t* __restrict__ lab_a,
+                                                   int32_t* __restrict__ val_a, int32_t* __restrict__ lab_b,
+                                                   int32_t* __restrict__ perm, int32_t* __restrict__ offs,
+                                                   int offs_stride, int32_t* __restrict__ poff, int part_rows) {
+  const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (a.active_dev && !a.active_dev[(size_t)h * a.active_stride]) return;
+  const int n = min(head_items(a, h), SMALL_SEGS * SEG);     // the launcher admits no more
+  const int nseg = (n + SEG - 1) / SEG;
+  __shared__ int32_t hist[SMALL_SEGS][RBINS];
+  __shared__ int32_t gsum[8][RBINS];
+  __shared__ int32_t tot[RBINS];
+  __shared__ int32_t sc[1024];
+  const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  const int32_t* lin = labels + (size_t)h * N;
+  const int32_t* vin = vals_in ? vals_in + (size_t)h * N : nullptr;
+  for (int ps = 0; ps < passes; ++ps) {
+    const bool last = ps == passes - 1;
+    int32_t* lout = (last ? lab_b : lab_a) + (size_t)h * N;
+    int32_t* vout = (last ? perm : val_a) + (size_t)h * N;
+    const int shift = ps * RBITS;
+    for (int i = tid; i < SMALL_SEGS * RBINS; i += 1024) (&hist[0][0])[i] = 0;
+    __syncthreads();
+    for (int seg = wave; seg < nseg; seg += 16) {
+      const int beg = seg * SEG, end = min(beg + SEG, n);
+      for (int p = beg + lane; p < end; p += 64) atomicAdd(&hist[seg][(lin[p] >> shift) & (RBINS - 1)], 1);
+    }
+    __syncthreads();
+    {   // exclusive scan, bins major, segments minor (as radix_scan)
+      const int b = tid & (RBINS - 1), g = tid >> RBITS;
+      const int per = (nseg + 7) / 8;
+      const int s0 = min(nseg, g * per), s1 = min(nseg, s0 + per);
+      int run = 0;
+      for (int sg = s0; sg < s1; ++sg) { const int c = hist[sg][b]; hist[sg][b] = run; run += c; }
+      gsum[g][b] = run;
+      __syncthreads();
+      int before = 0, all = 0;
+      for (int i = 0; i < 8; ++i) { const int v = gsum[i][b]; if (i < g) before += v; all += v; }
+      if (g == 0) tot[b] = all;
+      __syncthreads();
+      int base = before;
+      for (int i = 0; i < b; ++i) base += tot[i];
+      for (int sg = s0; sg < s1; ++sg) hist[sg][b] += base;
+    }
+    __syncthreads();
+    for (int seg = wave; seg < nseg; seg += 16) {
+      const int beg = seg * SEG, end = min(beg + SEG, n);
+      volatile int32_t* base = hist[seg];          // touched by this wave only, in program order
+      for (int p0 = beg; p0 < end; p0 += 64) {
+        const int p = p0 + lane;
+        const bool valid = p < end;
+        const int l = valid ? lin[p] : 0;
+        const int v = valid ? (vin ? vin[p] : p) : 0;
+        const int dig = (l >> shift) & (RBINS - 1);
+        uint64_t same = __ballot(valid);
+#pragma unroll
+        for (int b = 0; b < RBITS; ++b) {
+          const bool bit = (dig >> b) & 1;
+          const uint64_t bal = __ballot(bit);
+          same &= bit ? bal : ~bal;
+        }
+        const int rank = __popcll(same & lt_mask);
+        const int cnt = __popcll(same);
+        int pos = 0;
+        if (valid) pos = base[dig] + rank;
+        __builtin_amdgcn_wave_barrier();
+        if (valid && rank == 0) base[dig] = base[dig] + cnt;
+        __builtin_amdgcn_wave_barrier();
+        if (valid) { lout[pos] = l; vout[pos] = v; }
+      }
+    }
+    __syncthreads();        // the pass's output is read back by other waves of this workgroup
+    lin = lout; vin = vout;
+  }
+  // offs[j] = number of sorted labels < j (j = 0..m)
+  const int m = m_dev ? m_dev[(size_t)h * m_stride] : m_const;
+  int32_t* of = offs + (size_t)h * offs_stride;
+  for (int j = tid; j <= m; j += 1024) {
+    int lo = 0, hi = n;
+    while (lo < hi) { const int mid = (lo + hi) >> 1; if (lin[mid] < j) lo = mid + 1; else hi = mid; }
+    of[j] = lo;
+  }
+  if (!poff) return;
+  __syncthreads();
+  // poff[j] = number of parts of the clusters before j (a cluster of c rows has ceil(c / part_rows) parts)
+  int32_t* po = poff + (size_t)h * offs_stride;
+  const int per = (m + 1023) / 1024;
+  const int j0 = min(m, tid * per), j1 = min(m, j0 + per);
+  int run = 0;
+  for (int j = j0; j < j1; ++j) run += (of[j + 1] - of[j] + part_rows - 1) / part_rows;
+  sc[tid] = run;
+  __syncthreads();
+  for (int o = 1; o < 1024; o <<= 1) {
+    const int v = tid >= o ? sc[tid - o] : 0;
+    __syncthreads();
+    sc[tid] += v;
+    __syncthreads();
+  }
+  int base = sc[tid] - run;
+  for (int j = j0; j < j1; ++j) { po[j] = base; base += (of[j + 1] - of[j] + part_rows - 1) / part_rows; }
+  if (tid == 1023) po[m] = sc[1023];
+}
+
 int launch_sort(hipStream_t st, int H, int N, int n_bound, int m_bound,
                 const int32_t* labels, const int32_t* ulist,
                 const int32_t* n_dev, int n_stride, const int32_t* m_dev, int m_stride,
                 const int32_t* active_dev, int active_stride,
-                int32_t* perm, int32_t* offs, int offs_stride, const SortScratch& sc) {
+                int32_t* perm, int32_t* offs, int offs_stride, const SortScratch& sc, int32_t* poff,
+                int part_rows, int* poff_done) {
   SortArgs a{n_dev, n_stride, n_bound, active_dev, active_stride};
   const int nseg = (n_bound + SEG - 1) / SEG;
   int bits = 1;
   while ((1 << bits) < m_bound) ++bits;
   const int passes = (bits + RBITS - 1) / RBITS;
+  if (poff_done) *poff_done = 0;
+#ifndef SORT_SMALL_LIMIT
+#define SORT_SMALL_LIMIT 32
+#endif
+  if (nseg <= SORT_SMALL_LIMIT) {
+    sort_small<<<H, 1024, 0, st>>>(labels, ulist, N, passes, a, m_dev, m_stride, m_bound, sc.lab_a, sc.val_a, sc.lab_b,
+                                   perm, offs, offs_stride, poff, part_rows);
+    if (poff_done && poff) *poff_done = 1;
+    return hipGetLastError() == hipSuccess ? 0 : ADACLUSTER_E_INTERNAL;
+  }
   dim3 g(nseg, H);
   const int32_t* lin = labels;
   const int32_t* vin = ulist;
