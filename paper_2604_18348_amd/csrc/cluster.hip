@@ -342,13 +342,16 @@ __global__ __launch_bounds__(64) void seg_reduce(const T* __restrict__ X, Reduce
       }
     }
   };
-  // The wave first fetches up to 64 row indices with one coalesced load, then keeps UNR row
-  // gathers in flight per lane.  Every lane runs the same number of steps (the shuffles in
-  // add_row need all lanes of a row present); rows past the end contribute nothing.
-  constexpr int UNR = 4;
+  // The wave fetches up to 64 row indices with one coalesced load (the next 64 while the current
+  // rows are summed), then keeps UNR row gathers in flight per lane: small clusters are bound by
+  // the number of dependent memory round trips, not by bytes.  Every lane runs the same number of
+  // steps (the shuffles in add_row need all lanes of a row present); rows past the end contribute
+  // nothing.  The order in which a lane adds its rows is ascending, whatever UNR is.
+  constexpr int UNR = 8;
+  int idx_next = (mb + lane < me) ? pm[mb + lane] : 0;
   for (int r0 = mb; r0 < me; r0 += 64) {
-    const int my = r0 + lane;
-    const int idx = my < me ? pm[my] : 0;
+    const int idx = idx_next;
+    if (r0 + 64 < me) idx_next = (r0 + 64 + lane < me) ? pm[r0 + 64 + lane] : 0;
     const int nhere = min(64, me - r0);
     for (int k0 = 0; k0 < nhere; k0 += UNR * RPI) {
       float x[UNR][EV];
@@ -745,7 +748,8 @@ __global__ __launch_bounds__(256) void filter_scatter(const KState* __restrict__
   }
 }
 
-// The three filter passes in one workgroup per head, for heads whose |U| is small.
+// The three filter passes in one workgroup per head, for heads whose |U| is small.  A thread takes
+// four consecutive items per step (4096 per workgroup step), so most heads need one step.
 __global__ __launch_bounds__(1024) void filter_small(KState* __restrict__ st, const float* __restrict__ dist2, int N,
                                                      const float* __restrict__ tau,
                                                      const int32_t* __restrict__ ulist_in,
@@ -757,21 +761,37 @@ __global__ __launch_bounds__(1024) void filter_small(KState* __restrict__ st, co
   const int n = min(s0.ucount, N);
   const float t2 = tau[1];
   __shared__ int32_t ws[16];
-  const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  const float* dh = dist2 + (size_t)h * N;
+  const int32_t* uin = ulist_in ? ulist_in + (size_t)h * N : nullptr;
+  int32_t* uout = ulist_out + (size_t)h * N;
+  int32_t* sof = stage_of ? stage_of + (size_t)h * N : nullptr;
   int run = 0;
-  for (int base = 0; base < n; base += 1024) {
-    const int p = base + tid;
-    const bool valid = p < n;
-    const bool keep = valid && !(dist2[(size_t)h * N + p] < t2);
-    const int tok = valid ? (ulist_in ? ulist_in[(size_t)h * N + p] : p) : 0;
-    const uint64_t bal = __ballot(keep);
+  for (int base = 0; base < n; base += 4096) {
+    const int p0 = base + 4 * tid;
+    bool keep[4]; int tok[4]; int c = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int p = p0 + i;
+      const bool valid = p < n;
+      keep[i] = valid && !(dh[p < n ? p : 0] < t2);
+      tok[i] = valid ? (uin ? uin[p] : p) : -1;
+      c += keep[i] ? 1 : 0;
+    }
+    // exclusive prefix of the per-thread counts: inside the wave by shuffles, across waves through LDS
+    int incl = c;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) { const int v = __shfl_up(incl, o); if (lane >= o) incl += v; }
     __syncthreads();
-    if (lane == 0) ws[wave] = __popcll(bal);
+    if (lane == 63) ws[wave] = incl;
     __syncthreads();
     int before = 0, total = 0;
-    for (int w = 0; w < 16; ++w) { const int c = ws[w]; if (w < wave) before += c; total += c; }
-    if (keep) ulist_out[(size_t)h * N + run + before + __popcll(bal & lt_mask)] = tok;
-    if (valid && !keep && stage_of) stage_of[(size_t)h * N + tok] = stage;
+    for (int w = 0; w < 16; ++w) { const int v = ws[w]; if (w < wave) before += v; total += v; }
+    int pos = run + before + incl - c;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (keep[i]) uout[pos++] = tok[i];
+      else if (tok[i] >= 0 && sof) sof[tok[i]] = stage;
+    }
     run += total;
   }
   __syncthreads();      // every thread has taken its copy of the state

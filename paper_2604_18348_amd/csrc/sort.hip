@@ -130,9 +130,9 @@ __global__ void label_offsets(const int32_t* __restrict__ sorted, int N, SortArg
 // The whole sort of one head in ONE workgroup, for heads of at most SMALL_SEGS segments: all radix
 // passes, the label offsets and (optionally) the part offsets of the centroid reduction, which
 // otherwise take five launches per pass of a few microseconds each.  Same arithmetic, same stable
-// order as the kernels above: wave w takes segments w, w+16, ...; the per-(segment, digit) counts
-// live in LDS.
-static constexpr int SMALL_SEGS = 64;
+// order as the kernels above: wave w takes segments w and w+16 and holds their items in registers for
+// the whole pass; the per-(segment, digit) counts live in LDS.
+static constexpr int SMALL_SEGS = 32;
 __global__ __launch_bounds__(1024) void sort_small(const int32_t* __restrict__ labels, const int32_t* __restrict__ vals_in,
                                                    int N, int passes, SortArgs a, const int32_t* __restrict__ m_dev,
                                                    int m_stride, int m_const, int32_t* __restrict__ lab_a,
@@ -155,12 +155,25 @@ __global__ __launch_bounds__(1024) void sort_small(const int32_t* __restrict__ l
     int32_t* lout = (last ? lab_b : lab_a) + (size_t)h * N;
     int32_t* vout = (last ? perm : val_a) + (size_t)h * N;
     const int shift = ps * RBITS;
-    for (int i = tid; i < SMALL_SEGS * RBINS; i += 1024) (&hist[0][0])[i] = 0;
+    for (int i = tid; i < nseg * RBINS; i += 1024) (&hist[0][0])[i] = 0;
+    // this wave's items of the pass, all loads in flight at once: segment wave + 16*i, item 64*k + lane
+    int lab[SMALL_SEGS / 16][SEG / 64], val[SMALL_SEGS / 16][SEG / 64];
+#pragma unroll
+    for (int i = 0; i < SMALL_SEGS / 16; ++i)
+#pragma unroll
+      for (int k = 0; k < SEG / 64; ++k) {
+        const int p = (wave + 16 * i) * SEG + 64 * k + lane;
+        lab[i][k] = p < n ? lin[p] : 0;
+        val[i][k] = p < n ? (vin ? vin[p] : p) : 0;
+      }
     __syncthreads();
-    for (int seg = wave; seg < nseg; seg += 16) {
-      const int beg = seg * SEG, end = min(beg + SEG, n);
-      for (int p = beg + lane; p < end; p += 64) atomicAdd(&hist[seg][(lin[p] >> shift) & (RBINS - 1)], 1);
-    }
+#pragma unroll
+    for (int i = 0; i < SMALL_SEGS / 16; ++i)
+#pragma unroll
+      for (int k = 0; k < SEG / 64; ++k) {
+        const int seg = wave + 16 * i, p = seg * SEG + 64 * k + lane;
+        if (p < n) atomicAdd(&hist[seg][(lab[i][k] >> shift) & (RBINS - 1)], 1);
+      }
     __syncthreads();
     {   // exclusive scan, bins major, segments minor (as radix_scan)
       const int b = tid & (RBINS - 1), g = tid >> RBITS;
@@ -172,22 +185,31 @@ __global__ __launch_bounds__(1024) void sort_small(const int32_t* __restrict__ l
       __syncthreads();
       int before = 0, all = 0;
       for (int i = 0; i < 8; ++i) { const int v = gsum[i][b]; if (i < g) before += v; all += v; }
-      if (g == 0) tot[b] = all;
+      // exclusive prefix of the bin totals: the first two waves scan 64 bins each by shuffles
+      int incl = all;
+      if (g == 0) {
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) { const int v = __shfl_up(incl, o); if (lane >= o) incl += v; }
+        tot[b] = incl - all;
+        if (b == 63) sc[0] = incl;             // total of bins 0..63
+      }
       __syncthreads();
-      int base = before;
-      for (int i = 0; i < b; ++i) base += tot[i];
+      const int base = before + tot[b] + (b >= 64 ? sc[0] : 0);
       for (int sg = s0; sg < s1; ++sg) hist[sg][b] += base;
     }
     __syncthreads();
-    for (int seg = wave; seg < nseg; seg += 16) {
-      const int beg = seg * SEG, end = min(beg + SEG, n);
-      volatile int32_t* base = hist[seg];          // touched by this wave only, in program order
-      for (int p0 = beg; p0 < end; p0 += 64) {
-        const int p = p0 + lane;
-        const bool valid = p < end;
-        const int l = valid ? lin[p] : 0;
-        const int v = valid ? (vin ? vin[p] : p) : 0;
+#pragma unroll
+    for (int i = 0; i < SMALL_SEGS / 16; ++i) {
+      const int seg = wave + 16 * i;
+      if (seg >= nseg) break;                        // wave-uniform
+      volatile int32_t* base = hist[seg];            // touched by this wave only, in program order
+#pragma unroll
+      for (int k = 0; k < SEG / 64; ++k) {
+        const int p = seg * SEG + 64 * k + lane;
+        const bool valid = p < n;
+        const int l = lab[i][k], v = val[i][k];
         const int dig = (l >> shift) & (RBINS - 1);
+        // lanes holding my digit: intersect, bit by bit, the ballots of lanes that agree with me
         uint64_t same = __ballot(valid);
 #pragma unroll
         for (int b = 0; b < RBITS; ++b) {
@@ -224,17 +246,16 @@ __global__ __launch_bounds__(1024) void sort_small(const int32_t* __restrict__ l
   const int j0 = min(m, tid * per), j1 = min(m, j0 + per);
   int run = 0;
   for (int j = j0; j < j1; ++j) run += (of[j + 1] - of[j] + part_rows - 1) / part_rows;
-  sc[tid] = run;
+  int incl = run;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) { const int v = __shfl_up(incl, o); if (lane >= o) incl += v; }
+  if (lane == 63) sc[wave] = incl;
   __syncthreads();
-  for (int o = 1; o < 1024; o <<= 1) {
-    const int v = tid >= o ? sc[tid - o] : 0;
-    __syncthreads();
-    sc[tid] += v;
-    __syncthreads();
-  }
-  int base = sc[tid] - run;
+  int before = 0, total = 0;
+  for (int w = 0; w < 16; ++w) { const int v = sc[w]; if (w < wave) before += v; total += v; }
+  int base = before + incl - run;
   for (int j = j0; j < j1; ++j) { po[j] = base; base += (of[j + 1] - of[j] + part_rows - 1) / part_rows; }
-  if (tid == 1023) po[m] = sc[1023];
+  if (tid == 0) po[m] = total;
 }
 
 int launch_sort(hipStream_t st, int H, int N, int n_bound, int m_bound,
@@ -252,6 +273,7 @@ int launch_sort(hipStream_t st, int H, int N, int n_bound, int m_bound,
 #ifndef SORT_SMALL_LIMIT
 #define SORT_SMALL_LIMIT 32
 #endif
+  static_assert(SORT_SMALL_LIMIT <= SMALL_SEGS, "the one-workgroup sort holds SMALL_SEGS segments");
   if (nseg <= SORT_SMALL_LIMIT) {
     sort_small<<<H, 1024, 0, st>>>(labels, ulist, N, passes, a, m_dev, m_stride, m_bound, sc.lab_a, sc.val_a, sc.lab_b,
                                    perm, offs, offs_stride, poff, part_rows);
