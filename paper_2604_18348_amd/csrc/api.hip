@@ -53,7 +53,8 @@ AuxStream g_aux[64];
 struct StageReadback {
   bool ready = false;
   int device = -1;
-  int32_t* host = nullptr;     // [ADACLUSTER_MAX_STAGES + 2][4]
+  int32_t* host = nullptr;     // [ADACLUSTER_MAX_STAGES + 2][4], pinned and mapped
+  int32_t* dev = nullptr;      // the same memory as the device sees it
   hipEvent_t ev[2] = {nullptr, nullptr};
 };
 thread_local StageReadback t_readback;
@@ -69,7 +70,8 @@ StageReadback* stage_readback() {
   }
   if (!r.ready) {
     r.device = dev;
-    if (hipHostMalloc((void**)&r.host, (ADACLUSTER_MAX_STAGES + 2) * 4 * sizeof(int32_t), hipHostMallocDefault) != hipSuccess) return nullptr;
+    if (hipHostMalloc((void**)&r.host, (ADACLUSTER_MAX_STAGES + 2) * 4 * sizeof(int32_t), hipHostMallocMapped) != hipSuccess) return nullptr;
+    if (hipHostGetDevicePointer((void**)&r.dev, r.host, 0) != hipSuccess) return nullptr;
     for (int i = 0; i < 2; ++i)
       if (hipEventCreateWithFlags(&r.ev[i], hipEventDisableTiming) != hipSuccess) return nullptr;
     r.ready = true;
@@ -289,7 +291,7 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
                  float* tau_used, int* kc_bound_out) {
   const Dims D = dims_of(p);
   int kc_bound = 0;   // sum over stages of the largest stage centre count: an upper bound of every |C|
-  hipEvent_t pending_ev = nullptr;   // the last report copy may still be in flight when the stage loop ends
+  hipEvent_t pending_ev = nullptr;   // the last report may still be in flight when the stage loop ends
   int poff_done = 0;                 // set when the sort has already cut the clusters into reduction parts
   if (p->k_init_mode == 1) {
     // warm start: one pseudo-stage over all tokens with the previous centres, count fixed
@@ -330,10 +332,10 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
   int n_bound = D.N, m_bound = p->k_m0 < D.N ? p->k_m0 : D.N;
   for (int t = 0; t <= p->k_max_stages; ++t) {
     pending_ev = rb->ev[t & 1];
+    // the stage head writes its report straight into the pinned slot (no copy in between)
     RET_IF(launch_kstage_begin(st, w.kstate, D.H, D.N, p->k_max_clusters, p->k_m0, p->k_m_min, p->k_max_stages,
-                               u_min, w.summary));
-    if (hipMemcpyAsync(rb->host + 4 * t, w.summary, 3 * sizeof(int32_t), hipMemcpyDeviceToHost, st) != hipSuccess ||
-        hipEventRecord(rb->ev[t & 1], st) != hipSuccess)
+                               u_min, rb->dev + 4 * t));
+    if (hipEventRecord(rb->ev[t & 1], st) != hipSuccess)
       return fail(ADACLUSTER_E_INTERNAL, "stage read-back failed: %s", hipGetErrorString(hipGetLastError()));
     if (t > 0) {
       if (hipEventSynchronize(rb->ev[(t - 1) & 1]) != hipSuccess)
@@ -385,8 +387,8 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
   RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 2, 0, D.cap, P, D.cap, D.cap, w.kstate, 0, 0, want_box, w.offs_k,
                          D.cap + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax, nullptr, nullptr, nullptr, nullptr, k_centroids,
                          k_assign, k_sizes, nullptr, k_bmin, k_bmax));
-  // the pinned report slots are reused by the next call of this thread: let the last copy land
-  // (it was queued ahead of everything above, so this does not drain the stream)
+  // the pinned report slots are reused by the next call of this thread: let the last report land
+  // (its kernel was queued ahead of everything above, so this does not drain the stream)
   if (pending_ev && hipEventSynchronize(pending_ev) != hipSuccess)
     return fail(ADACLUSTER_E_INTERNAL, "stage read-back failed: %s", hipGetErrorString(hipGetLastError()));
   return 0;

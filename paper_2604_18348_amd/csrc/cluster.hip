@@ -303,13 +303,33 @@ __global__ __launch_bounds__(64) void seg_reduce(const T* __restrict__ X, Reduce
   if (!reduce_setup(cfg, h, m)) return;
   // part b of this head -> (cluster j, part index): parts of REDUCE_ROWS rows, clusters in order
   const int32_t* po = poff + (size_t)h * offs_stride;
+  const int32_t* of = offs + (size_t)h * offs_stride;
   const int b = blockIdx.x;
-  if (b >= po[m]) return;
-  int lo = 0, hi = m - 1;
-  while (lo < hi) { const int mid = (lo + hi + 1) >> 1; if (po[mid] <= b) lo = mid; else hi = mid - 1; }
-  const int j = lo, part = b - po[j];
   const int lane = threadIdx.x, slot = lane / LPR, cl = lane % LPR;
-  const int beg = offs[(size_t)h * offs_stride + j], end = offs[(size_t)h * offs_stride + j + 1];
+  int j, part, beg, end;
+  if (m <= 128) {
+    // few clusters: every lane takes two entries of both tables in one round trip and the
+    // cluster of this part is found by a vote (j = number of clusters that start at or before b)
+    const int a0 = lane, a1 = lane + 64;
+    const int p0 = a0 <= m ? po[a0] : INT32_MAX, p1 = a1 <= m ? po[a1] : INT32_MAX;
+    const int o0 = a0 <= m ? of[a0] : 0, o1 = a1 <= m ? of[a1] : 0;
+    const int o2 = of[m], ptotal = po[m];
+    if (b >= ptotal) return;
+    // entries 0..m-1 are cluster starts, entry m is the total
+    const int cnt = __popcll(__ballot(a0 < m && p0 <= b)) + __popcll(__ballot(a1 < m && p1 <= b));
+    j = cnt - 1;
+    const int pj = j < 64 ? __shfl(p0, j) : __shfl(p1, j - 64);
+    part = b - pj;
+    beg = j < 64 ? __shfl(o0, j) : __shfl(o1, j - 64);
+    const int jn = j + 1;
+    end = jn == m ? o2 : (jn < 64 ? __shfl(o0, jn) : __shfl(o1, jn - 64));
+  } else {
+    if (b >= po[m]) return;
+    int lo = 0, hi = m - 1;
+    while (lo < hi) { const int mid = (lo + hi + 1) >> 1; if (po[mid] <= b) lo = mid; else hi = mid - 1; }
+    j = lo; part = b - po[j];
+    beg = of[j]; end = of[j + 1];
+  }
   const int mb = beg + part * REDUCE_ROWS;
   const int me = min(end, mb + REDUCE_ROWS);
   const int32_t* pm = perm + (size_t)h * cfg.N;
