@@ -24,7 +24,10 @@ def dt_name(dtype):
 
 
 @pytest.mark.parametrize("dtype,d,N,Cq", [(B.BF16, 64, 3000, 17), (B.BF16, 128, 2511, 65), (B.F32, 64, 1500, 9),
-                                          (B.F32, 128, 700, 5), (B.BF16, 64, 70, 65)])
+                                          (B.F32, 128, 700, 5), (B.BF16, 64, 70, 65),
+                                          # both sides of the size at which the label sort changes from one
+                                          # workgroup per head to one wave per 512-item segment
+                                          (B.BF16, 64, 16384, 33), (B.BF16, 64, 16400, 33)])
 def test_qcluster_chained(dtype, d, N, Cq):
     H = 2
     Q, _, _ = wl.make_small(11, N, d, 10, dtype=dt_name(dtype), H=H)
@@ -161,6 +164,19 @@ def test_kcluster_chained(dtype, d, N, M):
     tau_ref = orc.tau_from_factor([K[h] for h in range(H)], 1.5, p.k_m0, p.k_iters, round_fn=rf)
     print("tau gpu", tau, "oracle", tau_ref)
     assert math.isclose(tau, tau_ref, rel_tol=2e-3)
+
+
+def test_kcluster_more_than_128_stage_centres():
+    """Stage centre counts above 128 need two radix passes of the label sort, here inside the
+    one-workgroup-per-head kernels (small heads)."""
+    H, N, d = 2, 6144, 64
+    _, K, _ = wl.make_small(23, N, d, 48, dtype="bf16", H=H)
+    p = B.Params(H=H, N=N, d=d, dtype=B.BF16, q_clusters=8, k_iters=3, k_m0=160, k_m_min=8, k_max_clusters=480,
+                 tau_factor=1.5, min_unassigned_frac=0.02)
+    out = B.adacluster_kcluster(p, to_dev(K, B.BF16))
+    torch.cuda.synchronize()
+    check_kcluster(K, p, out, B.BF16)
+    assert int(out["k_count"].cpu().numpy().min()) >= 160
 
 
 def test_kcluster_absolute_tau_and_limits():
