@@ -126,9 +126,10 @@ struct AttnArgs {
 };
 
 // position in the concatenation of ranges -> permuted key row; a cursor that only moves forward
-struct RangeCursor {
-  const int32_t* rs; const int32_t* rp; int nr; int r; int cur_end; int delta;
-  __device__ __forceinline__ void init(const int32_t* rs_, const int32_t* rp_, int nr_) {
+template <typename PTR>
+struct RangeCursorT {
+  PTR rs; PTR rp; int nr; int r; int cur_end; int delta;
+  __device__ __forceinline__ void init(PTR rs_, PTR rp_, int nr_) {
     rs = rs_; rp = rp_; nr = nr_; r = 0;
     cur_end = nr > 0 ? rp[1] : 0;
     delta = nr > 0 ? rs[0] - rp[0] : 0;
@@ -141,6 +142,8 @@ struct RangeCursor {
     return r < nr ? p + delta : -1;
   }
 };
+typedef RangeCursorT<const int32_t*> RangeCursor;
+typedef __attribute__((address_space(3))) const int32_t lds_ci32_t;
 
 // ------------------------------------------------------------------------------------------
 // bf16 MFMA kernel
@@ -203,8 +206,15 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
   bf16raw* Oh = (bf16raw*)a.O + (size_t)h * a.N * D;
   const int32_t* pq = a.perm_q ? a.perm_q + (size_t)h * a.N : nullptr;
 
-  __shared__ __attribute__((aligned(16))) char Ks[2][TILEB];
-  __shared__ __attribute__((aligned(16))) char Vs[2][TILEB];
+  // Every tile buffer is an LDS object of its own, and the tile loop below is unrolled so that each
+  // access names its buffer at compile time: the compiler orders an LDS read behind an outstanding
+  // direct-to-LDS load only when both may touch the same object, so this is what lets the load of
+  // tile t+1 run under the arithmetic of tile t (with one array indexed by t & 1 it put a
+  // vmcnt(0) wait in front of the first operand read of every tile).
+  __shared__ __attribute__((aligned(16))) char K0[TILEB];
+  __shared__ __attribute__((aligned(16))) char K1[TILEB];
+  __shared__ __attribute__((aligned(16))) char V0[TILEB];
+  __shared__ __attribute__((aligned(16))) char V1[TILEB];
   __shared__ int32_t ridx[4][BN];          // byte offset of each key row of a tile
 
   // query tokens of this lane and the B operand of S
@@ -236,15 +246,15 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
   for (int qb = 0; qb < QB; ++qb) { mrun[qb] = -INFINITY; lrun[qb] = 0.f; }
 
   // thread -> (row, slot) of its PT chunks; the slot holds global chunk slot ^ (row & 7)
-  auto issue_loads = [&](int buf, int rb) {
+  auto issue_loads = [&](char* kdst, char* vdst, int rb) {
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
       const int item = tid + i * NT;
       const int r = item / CH, q = item % CH;
       const uint32_t off = (uint32_t)ridx[rb][r] + (uint32_t)((q ^ (r & 7)) * 16);
       const int dst = (wave * 64 + i * NT) * 16;     // wave-uniform; the lane offset is implicit
-      __builtin_amdgcn_global_load_lds(Kh + off, (lds_void_t*)(Ks[buf] + dst), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(Vh + off, (lds_void_t*)(Vs[buf] + dst), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(Kh + off, (lds_void_t*)(kdst + dst), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(Vh + off, (lds_void_t*)(vdst + dst), 16, 0, 0);
     }
   };
 
@@ -267,10 +277,9 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
   const bf16x2_t ones2 = {(__bf16)1.0f, (__bf16)1.0f};   // row sums use the rounded probabilities P V uses
   const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-  auto compute_tile = [&](int buf, int nvalid /* < BN only on a masked tail tile */, auto masked) {
+  auto compute_tile = [&](const char* ks_, const char* vs_, int nvalid /* < BN only on a masked tail tile */,
+                          auto masked) {
     constexpr bool MASK = decltype(masked)::value;
-    const char* ks_ = Ks[buf];
-    const char* vs_ = Vs[buf];
     f32x16_t sacc[2][QB];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
@@ -364,30 +373,56 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
 
   // prologue: row offsets of tiles 0..2 (a slot past the end repeats the first row: it is loaded
   // but masked), tile 0 into LDS
+  // The range table of a query cluster is short (at most top-k entries): it is copied to LDS, so
+  // that walking it issues no vector-memory load (those complete in order with the tile loads and
+  // would make the walking wave wait for the tile just requested).  A longer table stays in HBM.
+  constexpr int RNG_LDS = 256;
+  __shared__ int32_t rng_s[RNG_LDS], rng_p[RNG_LDS + 1];
+  const bool rng_in_lds = nr <= RNG_LDS;
+  if (rng_in_lds) {
+    for (int i = tid; i < nr; i += NT) rng_s[i] = rs[i];
+    for (int i = tid; i <= nr; i += NT) rng_p[i] = rp[i];
+  }
+  __syncthreads();
   RangeCursor cur;
+  RangeCursorT<lds_ci32_t*> cur_l;
   const int first_off = nr > 0 ? rs[0] * ROWB : 0;
-  auto row_off = [&](int p) { const int r = cur.row(p); return r < 0 ? first_off : r * ROWB; };
+  auto row_off = [&](int p) {
+    const int r = rng_in_lds ? cur_l.row(p) : cur.row(p);
+    return r < 0 ? first_off : r * ROWB;
+  };
   if (tid < BN) {
-    cur.init(rs, rp, nr);
+    if (rng_in_lds) cur_l.init((lds_ci32_t*)rng_s, (lds_ci32_t*)rng_p, nr);
+    else cur.init(rs, rp, nr);
     ridx[0][tid] = row_off(tid);
     ridx[1][tid] = row_off(BN + tid);
     ridx[2][tid] = row_off(2 * BN + tid);
   }
   __syncthreads();
-  if (T > 0) issue_loads(0, 0);
+  if (T > 0) issue_loads(K0, V0, 0);
   __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's tile chunks have landed in LDS
   __syncthreads();
 
-  // full tiles in the loop; a ragged tail tile (the only one that needs masking) after it
+  // full tiles in the loop, two per trip (tile t lives in buffer t & 1); a ragged tail tile (the
+  // only one that needs masking) after it
   const int Tfull = total / BN;
-  for (int t = 0; t < Tfull; ++t) {
-    if (t + 1 < T) issue_loads((t + 1) & 1, (t + 1) & 3);
+  auto step = [&](int t, const char* kc, const char* vc, char* kn, char* vn) {
+    if (t + 1 < T) issue_loads(kn, vn, (t + 1) & 3);
     if (tid < BN && t + 3 < T) ridx[(t + 3) & 3][tid] = row_off((t + 3) * BN + tid);
-    if (wave_has_rows) compute_tile(t & 1, BN, std::false_type{});
+    if (wave_has_rows) compute_tile(kc, vc, BN, std::false_type{});
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
+  };
+  int t = 0;
+  for (; t + 2 <= Tfull; t += 2) {
+    step(t, K0, V0, K1, V1);
+    step(t + 1, K1, V1, K0, V0);
   }
-  if (T > Tfull && wave_has_rows) compute_tile(Tfull & 1, total - Tfull * BN, std::true_type{});
+  if (t < Tfull) { step(t, K0, V0, K1, V1); ++t; }
+  if (T > Tfull && wave_has_rows) {
+    if (Tfull & 1) compute_tile(K1, V1, total - Tfull * BN, std::true_type{});
+    else compute_tile(K0, V0, total - Tfull * BN, std::true_type{});
+  }
 
   // O^T accumulator value v of block db is column  db*32 + 8*(v/4) + 4*hb + v%4  of query c
 #pragma unroll
@@ -488,12 +523,20 @@ __global__ __launch_bounds__(64) void attn_f32(AttnArgs a) {
 // tile shapes of the bf16 kernel: queries per wave = 32*QB, waves per block NW, blocks per CU MINB
 #ifndef A64_QB
 #define A64_QB 1
+#endif
+#ifndef A64_NW
 #define A64_NW 4
-#define A64_MINB 2
+#endif
+#ifndef A64_MINB
+#define A64_MINB 4
 #endif
 #ifndef A128_QB
 #define A128_QB 1
+#endif
+#ifndef A128_NW
 #define A128_NW 4
+#endif
+#ifndef A128_MINB
 #define A128_MINB 2
 #endif
 
