@@ -18,7 +18,7 @@ thread_local char g_err[256] = "";
 // from the event in from[] (default: the previous recorded stage boundary); the fused call runs
 // the two clusterings side by side, so both of those are timed from the start of the call.
 enum { EV_START = 0, EV_QCLUSTER, EV_KCLUSTER, EV_SELECT, EV_PERMUTE, EV_PLAN, EV_ATTN, EV_STAGES,
-       EV_JOIN = EV_STAGES, EV_COUNT };
+       EV_JOIN = EV_STAGES, EV_JOIN2, EV_COUNT };
 struct Profiler {
   bool enabled = false;
   bool recorded[EV_COUNT] = {};
@@ -45,7 +45,7 @@ void prof_mark(int which, hipStream_t st, int from = -1) {
 struct AuxStream {
   bool ready = false;
   hipStream_t s = nullptr;
-  hipEvent_t fork = nullptr, join = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr, join2 = nullptr;
 };
 AuxStream g_aux[64];
 
@@ -87,6 +87,7 @@ AuxStream* aux_stream() {
     if (hipStreamCreateWithFlags(&a.s, hipStreamNonBlocking) != hipSuccess) return nullptr;
     if (hipEventCreateWithFlags(&a.fork, hipEventDisableTiming) != hipSuccess) return nullptr;
     if (hipEventCreateWithFlags(&a.join, hipEventDisableTiming) != hipSuccess) return nullptr;
+    if (hipEventCreateWithFlags(&a.join2, hipEventDisableTiming) != hipSuccess) return nullptr;
     a.ready = true;
   }
   return &a;
@@ -395,18 +396,29 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
 }
 
 // ---- attention over selected clusters, given both sorts ---------------------------------------
-int run_attention(const adacluster_params* p, const WS& w, hipStream_t st, const void* Q, const void* K,
-                  const void* V, void* O, const int32_t* k_count, const int32_t* sel_idx, const int32_t* sel_cnt) {
+// K and V rows into cluster order (needs only the key label sort)
+int run_permute(const adacluster_params* p, const WS& w, hipStream_t st, const void* K, const void* V, int prof_from) {
+  const Dims D = dims_of(p);
+  RET_IF(launch_permute_kv(st, D.H, D.N, D.d * (int)esize(p), K, V, w.perm_k, w.Kp, w.Vp));
+  prof_mark(EV_PERMUTE, st, prof_from);
+  return 0;
+}
+
+// range lists and query tiles from the selection, then the attention kernel over the permuted rows
+int run_plan_attention(const adacluster_params* p, const WS& w, hipStream_t st, const void* Q, void* O,
+                       const int32_t* k_count, const int32_t* sel_idx, const int32_t* sel_cnt, int prof_from,
+                       hipEvent_t permute_done) {
   const Dims D = dims_of(p);
   const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)D.d);
-  RET_IF(launch_permute_kv(st, D.H, D.N, D.d * (int)esize(p), K, V, w.perm_k, w.Kp, w.Vp));
-  prof_mark(EV_PERMUTE, st);
   RET_IF(launch_plan_sparse(st, D.H, D.Cq, D.cap, D.maxr, D.maxtiles, D.BM, w.offs_q, D.Cq + 1, w.offs_k, D.cap + 1,
                             k_count, sel_idx, sel_cnt, w.rng_start, w.rng_pre, w.rng_cnt, w.tiles, w.ntiles));
-  prof_mark(EV_PLAN, st);
+  prof_mark(EV_PLAN, st, prof_from);
+  if (permute_done && hipStreamWaitEvent(st, permute_done, 0) != hipSuccess)
+    return fail(ADACLUSTER_E_INTERNAL, "stream join failed");
+  if (permute_done) prof_mark(EV_JOIN2, st);
   RET_IF(launch_attention(st, p->dtype, D.d, D.H, D.N, D.Cq, D.maxtiles, D.maxr, scale, Q, w.Kp, w.Vp, O, w.perm_q,
                           w.tiles, w.ntiles, w.rng_start, w.rng_pre, w.rng_cnt));
-  prof_mark(EV_ATTN, st);
+  prof_mark(EV_ATTN, st, permute_done ? EV_JOIN2 : -1);
   return 0;
 }
 
@@ -501,7 +513,8 @@ int adacluster_sparse_attn(const adacluster_params* p, const void* Q, const void
   RET_IF(launch_sort(st, D.H, D.N, D.N, D.cap, k_labels, nullptr, nullptr, 0, k_count, 1, nullptr, 0, w.perm_k, w.offs_k,
                      D.cap + 1, w.sort));
   prof_mark(EV_SELECT, st);   // (time of the two label sorts when called stand-alone)
-  return run_attention(p, w, st, Q, K, V, O, k_count, sel_idx, sel_cnt);
+  if ((rc = run_permute(p, w, st, K, V, -1))) return rc;
+  return run_plan_attention(p, w, st, Q, O, k_count, sel_idx, sel_cnt, -1, nullptr);
 }
 
 int adacluster_attn(const adacluster_params* p, const void* Q, const void* K, const void* V, void* O,
@@ -547,9 +560,22 @@ int adacluster_attn(const adacluster_params* p, const void* Q, const void* K, co
   int rck = rc ? 0 : run_kcluster(p, w, st, K, k_labels, k_centroids, k_assign_centroids, k_bmin, k_bmax, k_sizes,
                                    k_count, full_flag, o.k_stage_offs, o.k_stage_of, tau_used, &kc_bound);
   prof_mark(EV_KCLUSTER, st, EV_START);
+  // The K/V permutation needs only the key label sort: it goes to the second stream too (behind
+  // the query clustering there) and runs beside the selection and the planning.
+  const bool fork2 = !rc && !rck;
+  int rcp = 0;
+  if (fork2) {
+    if (hipEventRecord(aux->fork, st) != hipSuccess || hipStreamWaitEvent(aux->s, aux->fork, 0) != hipSuccess)
+      return fail(ADACLUSTER_E_INTERNAL, "stream fork failed: %s", hipGetErrorString(hipGetLastError()));
+    rcp = run_permute(p, w, aux->s, K, V, EV_KCLUSTER);
+    if (hipEventRecord(aux->join2, aux->s) != hipSuccess) return fail(ADACLUSTER_E_INTERNAL, "stream join failed");
+  }
   if (hipStreamWaitEvent(st, aux->join, 0) != hipSuccess) return fail(ADACLUSTER_E_INTERNAL, "stream join failed");
-  if (rc) return rc;
-  if (rck) return rck;
+  if (rc || rck || rcp) {
+    // whatever was queued on the second stream is joined before the error is reported
+    if (fork2 && hipStreamWaitEvent(st, aux->join2, 0) != hipSuccess) return fail(ADACLUSTER_E_INTERNAL, "stream join failed");
+    return rc ? rc : (rck ? rck : rcp);
+  }
   prof_mark(EV_JOIN, st);
   const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->d);
   RET_IF(launch_select(st, p->H, p->q_clusters, capacity(p), p->d, p->score_mode, p->select_mode, p->topk, p->top_p,
@@ -557,7 +583,7 @@ int adacluster_attn(const adacluster_params* p, const void* Q, const void* K, co
                        sel_idx, sel_cnt, kc_bound));
   prof_mark(EV_SELECT, st, EV_JOIN);
   // both label sorts were left in the workspace by the clustering steps
-  return run_attention(p, w, st, Q, K, V, O, k_count, sel_idx, sel_cnt);
+  return run_plan_attention(p, w, st, Q, O, k_count, sel_idx, sel_cnt, EV_SELECT, aux->join2);
 }
 
 int adacluster_dense_attn(const adacluster_params* p, const void* Q, const void* K, const void* V, void* O,
