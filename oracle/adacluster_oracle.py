@@ -299,6 +299,22 @@ def finalize_key_clusters(K, labels, assign_centroids):
     return cent, sizes.astype(np.int64), bmin, bmax
 
 
+def compactness_mse(K, labels, centroids):
+    """Mean squared reconstruction error of one head (Sec. 3.2.1): the mean over tokens of
+    ||k - c(k)||^2, c(k) the centre of the token's cluster.  The layer score of the paper is
+    Comp = 1 / (mean of this over the heads)."""
+    K = np.asarray(K, dtype=F64)
+    C = np.asarray(centroids, dtype=F64)
+    lab = np.asarray(labels, dtype=np.int64)
+    diff = K - C[lab]
+    return float(np.mean(np.sum(diff * diff, axis=1)))
+
+
+def compactness_score(mse_per_head):
+    """Comp = 1 / mean_h MSE_h (Sec. 3.2.1)."""
+    return 1.0 / float(np.mean(np.asarray(mse_per_head, dtype=F64)))
+
+
 # --------------------------------------------------------------------------
 # cluster scores (Eq. 1, Eq. 2 / Alg. 2, and the mean-based ablation)
 # --------------------------------------------------------------------------

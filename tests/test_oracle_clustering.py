@@ -308,3 +308,30 @@ def test_warm_start_keeps_count_and_follows_lloyd_from_given_centres():
     far = np.concatenate([true_means, np.full((1, 6), 100.0)])
     out2 = orc.warm_key_clustering(X, far, 3)
     assert out2["sizes"][5] == 0 and np.array_equal(out2["assign_centroids"][5], far[5])
+
+
+def test_compactness_mse_pins():
+    """Sec. 3.2.1 MSE: explicit loops; zero when every token is its own centre; for member means the
+    textbook identity sum ||k - c||^2 = sum ||k||^2 - sum_j n_j ||c_j||^2; a shifted centre adds
+    exactly n_j ||shift||^2 (parallel-axis)."""
+    rng = np.random.default_rng(17)
+    N, d, m = 57, 6, 5
+    K = rng.standard_normal((N, d))
+    lab = rng.integers(0, m, N)
+    lab[:m] = np.arange(m)
+    C = rng.standard_normal((m, d))
+    tot = 0.0
+    for n in range(N):
+        for j in range(d):
+            tot += (K[n, j] - C[lab[n], j]) ** 2
+    assert math.isclose(orc.compactness_mse(K, lab, C), tot / N, rel_tol=1e-12)
+    assert orc.compactness_mse(K, np.arange(N), K) == 0.0
+    means = np.stack([K[lab == j].mean(0) for j in range(m)])
+    sizes = np.bincount(lab, minlength=m)
+    ident = (np.sum(K * K) - np.sum(sizes * np.sum(means * means, axis=1))) / N
+    assert math.isclose(orc.compactness_mse(K, lab, means), ident, rel_tol=1e-10)
+    shift = rng.standard_normal(d)
+    moved = means.copy(); moved[2] += shift
+    extra = sizes[2] * float(shift @ shift) / N
+    assert math.isclose(orc.compactness_mse(K, lab, moved), orc.compactness_mse(K, lab, means) + extra, rel_tol=1e-10)
+    assert math.isclose(orc.compactness_score([0.5, 1.5]), 1.0)
