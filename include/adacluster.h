@@ -201,6 +201,17 @@ int adacluster_dense_attn(const adacluster_params* p,
                           void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Compactness of a key clustering (Sec. 3.2.1): k_mse[h] = (1/N) sum_n || k_n - c(k_n) ||^2 with
+ * c(k_n) = k_centroids[h, k_labels[h,n], :]; the paper's layer score is Comp = 1 / mean_h k_mse[h].
+ *   K [H,N,d] in (dtype), k_labels [H,N] in (every label < capacity), k_centroids [H,cap,d] fp32 in,
+ *   k_mse [H] fp32 out.  Squares are summed in fp32 inside a row and in fp64 across rows, in a fixed
+ *   order.  Asynchronous on `stream`; reads no other state, so it may follow adacluster_kcluster or
+ *   adacluster_attn (with those outputs requested) at any time.
+ */
+int adacluster_compactness(const adacluster_params* p, const void* K, const int32_t* k_labels,
+                           const float* k_centroids, float* k_mse, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Stage timing for benchmarks.  adacluster_profile_enable(1) creates HIP events; while enabled,
  * adacluster_attn, adacluster_sparse_attn and adacluster_dense_attn record them on the call's
  * stream at their stage boundaries.  adacluster_profile_read waits for the last recorded call

@@ -99,10 +99,11 @@ def load_library():
     lib.adacluster_sparse_attn.argtypes = [P] + [vp] * 9 + [vp, sz, vp]
     lib.adacluster_attn.argtypes = [P] + [vp] * 4 + [ctypes.POINTER(COutputs), vp, sz, vp]
     lib.adacluster_dense_attn.argtypes = [P] + [vp] * 4 + [vp, sz, vp]
+    lib.adacluster_compactness.argtypes = [P] + [vp] * 4 + [vp, sz, vp]
     lib.adacluster_profile_enable.argtypes = [ctypes.c_int]
     lib.adacluster_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float)]
     for n in ("profile_enable", "profile_read", "centroid_capacity", "workspace_bytes", "last_error", "qcluster", "kcluster", "select",
-              "sparse_attn", "attn", "dense_attn"):
+              "sparse_attn", "attn", "dense_attn", "compactness"):
         getattr(lib, "adacluster_" + n).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -110,7 +111,7 @@ def load_library():
 
 EXPORTED = ["adacluster_centroid_capacity", "adacluster_workspace_bytes", "adacluster_last_error",
             "adacluster_qcluster", "adacluster_kcluster", "adacluster_select",
-            "adacluster_sparse_attn", "adacluster_attn", "adacluster_dense_attn",
+            "adacluster_sparse_attn", "adacluster_attn", "adacluster_dense_attn", "adacluster_compactness",
             "adacluster_profile_enable", "adacluster_profile_read"]
 
 STAGES = ["qcluster", "kcluster", "select", "permute", "plan", "attention"]
@@ -254,6 +255,17 @@ def adacluster_sparse_attn(p: Params, Q, K, V, q_labels, k_labels, k_count, sel_
         ctypes.byref(cp), _ptr(Q), _ptr(K), _ptr(V), _ptr(q_labels), _ptr(k_labels), _ptr(k_count),
         _ptr(sel_idx), _ptr(sel_cnt), _ptr(O), _ptr(ws), ws.numel(), _stream()), "adacluster_sparse_attn")
     return O
+
+
+def adacluster_compactness(p: Params, K, k_labels, k_centroids, ws=None):
+    """Per-head mean squared reconstruction error of a key clustering (Sec. 3.2.1) -> float32 [H]."""
+    ws = workspace(p, K.device) if ws is None else ws
+    mse = torch.empty((p.H,), dtype=torch.float32, device=K.device)
+    cp = p.c()
+    _check(load_library().adacluster_compactness(
+        ctypes.byref(cp), _ptr(K), _ptr(k_labels), _ptr(k_centroids), _ptr(mse), _ptr(ws), ws.numel(), _stream()),
+        "adacluster_compactness")
+    return mse
 
 
 def alloc_outputs(p: Params, dev, want_box=False, want_stage=True):

@@ -476,6 +476,18 @@ int adacluster_kcluster(const adacluster_params* p, const void* K, int32_t* k_la
                       k_sizes, k_count, full_flag, k_stage_offs, k_stage_of, tau_used, nullptr);
 }
 
+int adacluster_compactness(const adacluster_params* p, const void* K, const int32_t* k_labels,
+                           const float* k_centroids, float* k_mse, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_params(p);
+  if (rc) return rc;
+  if (!K || !k_labels || !k_centroids || !k_mse) return fail(ADACLUSTER_E_BADARG, "compactness: NULL pointer");
+  WS w;
+  if ((rc = check_ws(p, ws, ws_bytes, &w))) return rc;
+  RET_IF(launch_mse((hipStream_t)stream, p->dtype, p->d, p->H, p->N, capacity(p), K, k_labels, k_centroids, w.tau_part,
+                    k_mse));
+  return 0;
+}
+
 int adacluster_select(const adacluster_params* p, const float* q_centroids, const float* q_mean_norm,
                       const float* k_centroids, const float* k_box_min, const float* k_box_max,
                       const int32_t* k_sizes, const int32_t* k_count, const int32_t* full_flag,

@@ -844,6 +844,56 @@ __global__ void kstate_export(const KState* __restrict__ st, int H, int32_t* k_c
 }
 
 // ------------------------------------------------------------------------------------------
+// compactness (Sec. 3.2.1): MSE_h = mean_n || k_n - c(k_n) ||^2
+// ------------------------------------------------------------------------------------------
+// One row per group of LPR lanes (16-byte pieces), fp32 inside a row, fp64 across rows; block
+// partials are merged by mse_final in a fixed order.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void mse_partial(const T* __restrict__ X, const int32_t* __restrict__ labels,
+                                                   const float* __restrict__ cent, int N, int cap, int nblk,
+                                                   double* __restrict__ part) {
+  constexpr int EV = Vec16<T>::N, LPR = D / EV, RPB = 256 / LPR;   // rows per block step
+  const int h = blockIdx.y, b = blockIdx.x, tid = threadIdx.x;
+  const int slot = tid / LPR, cl = tid % LPR;
+  double acc = 0.0;
+  const int beg = b * 1024, end = min(N, beg + 1024);
+  for (int r0 = beg; r0 < end; r0 += RPB) {
+    const int r = r0 + slot;
+    float ss = 0.f;
+    if (r < end) {
+      const int j = labels[(size_t)h * N + r];
+      float x[EV];
+      Vec16<T>::load(X + ((size_t)h * N + r) * D + cl * EV, x);
+      const float* c = cent + ((size_t)h * cap + j) * D + cl * EV;
+#pragma unroll
+      for (int e = 0; e < EV; ++e) { const float df = x[e] - c[e]; ss = fmaf(df, df, ss); }
+    }
+#pragma unroll
+    for (int o = 1; o < LPR; o <<= 1) ss += __shfl_xor(ss, o);
+    if (cl == 0) acc += (double)ss;
+  }
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) acc += __shfl_xor(acc, o);
+  __shared__ double ws[4];
+  if ((tid & 63) == 0) ws[tid >> 6] = acc;
+  __syncthreads();
+  if (tid == 0) part[(size_t)h * nblk + b] = (ws[0] + ws[1]) + (ws[2] + ws[3]);
+}
+
+__global__ __launch_bounds__(256) void mse_final(const double* __restrict__ part, int nblk, int N,
+                                                 float* __restrict__ mse) {
+  const int h = blockIdx.x, tid = threadIdx.x;
+  double s = 0.0;
+  for (int i = tid; i < nblk; i += 256) s += part[(size_t)h * nblk + i];
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) s += __shfl_xor(s, o);
+  __shared__ double ws[4];
+  if ((tid & 63) == 0) ws[tid >> 6] = s;
+  __syncthreads();
+  if (tid == 0) mse[h] = (float)(((ws[0] + ws[1]) + (ws[2] + ws[3])) / (double)N);
+}
+
+// ------------------------------------------------------------------------------------------
 // host-side launchers
 // ------------------------------------------------------------------------------------------
 static inline int chk() { return hipGetLastError() == hipSuccess ? 0 : ADACLUSTER_E_INTERNAL; }
@@ -970,6 +1020,21 @@ int launch_filter(hipStream_t s, KState* st, int H, int N, int n_bound, const fl
   filter_scan<<<H, 64, 0, s>>>(st, nb, nblk, blockcnt, u_prev);
   filter_scatter<<<dim3(nb, H), 256, 0, s>>>(st, u_prev, dist2, N, nblk, tau, blockcnt, ulist_in, ulist_out,
                                              stage_of, stage);
+  return chk();
+}
+
+int launch_mse(hipStream_t s, int dtype, int d, int H, int N, int cap, const void* X, const int32_t* labels,
+               const float* cent, double* part, float* mse) {
+  const int nblk = (N + 1023) / 1024;
+  dim3 g(nblk, H);
+  if (dtype == ADACLUSTER_BF16) {
+    if (d == 64) mse_partial<bf16raw, 64><<<g, 256, 0, s>>>((const bf16raw*)X, labels, cent, N, cap, nblk, part);
+    else mse_partial<bf16raw, 128><<<g, 256, 0, s>>>((const bf16raw*)X, labels, cent, N, cap, nblk, part);
+  } else {
+    if (d == 64) mse_partial<float, 64><<<g, 256, 0, s>>>((const float*)X, labels, cent, N, cap, nblk, part);
+    else mse_partial<float, 128><<<g, 256, 0, s>>>((const float*)X, labels, cent, N, cap, nblk, part);
+  }
+  mse_final<<<H, 256, 0, s>>>(part, nblk, N, mse);
   return chk();
 }
 

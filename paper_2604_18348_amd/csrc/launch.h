@@ -50,6 +50,8 @@ int launch_tau(hipStream_t s, int H, int N, const float* dist2, double* part, fl
 int launch_filter(hipStream_t s, KState* st, int H, int N, int n_bound, const float* dist2, const float* tau,
                   int32_t* blockcnt, int32_t* u_prev, const int32_t* ulist_in, int32_t* ulist_out,
                   int32_t* stage_of, int stage);
+int launch_mse(hipStream_t s, int dtype, int d, int H, int N, int cap, const void* X, const int32_t* labels,
+               const float* cent, double* part, float* mse);
 int launch_fill_i32(hipStream_t s, int32_t* p, size_t n, int32_t v);
 int launch_kstate_export(hipStream_t s, const KState* st, int H, int32_t* k_count, int32_t* full_flag,
                          int32_t* stage_offs);

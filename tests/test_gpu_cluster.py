@@ -261,3 +261,24 @@ def test_kcluster_warm_start_chained(dtype, d):
         # free-running comparison: bf16 centre rounding can flip near-tied tokens between
         # neighbouring centres, so only broad agreement is required here (the chained checks above are exact)
         assert agree > (0.95 if dtype == B.BF16 else 0.999) and close > (0.95 if dtype == B.BF16 else 0.999)
+
+
+@pytest.mark.parametrize("dtype,d,N", [(B.BF16, 64, 4100), (B.BF16, 128, 2050), (B.F32, 64, 1500)])
+def test_compactness_matches_oracle(dtype, d, N):
+    """Sec. 3.2.1: per-head MSE of the clustering the GPU produced, against the fp64 oracle on the
+    GPU's own labels and centroids (fp32 inside a row, fp64 across rows: 1e-5 relative)."""
+    H = 3
+    _, K, _ = wl.make_small(31, N, d, 14, dtype=dt_name(dtype), H=H)
+    K[2] = wl.round_bf16_f32(np.random.default_rng(4).standard_normal((N, d)).astype(np.float32))
+    p = B.Params(H=H, N=N, d=d, dtype=dtype, q_clusters=8, k_iters=3, k_m0=20, k_m_min=4, k_max_clusters=80,
+                 tau_factor=1.5, min_unassigned_frac=0.03)
+    Kd = to_dev(K, dtype)
+    out = B.adacluster_kcluster(p, Kd)
+    mse = B.adacluster_compactness(p, Kd, out["k_labels"], out["k_centroids"]).cpu().numpy()
+    torch.cuda.synchronize()
+    lab = out["k_labels"].cpu().numpy()
+    cen = to_np(out["k_centroids"])
+    ref = np.array([orc.compactness_mse(K[h], lab[h], cen[h]) for h in range(H)])
+    print("mse gpu", mse, "oracle", ref)
+    assert np.allclose(mse, ref, rtol=1e-5, atol=1e-7)
+    assert mse[2] > mse[0] and mse[2] > mse[1]          # the isotropic head is the least compact
