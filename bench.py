@@ -21,6 +21,13 @@ BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 FP32_VALU_PEAK_TFLOPS = 157.3
 
 
+# HBM-side traffic of one attention-kernel launch, bytes: FETCH_SIZE (divided by the 0.504 the counter
+# reads for a plain copy of known size) + WRITE_SIZE of the two rocprofv3 --pmc passes summarised in
+# profiles/attn_pipeline_<config>.txt.  A counter cannot be read from inside this script, so the
+# figures are stored; a config without a profile reports null.
+PROFILED_ATTN_TRAFFIC_BYTES = {"c2": 657.8e6, "c3": 270.7e6, "c4": 2474.2e6, "c5": 4378.8e6}
+
+
 def gen_inputs(name, torch, B, wl):
     cfg = wl.CONFIGS[name]
     H, N, d = cfg["H"], wl.n_tokens(cfg), cfg["d"]
@@ -54,16 +61,27 @@ def executed_pairs(outs, p):
     return tot
 
 
-def cpu_baseline(name, wl, budget_heads=1):
-    """The oracle, as it stands, on a bounded sample: whole call on `budget_heads` head(s)."""
+def cpu_baseline(name, wl, target_s=15.0):
+    """The oracle, as it stands, on a bounded sample of the workload: the whole call on the first
+    heads.  One head is timed first; if that leaves room, as many heads as fit about `target_s`
+    seconds are then run in one call (tau is then the mean over those heads) and that run is the
+    one reported."""
     from oracle import adacluster_oracle as orc
     cfg = wl.CONFIGS[name]
-    heads = list(range(budget_heads))
-    Q, K, V = wl.make_qkv(name, heads=heads)
     rf = orc.round_to_bf16 if cfg["dtype"] == "bf16" else None
-    t0 = time.perf_counter()
-    orc.adacluster_attention(Q, K, V, use_gather=True, round_fn=rf, **cfg["params"])
-    dt = time.perf_counter() - t0
+
+    def timed(heads):
+        Q, K, V = wl.make_qkv(name, heads=heads)
+        t0 = time.perf_counter()
+        orc.adacluster_attention(Q, K, V, use_gather=True, round_fn=rf, **cfg["params"])
+        return time.perf_counter() - t0
+
+    heads = [0]
+    dt = timed(heads)
+    more = min(cfg["H"], int(target_s / max(dt, 1e-3)))
+    if more > 1:
+        heads = list(range(more))
+        dt = timed(heads)
     try:
         from threadpoolctl import threadpool_info
         cores = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
@@ -193,7 +211,8 @@ def main():
         "roofline": {"kernel": "attn_mfma" if dtype == B.BF16 else "attn_f32",
                      "bound": "mfma" if dtype == B.BF16 else "alu",
                      "achieved": attn_tflops, "peak": peak, "unit": "TFLOP/s",
-                     "frac": attn_tflops / peak, "traffic": None},
+                     "frac": attn_tflops / peak, "traffic": PROFILED_ATTN_TRAFFIC_BYTES.get(a.config),
+                     "traffic_unit": "bytes per launch (rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE, see profiles/)"},
     }
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(a.config, wl)
