@@ -7,12 +7,10 @@
 // traffic of 4-byte labels and indices.
 #include "common.h"
 #include "launch.h"
+#include "small_head.h"
 
 namespace adac {
 
-static constexpr int SEG = 512;      // items per single-wave block
-static constexpr int RBITS = 7;
-static constexpr int RBINS = 1 << RBITS;
 
 struct SortArgs {
   const int32_t* n_dev;  int n_stride;  int n_const;
@@ -127,135 +125,20 @@ __global__ void label_offsets(const int32_t* __restrict__ sorted, int N, SortArg
   offs[(size_t)h * offs_stride + j] = lo;
 }
 
-// The whole sort of one head in ONE workgroup, for heads of at most SMALL_SEGS segments: all radix
-// passes, the label offsets and (optionally) the part offsets of the centroid reduction, which
-// otherwise take five launches per pass of a few microseconds each.  Same arithmetic, same stable
-// order as the kernels above: wave w takes segments w and w+16 and holds their items in registers for
-// the whole pass; the per-(segment, digit) counts live in LDS.
-static constexpr int SMALL_SEGS = 32;
+// One workgroup per head: see sort_one_head.
 __global__ __launch_bounds__(1024) void sort_small(const int32_t* __restrict__ labels, const int32_t* __restrict__ vals_in,
                                                    int N, int passes, SortArgs a, const int32_t* __restrict__ m_dev,
                                                    int m_stride, int m_const, int32_t* __restrict__ lab_a,
                                                    int32_t* __restrict__ val_a, int32_t* __restrict__ lab_b,
                                                    int32_t* __restrict__ perm, int32_t* __restrict__ offs,
                                                    int offs_stride, int32_t* __restrict__ poff, int part_rows) {
-  const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int h = blockIdx.x;
   if (a.active_dev && !a.active_dev[(size_t)h * a.active_stride]) return;
-  const int n = min(head_items(a, h), SMALL_SEGS * SEG);     // the launcher admits no more
-  const int nseg = (n + SEG - 1) / SEG;
-  __shared__ int32_t hist[SMALL_SEGS][RBINS];
-  __shared__ int32_t gsum[8][RBINS];
-  __shared__ int32_t tot[RBINS];
-  __shared__ int32_t sc[1024];
-  const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-  const int32_t* lin = labels + (size_t)h * N;
-  const int32_t* vin = vals_in ? vals_in + (size_t)h * N : nullptr;
-  for (int ps = 0; ps < passes; ++ps) {
-    const bool last = ps == passes - 1;
-    int32_t* lout = (last ? lab_b : lab_a) + (size_t)h * N;
-    int32_t* vout = (last ? perm : val_a) + (size_t)h * N;
-    const int shift = ps * RBITS;
-    for (int i = tid; i < nseg * RBINS; i += 1024) (&hist[0][0])[i] = 0;
-    // this wave's items of the pass, all loads in flight at once: segment wave + 16*i, item 64*k + lane
-    int lab[SMALL_SEGS / 16][SEG / 64], val[SMALL_SEGS / 16][SEG / 64];
-#pragma unroll
-    for (int i = 0; i < SMALL_SEGS / 16; ++i)
-#pragma unroll
-      for (int k = 0; k < SEG / 64; ++k) {
-        const int p = (wave + 16 * i) * SEG + 64 * k + lane;
-        lab[i][k] = p < n ? lin[p] : 0;
-        val[i][k] = p < n ? (vin ? vin[p] : p) : 0;
-      }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < SMALL_SEGS / 16; ++i)
-#pragma unroll
-      for (int k = 0; k < SEG / 64; ++k) {
-        const int seg = wave + 16 * i, p = seg * SEG + 64 * k + lane;
-        if (p < n) atomicAdd(&hist[seg][(lab[i][k] >> shift) & (RBINS - 1)], 1);
-      }
-    __syncthreads();
-    {   // exclusive scan, bins major, segments minor (as radix_scan)
-      const int b = tid & (RBINS - 1), g = tid >> RBITS;
-      const int per = (nseg + 7) / 8;
-      const int s0 = min(nseg, g * per), s1 = min(nseg, s0 + per);
-      int run = 0;
-      for (int sg = s0; sg < s1; ++sg) { const int c = hist[sg][b]; hist[sg][b] = run; run += c; }
-      gsum[g][b] = run;
-      __syncthreads();
-      int before = 0, all = 0;
-      for (int i = 0; i < 8; ++i) { const int v = gsum[i][b]; if (i < g) before += v; all += v; }
-      // exclusive prefix of the bin totals: the first two waves scan 64 bins each by shuffles
-      int incl = all;
-      if (g == 0) {
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) { const int v = __shfl_up(incl, o); if (lane >= o) incl += v; }
-        tot[b] = incl - all;
-        if (b == 63) sc[0] = incl;             // total of bins 0..63
-      }
-      __syncthreads();
-      const int base = before + tot[b] + (b >= 64 ? sc[0] : 0);
-      for (int sg = s0; sg < s1; ++sg) hist[sg][b] += base;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < SMALL_SEGS / 16; ++i) {
-      const int seg = wave + 16 * i;
-      if (seg >= nseg) break;                        // wave-uniform
-      volatile int32_t* base = hist[seg];            // touched by this wave only, in program order
-#pragma unroll
-      for (int k = 0; k < SEG / 64; ++k) {
-        const int p = seg * SEG + 64 * k + lane;
-        const bool valid = p < n;
-        const int l = lab[i][k], v = val[i][k];
-        const int dig = (l >> shift) & (RBINS - 1);
-        // lanes holding my digit: intersect, bit by bit, the ballots of lanes that agree with me
-        uint64_t same = __ballot(valid);
-#pragma unroll
-        for (int b = 0; b < RBITS; ++b) {
-          const bool bit = (dig >> b) & 1;
-          const uint64_t bal = __ballot(bit);
-          same &= bit ? bal : ~bal;
-        }
-        const int rank = __popcll(same & lt_mask);
-        const int cnt = __popcll(same);
-        int pos = 0;
-        if (valid) pos = base[dig] + rank;
-        __builtin_amdgcn_wave_barrier();
-        if (valid && rank == 0) base[dig] = base[dig] + cnt;
-        __builtin_amdgcn_wave_barrier();
-        if (valid) { lout[pos] = l; vout[pos] = v; }
-      }
-    }
-    __syncthreads();        // the pass's output is read back by other waves of this workgroup
-    lin = lout; vin = vout;
-  }
-  // offs[j] = number of sorted labels < j (j = 0..m)
+  const int n = head_items(a, h);
   const int m = m_dev ? m_dev[(size_t)h * m_stride] : m_const;
-  int32_t* of = offs + (size_t)h * offs_stride;
-  for (int j = tid; j <= m; j += 1024) {
-    int lo = 0, hi = n;
-    while (lo < hi) { const int mid = (lo + hi) >> 1; if (lin[mid] < j) lo = mid + 1; else hi = mid; }
-    of[j] = lo;
-  }
-  if (!poff) return;
-  __syncthreads();
-  // poff[j] = number of parts of the clusters before j (a cluster of c rows has ceil(c / part_rows) parts)
-  int32_t* po = poff + (size_t)h * offs_stride;
-  const int per = (m + 1023) / 1024;
-  const int j0 = min(m, tid * per), j1 = min(m, j0 + per);
-  int run = 0;
-  for (int j = j0; j < j1; ++j) run += (of[j + 1] - of[j] + part_rows - 1) / part_rows;
-  int incl = run;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) { const int v = __shfl_up(incl, o); if (lane >= o) incl += v; }
-  if (lane == 63) sc[wave] = incl;
-  __syncthreads();
-  int before = 0, total = 0;
-  for (int w = 0; w < 16; ++w) { const int v = sc[w]; if (w < wave) before += v; total += v; }
-  int base = before + incl - run;
-  for (int j = j0; j < j1; ++j) { po[j] = base; base += (of[j + 1] - of[j] + part_rows - 1) / part_rows; }
-  if (tid == 0) po[m] = total;
+  const size_t o = (size_t)h * N;
+  sort_one_head(labels + o, vals_in ? vals_in + o : nullptr, n, passes, m, lab_a + o, val_a + o, lab_b + o, perm + o,
+                offs + (size_t)h * offs_stride, poff ? poff + (size_t)h * offs_stride : nullptr, part_rows);
 }
 
 int launch_sort(hipStream_t st, int H, int N, int n_bound, int m_bound,
