@@ -6,8 +6,8 @@
 // costs nothing but one masked tail tile.  The flash-style kernel keeps the S^T = K Q^T
 // orientation: in the 32x32 MFMA accumulator a lane then owns one query and 16 keys, soft-max
 // statistics are per-lane scalars, and the exponentiated block feeds the P V product as the B
-// operand straight from registers.  V is transposed on its way into LDS so that the A operand of
-// that product is one 16-byte read.
+// operand straight from registers.  K and V tiles both sit row-major in LDS; the A operand of that
+// product (a column of V over 8 keys) is gathered by LDS transpose reads.
 #include "common.h"
 #include "launch.h"
 
@@ -148,8 +148,6 @@ typedef __attribute__((address_space(3))) const int32_t lds_ci32_t;
 // ------------------------------------------------------------------------------------------
 // bf16 MFMA kernel
 // ------------------------------------------------------------------------------------------
-// One block = NW waves, each owning QB blocks of 32 queries; all waves share the 64-key K and V
-// tiles.  LDS is double buffered (one barrier per tile); global loads run two tiles ahead.
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4_t;
 typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
 typedef __attribute__((address_space(3))) void lds_void_t;
