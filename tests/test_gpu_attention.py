@@ -85,6 +85,39 @@ def test_selecting_every_cluster_reproduces_dense(dtype):
         check(got[h], orc.dense_attention(Q[h], K[h], V[h]), dtype)
 
 
+def test_more_ranges_than_the_lds_table_holds():
+    """A query cluster whose selection is > 256 separate row ranges walks its range table from HBM
+    instead of the LDS copy; every other of 700 tiny key clusters gives 350 ranges."""
+    H, N, d, Cq, Ck = 2, 2800, 64, 3, 700
+    Q, K, V = wl.make_small(7, N, d, 10, dtype="bf16", H=H)
+    rng = np.random.default_rng(8)
+    ql = rng.integers(0, Cq, (H, N)).astype(np.int32)
+    kl = (np.arange(N) % Ck).astype(np.int32)[None].repeat(H, 0)
+    kl = np.ascontiguousarray(rng.permuted(kl, axis=1))
+    sel = [[np.arange(i % 2, Ck, 2, dtype=np.int64) if i < 2 else np.arange(0, Ck, 7, dtype=np.int64)
+            for i in range(Cq)] for _ in range(H)]
+    got = run_sparse(Q, K, V, ql, kl, sel, B.BF16, Cq, Ck)
+    for h in range(H):
+        ref = orc.sparse_attention_gather(Q[h], K[h], V[h], ql[h], kl[h], sel[h])
+        print("many ranges", h, check(got[h], ref, B.BF16))
+
+
+@pytest.mark.parametrize("H", [8, 11])
+def test_heads_dealt_to_xcds_whole_and_leftover_heads(H):
+    """Small heads take the mapping that gives every XCD whole heads, eight at a time, and splits the
+    H mod 8 leftover heads by tile: H = 8 has no leftover, H = 11 has both kinds."""
+    N, d, Cq, Ck = 300, 64, 5, 23
+    Q, K, V, ql, kl, sel = make_case(9, N, d, B.BF16, H=H)
+    got = run_sparse(Q, K, V, ql, kl, sel, B.BF16, Cq, Ck)
+    for h in range(H):
+        ref = orc.sparse_attention_gather(Q[h], K[h], V[h], ql[h], kl[h], sel[h])
+        check(got[h], ref, B.BF16)
+    p = B.Params(H=H, N=N, d=d, dtype=B.BF16, q_clusters=1, k_m0=1, k_m_min=1, k_max_clusters=1)
+    O = to_np(B.adacluster_dense_attn(p, to_dev(Q, B.BF16), to_dev(K, B.BF16), to_dev(V, B.BF16)))
+    for h in range(H):
+        check(O[h], orc.dense_attention(Q[h], K[h], V[h]), B.BF16)
+
+
 def test_empty_selection_gives_zero_rows_and_custom_scale():
     Cq, Ck = 5, 23
     Q, K, V, ql, kl, sel = make_case(4, 600, 64, B.BF16)
