@@ -151,6 +151,7 @@ struct WS {
   void* q_cent_lp; float* q_bias; SortScratch q_sort; int32_t* q_poff; float* q_psum; float* q_pnorm;
   void* Kp; void* Vp;
   int32_t* rng_start; int32_t* rng_pre; int32_t* rng_cnt; int32_t* tiles; int32_t* ntiles;
+  int32_t* merge; int32_t* nmerge; float* part_o; float* part_ml;   // cut key lists of the attention step
   // homes for outputs of the fused call the caller did not ask for
   int32_t* q_labels; float* q_centroids; float* q_assign; int32_t* q_sizes; float* q_mean_norm;
   int32_t* k_labels; float* k_centroids; float* k_assign; float* k_bmin; float* k_bmax;
@@ -169,7 +170,7 @@ Dims dims_of(const adacluster_params* p) {
   D.nblk = (p->N + 1023) / 1024;
   D.nseg = (p->N + 511) / 512;
   D.BM = attn_block_rows(p->dtype, p->d);
-  D.maxtiles = p->N / D.BM + D.Cq + 1;
+  D.maxtiles = p->N / D.BM + D.Cq + 1 + attn_split_slots();
   D.maxr = D.cap;
   D.prow = p->N / 128 + D.capmax + 34;
   return D;
@@ -222,7 +223,11 @@ size_t layout(const adacluster_params* p, WS* w, unsigned char* base) {
   TAKE(rng_start, int32_t*, H * (size_t)D.Cq * D.maxr * 4);
   TAKE(rng_pre, int32_t*, H * (size_t)D.Cq * (D.maxr + 1) * 4);
   TAKE(rng_cnt, int32_t*, H * (size_t)D.Cq * 4);
-  TAKE(tiles, int32_t*, H * (size_t)D.maxtiles * 3 * 4);
+  TAKE(tiles, int32_t*, H * (size_t)D.maxtiles * 6 * 4);
+  TAKE(merge, int32_t*, H * (size_t)attn_split_slots() * 4 * 4);
+  TAKE(nmerge, int32_t*, H * 4);
+  TAKE(part_o, float*, H * (size_t)attn_split_slots() * D.BM * d * 4);
+  TAKE(part_ml, float*, H * (size_t)attn_split_slots() * D.BM * 2 * 4);
   TAKE(ntiles, int32_t*, H * 4);
   TAKE(q_labels, int32_t*, H * N * 4);
   TAKE(q_centroids, float*, H * (size_t)D.Cq * d * 4);
@@ -410,14 +415,15 @@ int run_plan_attention(const adacluster_params* p, const WS& w, hipStream_t st, 
                        hipEvent_t permute_done) {
   const Dims D = dims_of(p);
   const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)D.d);
-  RET_IF(launch_plan_sparse(st, D.H, D.Cq, D.cap, D.maxr, D.maxtiles, D.BM, w.offs_q, D.Cq + 1, w.offs_k, D.cap + 1,
-                            k_count, sel_idx, sel_cnt, w.rng_start, w.rng_pre, w.rng_cnt, w.tiles, w.ntiles));
+  RET_IF(launch_plan_sparse(st, p->dtype, D.H, D.Cq, D.cap, D.maxr, D.maxtiles, D.BM, w.offs_q, D.Cq + 1, w.offs_k,
+                            D.cap + 1, k_count, sel_idx, sel_cnt, w.rng_start, w.rng_pre, w.rng_cnt, w.tiles, w.ntiles,
+                            w.merge, w.nmerge));
   prof_mark(EV_PLAN, st, prof_from);
   if (permute_done && hipStreamWaitEvent(st, permute_done, 0) != hipSuccess)
     return fail(ADACLUSTER_E_INTERNAL, "stream join failed");
   if (permute_done) prof_mark(EV_JOIN2, st);
   RET_IF(launch_attention(st, p->dtype, D.d, D.H, D.N, D.Cq, D.maxtiles, D.maxr, scale, Q, w.Kp, w.Vp, O, w.perm_q,
-                          w.tiles, w.ntiles, w.rng_start, w.rng_pre, w.rng_cnt));
+                          w.tiles, w.ntiles, w.rng_start, w.rng_pre, w.rng_cnt, w.part_o, w.part_ml, w.merge, w.nmerge));
   prof_mark(EV_ATTN, st, permute_done ? EV_JOIN2 : -1);
   return 0;
 }
@@ -612,7 +618,7 @@ int adacluster_dense_attn(const adacluster_params* p, const void* Q, const void*
   RET_IF(launch_plan_dense(st, D.H, D.N, D.maxtiles, D.BM, w.rng_start, w.rng_pre, w.rng_cnt, w.tiles, w.ntiles));
   prof_mark(EV_PLAN, st);
   RET_IF(launch_attention(st, p->dtype, D.d, D.H, D.N, 1, D.maxtiles, 1, scale, Q, K, V, O, nullptr, w.tiles,
-                          w.ntiles, w.rng_start, w.rng_pre, w.rng_cnt));
+                          w.ntiles, w.rng_start, w.rng_pre, w.rng_cnt, nullptr, nullptr, nullptr, nullptr));
   prof_mark(EV_ATTN, st);
   return 0;
 }

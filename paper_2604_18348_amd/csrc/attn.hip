@@ -15,6 +15,9 @@
 
 namespace adac {
 
+static constexpr int TILE_REC = 6;       // ints per query-tile record
+static constexpr int SPLIT_SLOTS = 64;   // partial slots per head for the chunks of cut key lists
+
 // ------------------------------------------------------------------------------------------
 // permutation of K and V rows
 // ------------------------------------------------------------------------------------------
@@ -53,50 +56,109 @@ int launch_permute_kv(hipStream_t s, int H, int N, int row_bytes, const void* K,
 // rng_start [H][Cq][maxr]   first permuted key row of range r
 // rng_pre   [H][Cq][maxr+1] keys before range r in the concatenation (last = total)
 // rng_cnt   [H][Cq]
-// tiles     [H][maxtiles] x {cluster, first sorted query position, rows}; ntiles [H]
-__global__ void plan_sparse(int Cq, int cap, int maxr, int maxtiles, int BM,
-                            const int32_t* __restrict__ q_offs, int q_offs_stride,
+// tiles     [H][maxtiles] x {cluster, first sorted query position, rows, first key tile, end key
+//           tile, partial slot or -1}; ntiles [H]
+__global__ void plan_sparse(int Cq, int cap, int maxr,
                             const int32_t* __restrict__ k_offs, int k_offs_stride,
                             const int32_t* __restrict__ k_count,
                             const int32_t* __restrict__ sel_idx, const int32_t* __restrict__ sel_cnt,
                             int32_t* __restrict__ rng_start, int32_t* __restrict__ rng_pre,
-                            int32_t* __restrict__ rng_cnt, int32_t* __restrict__ tiles,
-                            int32_t* __restrict__ ntiles) {
+                            int32_t* __restrict__ rng_cnt) {
   const int h = blockIdx.y, i = blockIdx.x;
   if (threadIdx.x != 0) return;
-  if (i < Cq) {
-    const int32_t* sel = sel_idx + ((size_t)h * Cq + i) * cap;
-    const int cnt = sel_cnt[(size_t)h * Cq + i];
-    const int32_t* ko = k_offs + (size_t)h * k_offs_stride;
-    const int kc = k_count[h];
-    int32_t* rs = rng_start + ((size_t)h * Cq + i) * maxr;
-    int32_t* rp = rng_pre + ((size_t)h * Cq + i) * (maxr + 1);
-    int nr = 0, total = 0, cur_s = 0, cur_e = -1;
-    for (int t = 0; t < cnt; ++t) {
-      const int j = sel[t];
-      if (j < 0 || j >= kc) continue;
-      const int s = ko[j], e = ko[j + 1];
-      if (e <= s) continue;
-      if (s == cur_e) { cur_e = e; continue; }
-      if (cur_e > cur_s) { rs[nr] = cur_s; rp[nr] = total; total += cur_e - cur_s; ++nr; }
-      cur_s = s; cur_e = e;
-    }
+  const int32_t* sel = sel_idx + ((size_t)h * Cq + i) * cap;
+  const int cnt = sel_cnt[(size_t)h * Cq + i];
+  const int32_t* ko = k_offs + (size_t)h * k_offs_stride;
+  const int kc = k_count[h];
+  int32_t* rs = rng_start + ((size_t)h * Cq + i) * maxr;
+  int32_t* rp = rng_pre + ((size_t)h * Cq + i) * (maxr + 1);
+  int nr = 0, total = 0, cur_s = 0, cur_e = -1;
+  for (int t = 0; t < cnt; ++t) {
+    const int j = sel[t];
+    if (j < 0 || j >= kc) continue;
+    const int s = ko[j], e = ko[j + 1];
+    if (e <= s) continue;
+    if (s == cur_e) { cur_e = e; continue; }
     if (cur_e > cur_s) { rs[nr] = cur_s; rp[nr] = total; total += cur_e - cur_s; ++nr; }
-    rp[nr] = total;
-    rng_cnt[(size_t)h * Cq + i] = nr;
-  } else {
-    // query tiles of this head, cluster by cluster
-    const int32_t* qo = q_offs + (size_t)h * q_offs_stride;
-    int32_t* tl = tiles + (size_t)h * maxtiles * 3;
-    int nt = 0;
-    for (int c = 0; c < Cq; ++c) {
-      const int s = qo[c], e = qo[c + 1];
-      for (int r0 = s; r0 < e; r0 += BM) {
-        tl[nt * 3 + 0] = c; tl[nt * 3 + 1] = r0; tl[nt * 3 + 2] = min(BM, e - r0);
-        ++nt;
+    cur_s = s; cur_e = e;
+  }
+  if (cur_e > cur_s) { rs[nr] = cur_s; rp[nr] = total; total += cur_e - cur_s; ++nr; }
+  rp[nr] = total;
+  rng_cnt[(size_t)h * Cq + i] = nr;
+}
+
+// Query tiles of a head, cluster by cluster.  A query cluster whose key list is much longer than
+// the head's average (top-p selections can be that skewed) would make its few workgroups the whole
+// critical path of the launch, so such a list is cut into chunks of key tiles: each chunk is a
+// workgroup of its own that leaves unnormalised (O, m, l) in a partial slot, and attn_merge
+// combines the slots of a query tile.  merge [H][slots] x {first query position, rows, first slot,
+// chunks}; a head has `slots` partial slots, and lists stay whole once they are used up.
+__global__ __launch_bounds__(256) void plan_tiles(int Cq, int maxr, int maxtiles, int BM, int slots, int allow_split,
+                                                  const int32_t* __restrict__ q_offs, int q_offs_stride,
+                                                  const int32_t* __restrict__ rng_pre,
+                                                  const int32_t* __restrict__ rng_cnt,
+                                                  int32_t* __restrict__ tiles, int32_t* __restrict__ ntiles,
+                                                  int32_t* __restrict__ merge, int32_t* __restrict__ nmerge) {
+  constexpr int MAXC = 4096;                       // the largest q_clusters the library accepts
+  const int h = blockIdx.x, tid = threadIdx.x;
+  const int32_t* qo = q_offs + (size_t)h * q_offs_stride;
+  int32_t* tl = tiles + (size_t)h * maxtiles * TILE_REC;
+  int32_t* ml = merge + (size_t)h * slots * 4;
+  __shared__ int32_t s_T[MAXC], s_nq[MAXC], s_pieces[MAXC], s_tile0[MAXC], s_slot0[MAXC], s_merge0[MAXC];
+  __shared__ int32_t s_chunk;
+  const int C = min(Cq, MAXC);
+  for (int c = tid; c < C; c += 256) {
+    s_nq[c] = (qo[c + 1] - qo[c] + BM - 1) / BM;
+    const int tot = rng_pre[((size_t)h * Cq + c) * (maxr + 1) + rng_cnt[(size_t)h * Cq + c]];
+    s_T[c] = (tot + 63) / 64;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    // key tiles per chunk of a list that is cut: twice the average list of the head, at least 16
+    long long work = 0; int qtiles = 0;
+    for (int c = 0; c < C; ++c) { work += (long long)s_nq[c] * s_T[c]; qtiles += s_nq[c]; }
+    const int mean_t = qtiles > 0 ? (int)((work + qtiles - 1) / qtiles) : 0;
+    const int chunk = max(16, 2 * mean_t);
+    s_chunk = chunk;
+    // which lists are cut (in cluster order, while slots last), and where every cluster's records start
+    int nt = 0, used = 0, nm = 0;
+    for (int c = 0; c < C; ++c) {
+      const int T = s_T[c];
+      int pieces = 1;
+      if (allow_split && T > 2 * chunk) {
+        pieces = min(16, (T + chunk - 1) / chunk);
+        const int per = (T + pieces - 1) / pieces;
+        pieces = max(1, (T + per - 1) / max(per, 1));          // no empty chunk
+        if (used + pieces * s_nq[c] > slots) pieces = 1;
       }
+      s_pieces[c] = pieces; s_tile0[c] = nt; s_slot0[c] = used; s_merge0[c] = nm;
+      nt += s_nq[c] * pieces;
+      if (pieces > 1) { used += s_nq[c] * pieces; nm += s_nq[c]; }
     }
     ntiles[h] = nt;
+    nmerge[h] = nm;
+  }
+  __syncthreads();
+  // records of every cluster, one thread per cluster
+  for (int c = tid; c < C; c += 256) {
+    const int s0 = qo[c], e0 = qo[c + 1], T = s_T[c], pieces = s_pieces[c];
+    const int per = (T + pieces - 1) / pieces;
+    int nt = s_tile0[c], slot = s_slot0[c], nm = s_merge0[c];
+    for (int r0 = s0; r0 < e0; r0 += BM) {
+      const int rows = min(BM, e0 - r0);
+      if (pieces > 1) {
+        ml[nm * 4 + 0] = r0; ml[nm * 4 + 1] = rows; ml[nm * 4 + 2] = slot; ml[nm * 4 + 3] = pieces;
+        ++nm;
+      }
+      for (int k = 0; k < pieces; ++k) {
+        int32_t* t6 = tl + (size_t)nt * TILE_REC;
+        t6[0] = c; t6[1] = r0; t6[2] = rows;
+        t6[3] = pieces > 1 ? k * per : 0; t6[4] = pieces > 1 ? min(T, (k + 1) * per) : T;
+        t6[5] = pieces > 1 ? slot + k : -1;
+        ++nt;
+      }
+      if (pieces > 1) slot += pieces;
+    }
   }
 }
 
@@ -109,9 +171,10 @@ __global__ void plan_dense(int N, int maxtiles, int BM, int32_t* __restrict__ rn
     rng_start[h] = 0; rng_pre[(size_t)h * 2] = 0; rng_pre[(size_t)h * 2 + 1] = N; rng_cnt[h] = 1;
     ntiles[h] = (N + BM - 1) / BM;
   }
-  int32_t* tl = tiles + (size_t)h * maxtiles * 3;
+  int32_t* tl = tiles + (size_t)h * maxtiles * TILE_REC;
   for (int t = threadIdx.x; t * BM < N; t += blockDim.x) {
-    tl[t * 3 + 0] = 0; tl[t * 3 + 1] = t * BM; tl[t * 3 + 2] = min(BM, N - t * BM);
+    int32_t* t6 = tl + (size_t)t * TILE_REC;
+    t6[0] = 0; t6[1] = t * BM; t6[2] = min(BM, N - t * BM); t6[3] = 0; t6[4] = (N + 63) / 64; t6[5] = -1;
   }
 }
 
@@ -123,6 +186,8 @@ struct AttnArgs {
   int N, Cq, maxtiles, maxr;
   float scale_log2e;            // softmax scale x log2(e)
   int head_major;               // workgroup -> (head, tile) mapping, see attn_mfma
+  float* part_o; float* part_ml;   // partial slots of cut key lists: [H][slots][BM][d], [H][slots][BM][2]
+  int slots, BM;
 };
 
 // position in the concatenation of ranges -> permuted key row; a cursor that only moves forward
@@ -178,24 +243,37 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
     const int gx = gridDim.x, gx8 = gx >> 3;
     const int xcd = blockIdx.x & 7, slot = (blockIdx.y * gx + blockIdx.x) >> 3;
     const int Hfull = (gridDim.y >> 3) << 3, full_slots = (Hfull >> 3) * gx;
-    if (slot < full_slots) { h = (slot / gx) * 8 + xcd; tile = slot % gx; }
-    else { const int r = slot - full_slots; h = Hfull + r / gx8; tile = xcd * gx8 + r % gx8; }
+    if (slot < full_slots) {
+      h = (slot / gx) * 8 + xcd; tile = slot % gx;
+      if (tile >= a.ntiles[h]) return;
+    } else {
+      const int r = slot - full_slots, j = r % gx8;
+      h = Hfull + r / gx8;
+      const int nt = a.ntiles[h], per = (nt + 7) >> 3;    // eighths of the tiles the head has, not of the grid
+      tile = xcd * per + j;
+      if (j >= per || tile >= nt) return;
+    }
   } else {
     // Every head is split eight ways: an XCD takes a contiguous run of its query tiles (the tiles
-    // of one query cluster stream the same K/V rows, and so do it behind the same L2).
+    // of one query cluster stream the same K/V rows, and so do it behind the same L2).  The runs
+    // are eighths of the tiles the head has; the grid is sized for the most it could have.
     h = blockIdx.y;
-    tile = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const int nt = a.ntiles[h], per = (nt + 7) >> 3, j = blockIdx.x >> 3;
+    tile = (blockIdx.x & 7) * per + j;
+    if (j >= per || tile >= nt) return;
   }
-  if (tile >= a.ntiles[h]) return;
-  const int32_t* tl = a.tiles + ((size_t)h * a.maxtiles + tile) * 3;
+  const int32_t* tl = a.tiles + ((size_t)h * a.maxtiles + tile) * TILE_REC;
   const int qc = tl[0], row0 = tl[1], nrows = tl[2];
+  const int kt0 = tl[3], kt1 = tl[4], pslot = tl[5];    // this workgroup's share of the key list
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c = lane & 31, hb = lane >> 5;
 
   const int nr = a.rng_cnt[(size_t)h * a.Cq + qc];
   const int32_t* rs = a.rng_start + ((size_t)h * a.Cq + qc) * a.maxr;
   const int32_t* rp = a.rng_pre + ((size_t)h * a.Cq + qc) * (a.maxr + 1);
-  const int total = rp[nr];
+  // positions below are relative to the first key of the share
+  const int pbase = kt0 * BN;
+  const int total = max(0, min(rp[nr], kt1 * BN) - pbase);
   const int T = (total + BN - 1) / BN;
 
   const bf16raw* Qh = (const bf16raw*)a.Q + (size_t)h * a.N * D;
@@ -386,7 +464,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
   RangeCursorT<lds_ci32_t*> cur_l;
   const int first_off = nr > 0 ? rs[0] * ROWB : 0;
   auto row_off = [&](int p) {
-    const int r = rng_in_lds ? cur_l.row(p) : cur.row(p);
+    const int r = rng_in_lds ? cur_l.row(p + pbase) : cur.row(p + pbase);
     return r < 0 ? first_off : r * ROWB;
   };
   if (tid < BN) {
@@ -426,6 +504,22 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     const float l = lrun[qb] + __shfl_xor(lrun[qb], 32);
+    if (pslot >= 0) {
+      // a chunk of a cut key list: leave the unnormalised accumulator, the running maximum and the
+      // row sum in this chunk's slot; attn_merge combines the chunks of the query tile
+      const int rr = wave * (32 * QB) + qb * 32 + c;
+      const size_t so = ((size_t)h * a.slots + pslot) * a.BM + rr;
+      float* po = a.part_o + so * D;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float4 o = {oacc[db][qb][4 * i], oacc[db][qb][4 * i + 1], oacc[db][qb][4 * i + 2], oacc[db][qb][4 * i + 3]};
+          *reinterpret_cast<float4*>(po + db * 32 + 8 * i + 4 * hb) = o;
+        }
+      if (hb == 0) { a.part_ml[so * 2] = mrun[qb]; a.part_ml[so * 2 + 1] = l; }
+      continue;
+    }
     const float inv = l > 0.f ? 1.0f / l : 0.f;
     if (qtok[qb] < 0) continue;
     bf16raw* orow = Oh + (size_t)qtok[qb] * D;
@@ -449,7 +543,7 @@ __global__ __launch_bounds__(64) void attn_f32(AttnArgs a) {
   constexpr int BN = 32;
   const int h = blockIdx.y, tile = blockIdx.x;
   if (tile >= a.ntiles[h]) return;
-  const int32_t* tl = a.tiles + ((size_t)h * a.maxtiles + tile) * 3;
+  const int32_t* tl = a.tiles + ((size_t)h * a.maxtiles + tile) * TILE_REC;   // (key lists are never cut for fp32)
   const int qc = tl[0], row0 = tl[1], nrows = tl[2];
   const int tid = threadIdx.x;
   const int nr = a.rng_cnt[(size_t)h * a.Cq + qc];
@@ -518,6 +612,44 @@ __global__ __launch_bounds__(64) void attn_f32(AttnArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
+// merge of the chunks of cut key lists
+// ------------------------------------------------------------------------------------------
+// One workgroup per cut query tile: O = sum_s 2^((m_s - m) scale) O_s / sum_s 2^((m_s - m) scale) l_s
+// with m = max_s m_s; a chunk always holds at least one key, so every m_s is finite and l_s > 0.
+template <int D>
+__global__ __launch_bounds__(256) void attn_merge(AttnArgs a, const int32_t* __restrict__ merge,
+                                                  const int32_t* __restrict__ nmerge) {
+  const int h = blockIdx.y, e = blockIdx.x;
+  if (e >= nmerge[h]) return;
+  const int32_t* ml = merge + ((size_t)h * a.slots + e) * 4;
+  const int row0 = ml[0], nrows = ml[1], slot0 = ml[2], pieces = ml[3];
+  const int32_t* pq = a.perm_q ? a.perm_q + (size_t)h * a.N : nullptr;
+  bf16raw* Oh = (bf16raw*)a.O + (size_t)h * a.N * D;
+  constexpr int LPR = D / 4;                     // lanes per row, four columns each
+  for (int r = threadIdx.x / LPR; r < nrows; r += 256 / LPR) {
+    const int col = (threadIdx.x % LPR) * 4;
+    float m = -INFINITY;
+    for (int s = 0; s < pieces; ++s)
+      m = fmaxf(m, a.part_ml[(((size_t)h * a.slots + slot0 + s) * a.BM + r) * 2]);
+    float l = 0.f;
+    float4 o = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < pieces; ++s) {
+      const size_t so = ((size_t)h * a.slots + slot0 + s) * a.BM + r;
+      const float w = __builtin_amdgcn_exp2f((a.part_ml[so * 2] - m) * a.scale_log2e);
+      l = fmaf(w, a.part_ml[so * 2 + 1], l);
+      const float4 v = *reinterpret_cast<const float4*>(a.part_o + so * D + col);
+      o.x = fmaf(w, v.x, o.x); o.y = fmaf(w, v.y, o.y); o.z = fmaf(w, v.z, o.z); o.w = fmaf(w, v.w, o.w);
+    }
+    const float inv = l > 0.f ? 1.0f / l : 0.f;
+    const int tok = pq ? pq[row0 + r] : row0 + r;
+    uint2 out;
+    out.x = pack_bf16x2(o.x * inv, o.y * inv);
+    out.y = pack_bf16x2(o.z * inv, o.w * inv);
+    *reinterpret_cast<uint2*>(Oh + (size_t)tok * D + col) = out;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
 // tile shapes of the bf16 kernel: queries per wave = 32*QB, waves per block NW, blocks per CU MINB
 #ifndef A64_QB
 #define A64_QB 1
@@ -543,13 +675,17 @@ int attn_block_rows(int dtype, int d) {
   return d == 64 ? A64_NW * 32 * A64_QB : A128_NW * 32 * A128_QB;
 }
 
-int launch_plan_sparse(hipStream_t s, int H, int Cq, int cap, int maxr, int maxtiles, int BM,
+int attn_split_slots() { return SPLIT_SLOTS; }
+
+int launch_plan_sparse(hipStream_t s, int dtype, int H, int Cq, int cap, int maxr, int maxtiles, int BM,
                        const int32_t* q_offs, int q_offs_stride, const int32_t* k_offs, int k_offs_stride,
                        const int32_t* k_count, const int32_t* sel_idx, const int32_t* sel_cnt,
-                       int32_t* rng_start, int32_t* rng_pre, int32_t* rng_cnt, int32_t* tiles, int32_t* ntiles) {
-  plan_sparse<<<dim3(Cq + 1, H), 64, 0, s>>>(Cq, cap, maxr, maxtiles, BM, q_offs, q_offs_stride, k_offs,
-                                            k_offs_stride, k_count, sel_idx, sel_cnt, rng_start, rng_pre,
-                                            rng_cnt, tiles, ntiles);
+                       int32_t* rng_start, int32_t* rng_pre, int32_t* rng_cnt, int32_t* tiles, int32_t* ntiles,
+                       int32_t* merge, int32_t* nmerge) {
+  plan_sparse<<<dim3(Cq, H), 64, 0, s>>>(Cq, cap, maxr, k_offs, k_offs_stride, k_count, sel_idx, sel_cnt, rng_start,
+                                        rng_pre, rng_cnt);
+  plan_tiles<<<H, 256, 0, s>>>(Cq, maxr, maxtiles, BM, SPLIT_SLOTS, dtype == ADACLUSTER_BF16 ? 1 : 0, q_offs,
+                              q_offs_stride, rng_pre, rng_cnt, tiles, ntiles, merge, nmerge);
   return hipGetLastError() == hipSuccess ? 0 : ADACLUSTER_E_INTERNAL;
 }
 
@@ -562,14 +698,20 @@ int launch_plan_dense(hipStream_t s, int H, int N, int maxtiles, int BM, int32_t
 int launch_attention(hipStream_t s, int dtype, int d, int H, int N, int Cq, int maxtiles, int maxr, float scale,
                      const void* Q, const void* Kp, const void* Vp, void* O, const int32_t* perm_q,
                      const int32_t* tiles, const int32_t* ntiles, const int32_t* rng_start,
-                     const int32_t* rng_pre, const int32_t* rng_cnt) {
+                     const int32_t* rng_pre, const int32_t* rng_cnt, float* part_o, float* part_ml,
+                     const int32_t* merge, const int32_t* nmerge) {
   AttnArgs a{Q, Kp, Vp, O, perm_q, tiles, ntiles, rng_start, rng_pre, rng_cnt, N, Cq, maxtiles, maxr,
              scale * 1.4426950408889634f,
-             (Cq == 1 || (size_t)4 * N * d <= ((size_t)8 << 20)) ? 1 : 0};
+             (Cq == 1 || (size_t)4 * N * d <= ((size_t)8 << 20)) ? 1 : 0,
+             part_o, part_ml, SPLIT_SLOTS, attn_block_rows(dtype, d)};
   dim3 g((maxtiles + 7) / 8 * 8, H);
   if (dtype == ADACLUSTER_BF16) {
     if (d == 64) attn_mfma<64, A64_QB, A64_NW, A64_MINB><<<g, A64_NW * 64, 0, s>>>(a);
     else attn_mfma<128, A128_QB, A128_NW, A128_MINB><<<g, A128_NW * 64, 0, s>>>(a);
+    if (merge) {      // the chunks of cut key lists (none for the dense branch)
+      if (d == 64) attn_merge<64><<<dim3(SPLIT_SLOTS, H), 256, 0, s>>>(a, merge, nmerge);
+      else attn_merge<128><<<dim3(SPLIT_SLOTS, H), 256, 0, s>>>(a, merge, nmerge);
+    }
   } else {
     if (d == 64) attn_f32<64><<<g, 64, 0, s>>>(a);
     else attn_f32<128><<<g, 64, 0, s>>>(a);

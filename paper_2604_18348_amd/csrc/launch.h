@@ -64,15 +64,18 @@ int launch_select(hipStream_t s, int H, int Cq, int cap, int d, int score_mode, 
 int attn_block_rows(int dtype, int d);
 int launch_permute_kv(hipStream_t s, int H, int N, int row_bytes, const void* K, const void* V,
                       const int32_t* perm, void* Kp, void* Vp);
-int launch_plan_sparse(hipStream_t s, int H, int Cq, int cap, int maxr, int maxtiles, int BM,
+int attn_split_slots();      // partial slots per head for the chunks of cut key lists (also extra tile records)
+int launch_plan_sparse(hipStream_t s, int dtype, int H, int Cq, int cap, int maxr, int maxtiles, int BM,
                        const int32_t* q_offs, int q_offs_stride, const int32_t* k_offs, int k_offs_stride,
                        const int32_t* k_count, const int32_t* sel_idx, const int32_t* sel_cnt,
-                       int32_t* rng_start, int32_t* rng_pre, int32_t* rng_cnt, int32_t* tiles, int32_t* ntiles);
+                       int32_t* rng_start, int32_t* rng_pre, int32_t* rng_cnt, int32_t* tiles, int32_t* ntiles,
+                       int32_t* merge, int32_t* nmerge);
 int launch_plan_dense(hipStream_t s, int H, int N, int maxtiles, int BM, int32_t* rng_start, int32_t* rng_pre,
                       int32_t* rng_cnt, int32_t* tiles, int32_t* ntiles);
 int launch_attention(hipStream_t s, int dtype, int d, int H, int N, int Cq, int maxtiles, int maxr, float scale,
                      const void* Q, const void* Kp, const void* Vp, void* O, const int32_t* perm_q,
                      const int32_t* tiles, const int32_t* ntiles, const int32_t* rng_start,
-                     const int32_t* rng_pre, const int32_t* rng_cnt);
+                     const int32_t* rng_pre, const int32_t* rng_cnt, float* part_o, float* part_ml,
+                     const int32_t* merge /* NULL: no cut lists */, const int32_t* nmerge);
 
 }  // namespace adac

@@ -118,6 +118,23 @@ def test_heads_dealt_to_xcds_whole_and_leftover_heads(H):
         check(O[h], orc.dense_attention(Q[h], K[h], V[h]), B.BF16)
 
 
+@pytest.mark.parametrize("d", [64, 128])
+def test_skewed_selection_cuts_the_long_key_list(d):
+    """One query cluster selects every key cluster (a list of 94 key tiles) while the others select one
+    small cluster each: the long list is cut into chunks handled by separate workgroups and merged."""
+    H, N, Cq, Ck = 2, 6000, 6, 40
+    Q, K, V = wl.make_small(12, N, d, 10, dtype="bf16", H=H)
+    rng = np.random.default_rng(13)
+    ql = rng.integers(0, Cq, (H, N)).astype(np.int32)
+    kl = rng.integers(0, Ck, (H, N)).astype(np.int32)
+    sel = [[np.arange(Ck, dtype=np.int64) if i == 2 else np.array([i], dtype=np.int64) for i in range(Cq)]
+           for _ in range(H)]
+    got = run_sparse(Q, K, V, ql, kl, sel, B.BF16, Cq, Ck)
+    for h in range(H):
+        ref = orc.sparse_attention_gather(Q[h], K[h], V[h], ql[h], kl[h], sel[h])
+        print("skewed", d, h, check(got[h], ref, B.BF16))
+
+
 def test_empty_selection_gives_zero_rows_and_custom_scale():
     Cq, Ck = 5, 23
     Q, K, V, ql, kl, sel = make_case(4, 600, 64, B.BF16)
