@@ -34,13 +34,15 @@ __device__ __forceinline__ bool assign_setup(const AssignCfg& c, int h, int& n, 
 // MFMA formulation: D[32 centres x 32 points] += A[32 x 16] B[16 x 32] with A = centre rows from
 // LDS and B = point rows held in registers for the whole kernel.  In the 32x32 accumulator a lane
 // owns ONE point (column lane%32) and 16 centres, so the arg-max over centres runs in-lane; the
-// two half-waves are merged once at the end.
+// two half-waves are merged once at the end.  Two workgroups per CU in the launch bounds keep the
+// register budget at 256, so the accumulators are ordinary VGPRs that the arg-max reads directly (with
+// 512 the compiler parks them in AGPRs and copies every value out first).
 template <int D>
-__global__ __launch_bounds__(256) void assign_mfma(const bf16raw* __restrict__ X, AssignCfg cfg,
+__global__ __launch_bounds__(256, 2) void assign_mfma(const bf16raw* __restrict__ X, AssignCfg cfg,
                                                    const bf16raw* __restrict__ cent,
                                                    const float* __restrict__ bias,
                                                    int32_t* __restrict__ labels, float* __restrict__ dist2) {
-  constexpr int CB = 128;               // centres per LDS chunk
+  constexpr int CB = D == 128 ? 64 : 128;   // centres per LDS chunk (about 17 KB either way; larger chunks measured slower)
   constexpr int LDW = D + 8;            // padded row (bf16 elements): conflict-free 16-byte reads
   constexpr int KS = D / 16;
   constexpr int PB = 2;                 // 32-point blocks per wave
