@@ -18,7 +18,7 @@ thread_local char g_err[256] = "";
 // from the event in from[] (default: the previous recorded stage boundary); the fused call runs
 // the two clusterings side by side, so both of those are timed from the start of the call.
 enum { EV_START = 0, EV_QCLUSTER, EV_KCLUSTER, EV_SELECT, EV_PERMUTE, EV_PLAN, EV_ATTN, EV_STAGES,
-       EV_JOIN = EV_STAGES, EV_JOIN2, EV_COUNT };
+       EV_JOIN = EV_STAGES, EV_JOIN2, EV_KSORT, EV_COUNT };
 struct Profiler {
   bool enabled = false;
   bool recorded[EV_COUNT] = {};
@@ -294,7 +294,7 @@ int run_qcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
 int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const void* K, int32_t* k_labels,
                  float* k_centroids, float* k_assign, float* k_bmin, float* k_bmax, int32_t* k_sizes,
                  int32_t* k_count, int32_t* full_flag, int32_t* k_stage_offs, int32_t* k_stage_of,
-                 float* tau_used, int* kc_bound_out) {
+                 float* tau_used, int* kc_bound_out, hipEvent_t sorted_ev = nullptr) {
   const Dims D = dims_of(p);
   int kc_bound = 0;   // sum over stages of the largest stage centre count: an upper bound of every |C|
   hipEvent_t pending_ev = nullptr;   // the last report may still be in flight when the stage loop ends
@@ -386,6 +386,11 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
   }
   RET_IF(launch_sort(st, D.H, D.N, D.N, D.cap, k_labels, nullptr, nullptr, 0, &w.kstate->ccount, sizeof(KState) / 4,
                      nullptr, 0, w.perm_k, w.offs_k, D.cap + 1, w.sort, w.poff, reduce_part_rows(), &poff_done));
+  // the key permutation is final here: work that needs nothing else of the clustering may start
+  if (sorted_ev) {
+    if (hipEventRecord(sorted_ev, st) != hipSuccess) return fail(ADACLUSTER_E_INTERNAL, "stream fork failed");
+    prof_mark(EV_KSORT, st);
+  }
   const int want_box = (k_bmin && k_bmax) ? 1 : 0;
   const int P = parts_for(D.N, D.cap);
   RET_IF(launch_seg_reduce(st, p->dtype, D.d, D.H, D.N, 2, 0, D.cap, P, w.kstate, 0, want_box, K, w.perm_k, w.offs_k,
@@ -576,16 +581,17 @@ int adacluster_attn(const adacluster_params* p, const void* Q, const void* K, co
   if (hipEventRecord(aux->join, aux->s) != hipSuccess) return fail(ADACLUSTER_E_INTERNAL, "stream join failed");
   int kc_bound = capacity(p);
   int rck = rc ? 0 : run_kcluster(p, w, st, K, k_labels, k_centroids, k_assign_centroids, k_bmin, k_bmax, k_sizes,
-                                   k_count, full_flag, o.k_stage_offs, o.k_stage_of, tau_used, &kc_bound);
+                                   k_count, full_flag, o.k_stage_offs, o.k_stage_of, tau_used, &kc_bound, aux->fork);
   prof_mark(EV_KCLUSTER, st, EV_START);
-  // The K/V permutation needs only the key label sort: it goes to the second stream too (behind
-  // the query clustering there) and runs beside the selection and the planning.
+  // The K/V permutation needs only the key label sort, which is final before the last centroid
+  // update of the key clustering: it goes to the second stream too (behind the query clustering
+  // there) and runs beside that update, the selection and the planning.
   const bool fork2 = !rc && !rck;
   int rcp = 0;
   if (fork2) {
-    if (hipEventRecord(aux->fork, st) != hipSuccess || hipStreamWaitEvent(aux->s, aux->fork, 0) != hipSuccess)
+    if (hipStreamWaitEvent(aux->s, aux->fork, 0) != hipSuccess)
       return fail(ADACLUSTER_E_INTERNAL, "stream fork failed: %s", hipGetErrorString(hipGetLastError()));
-    rcp = run_permute(p, w, aux->s, K, V, EV_KCLUSTER);
+    rcp = run_permute(p, w, aux->s, K, V, EV_KSORT);
     if (hipEventRecord(aux->join2, aux->s) != hipSuccess) return fail(ADACLUSTER_E_INTERNAL, "stream join failed");
   }
   if (hipStreamWaitEvent(st, aux->join, 0) != hipSuccess) return fail(ADACLUSTER_E_INTERNAL, "stream join failed");

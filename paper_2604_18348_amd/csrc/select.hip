@@ -55,19 +55,27 @@ __global__ __launch_bounds__(256) void select_kernel(SelectCfg cfg, const float*
   double* sval = reinterpret_cast<double*>(smem);                        // [cap] score, then weight
   uint64_t* skey = reinterpret_cast<uint64_t*>(smem + (size_t)cfg.lds_cap * 8);   // [lds_cap]
   int32_t* sflag = reinterpret_cast<int32_t*>(smem + (size_t)cfg.lds_cap * 16);   // [lds_cap]
-  __shared__ double qrow[128];
-  __shared__ int32_t wsum[4];
-  __shared__ int32_t s_take;
+  __shared__ double qrow[128], qpos[128], qneg[128];
+  __shared__ int32_t wsum[4], wsum2[4];
+  __shared__ int32_t s_take, s_digit, s_krem;
+  __shared__ int32_t hist[256];
   __shared__ double s_max;
 
   const int h = blockIdx.y, i = blockIdx.x, tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
   const int d = cfg.d;
+  bool use_thr = false;          // top-k by threshold key: selected = key > thr_key, or == thr_key among the first thr_rem
+  uint64_t thr_key = 0;
+  int thr_rem = 0;
   const int kc = min(k_count[h], cfg.lds_cap);
   const bool all = full_flag[h] != 0;
-  if (tid < d) qrow[tid] = (double)q_cent[((size_t)h * cfg.Cq + i) * d + tid];
+  if (tid < d) {
+    const double q = (double)q_cent[((size_t)h * cfg.Cq + i) * d + tid];
+    qrow[tid] = q; qpos[tid] = fmax(q, 0.0); qneg[tid] = fmin(q, 0.0);
+  }
   __syncthreads();
 
-  // ---- scores
+  // ---- scores (a thread owns a key cluster; its row is read 16 bytes at a time)
   for (int j = tid; j < kc; j += 256) {
     const int nj = k_sizes[(size_t)h * cfg.cap + j];
     double s;
@@ -76,20 +84,31 @@ __global__ __launch_bounds__(256) void select_kernel(SelectCfg cfg, const float*
     } else if (all) {
       s = 0.0;
     } else if (cfg.score_mode == ADACLUSTER_SCORE_DOT) {
-      const float* cr = k_cent + ((size_t)h * cfg.cap + j) * d;
+      const float4* cr = reinterpret_cast<const float4*>(k_cent + ((size_t)h * cfg.cap + j) * d);
       s = 0.0;
-      for (int t = 0; t < d; ++t) s = s + qrow[t] * (double)cr[t];
+      for (int t4 = 0; t4 < d / 4; ++t4) {
+        const float4 c4 = cr[t4];
+        s = s + qrow[4 * t4 + 0] * (double)c4.x;
+        s = s + qrow[4 * t4 + 1] * (double)c4.y;
+        s = s + qrow[4 * t4 + 2] * (double)c4.z;
+        s = s + qrow[4 * t4 + 3] * (double)c4.w;
+      }
     } else {
-      const float* rpos = (cfg.score_mode == ADACLUSTER_SCORE_BOX ? k_bmax : k_cent) + ((size_t)h * cfg.cap + j) * d;
-      const float* rneg = (cfg.score_mode == ADACLUSTER_SCORE_BOX ? k_bmin : k_cent) + ((size_t)h * cfg.cap + j) * d;
-      const bool clampk = cfg.score_mode == ADACLUSTER_SCORE_TQ;
+      const bool box = cfg.score_mode == ADACLUSTER_SCORE_BOX;
+      const float4* rpos = reinterpret_cast<const float4*>((box ? k_bmax : k_cent) + ((size_t)h * cfg.cap + j) * d);
+      const float4* rneg = reinterpret_cast<const float4*>((box ? k_bmin : k_cent) + ((size_t)h * cfg.cap + j) * d);
       double sp = 0.0, sn = 0.0;
-      for (int t = 0; t < d; ++t) {
-        const double q = qrow[t];
-        double kp = (double)rpos[t], kn = (double)rneg[t];
-        if (clampk) { kp = fmax(kp, 0.0); kn = fmin(kn, 0.0); }
-        sp = sp + fmax(q, 0.0) * kp;
-        sn = sn + fmin(q, 0.0) * kn;
+      for (int t4 = 0; t4 < d / 4; ++t4) {
+        const float4 p4 = rpos[t4];
+        const float4 n4 = box ? rneg[t4] : p4;
+        const float pv[4] = {p4.x, p4.y, p4.z, p4.w}, nv[4] = {n4.x, n4.y, n4.z, n4.w};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          double kp = (double)pv[u], kn = (double)nv[u];
+          if (!box) { kp = fmax(kp, 0.0); kn = fmin(kn, 0.0); }
+          sp = sp + qpos[4 * t4 + u] * kp;
+          sn = sn + qneg[4 * t4 + u] * kn;
+        }
       }
       s = sp + sn;
     }
@@ -101,17 +120,53 @@ __global__ __launch_bounds__(256) void select_kernel(SelectCfg cfg, const float*
   if (all || (topp && cfg.top_p >= 1.0)) {
     for (int j = tid; j < kc; j += 256) sflag[j] = sval[j] > -INFINITY;
   } else if (!topp) {
-    // rank by (score desc, index asc); keep rank < topk
-    for (int j = tid; j < kc; j += 256) skey[j] = order_key(sval[j]);
-    __syncthreads();
+    // The topk largest by (score desc, index asc).  No ranks are needed, only the key of the
+    // topk-th largest: an MSB-first radix select over the 64-bit order keys (eight 8-bit digits, a
+    // 256-bin histogram per digit).  Equal keys at the threshold are resolved by index in the
+    // compaction below, which walks the clusters in ascending order anyway.
+    int nv = 0;
     for (int j = tid; j < kc; j += 256) {
-      const uint64_t kj = skey[j];
-      int rank = 0;
-      for (int t = 0; t < kc; ++t) {
-        const uint64_t kt = skey[t];
-        rank += (kt > kj) || (kt == kj && t < j);
+      const double v = sval[j];
+      skey[j] = order_key(v);
+      nv += v > -INFINITY;
+    }
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) nv += __shfl_xor(nv, o);
+    if (lane == 0) wsum[wave] = nv;
+    __syncthreads();
+    const int nvalid = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+    __syncthreads();
+    if (nvalid <= cfg.topk) {
+      for (int j = tid; j < kc; j += 256) sflag[j] = sval[j] > -INFINITY;
+    } else {
+      use_thr = true;
+      uint64_t prefix = 0;
+      int krem = cfg.topk;
+      for (int pass = 0; pass < 8; ++pass) {
+        const int shift = 56 - 8 * pass;
+        hist[tid] = 0;
+        __syncthreads();
+        for (int j = tid; j < kc; j += 256) {
+          const uint64_t k = skey[j];
+          if (pass == 0 || (k >> (shift + 8)) == (prefix >> (shift + 8))) atomicAdd(&hist[(int)((k >> shift) & 255)], 1);
+        }
+        __syncthreads();
+        // thread t owns bin 255 - t: an inclusive scan over t counts the keys in higher or equal bins
+        const int bin = 255 - tid;
+        const int cnt = hist[bin];
+        int incl = cnt;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) { const int u = __shfl_up(incl, o); if (lane >= o) incl += u; }
+        if (lane == 63) wsum[wave] = incl;
+        __syncthreads();
+        for (int w = 0; w < wave; ++w) incl += wsum[w];
+        const int excl = incl - cnt;
+        if (excl < krem && krem <= incl) { s_digit = bin; s_krem = krem - excl; }
+        __syncthreads();
+        prefix |= (uint64_t)s_digit << shift;
+        krem = s_krem;
       }
-      sflag[j] = (sval[j] > -INFINITY) && rank < cfg.topk;
+      thr_key = prefix; thr_rem = krem;
     }
   } else {
     // weights w_j = n_j exp(alpha (S_j - max S)); order by (w desc, j asc); shortest prefix
@@ -175,14 +230,28 @@ __global__ __launch_bounds__(256) void select_kernel(SelectCfg cfg, const float*
   }
   __syncthreads();
 
-  // ---- ascending compaction of the flagged indices
+  // ---- ascending compaction of the selected indices
   int32_t* out = sel_idx + ((size_t)h * cfg.Cq + i) * cfg.cap;
-  int run = 0;
-  const int lane = tid & 63, wave = tid >> 6;
+  int run = 0, run_eq = 0;
   const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
   for (int j0 = 0; j0 < kc; j0 += 256) {
     const int j = j0 + tid;
-    const bool f = j < kc && sflag[j] != 0;
+    bool f;
+    if (use_thr) {
+      const bool valid = j < kc && sval[j] > -INFINITY;
+      const uint64_t k = j < kc ? skey[j] : 0ull;
+      const bool eq = valid && k == thr_key;
+      const uint64_t bal_eq = __ballot(eq);
+      __syncthreads();
+      if (lane == 0) wsum2[wave] = __popcll(bal_eq);
+      __syncthreads();
+      int eq_before = run_eq + __popcll(bal_eq & lt_mask);
+      for (int w = 0; w < wave; ++w) eq_before += wsum2[w];
+      run_eq += wsum2[0] + wsum2[1] + wsum2[2] + wsum2[3];
+      f = valid && (k > thr_key || (eq && eq_before < thr_rem));
+    } else {
+      f = j < kc && sflag[j] != 0;
+    }
     const uint64_t bal = __ballot(f);
     __syncthreads();
     if (lane == 0) wsum[wave] = __popcll(bal);

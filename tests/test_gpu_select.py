@@ -68,3 +68,34 @@ def test_full_flag_selects_all_nonempty_and_ties_go_low():
     for i in range(Cq):
         assert np.array_equal(got[0][i], np.flatnonzero(sizes[0, :20] > 0))
         assert got[1][i].tolist() == [0, 1, 2, 3]
+
+
+@pytest.mark.parametrize("topk", [5, 64, 300])
+def test_equal_scores_at_the_topk_boundary_over_several_chunks(topk):
+    """Duplicate key centroids give exactly equal scores; the ones that tie at the k-th place must be
+    taken in ascending index order, wherever in the list they sit (the kernel walks the list 256 at a
+    time)."""
+    H, Cq, d = 2, 5, 64
+    m0, nmax = 100, 700
+    cap = m0 + nmax
+    kc = 700
+    qc, mean_norm, kcent, bmin, bmax, sizes, kcount = make_inputs(11, H, Cq, cap, [kc, kc], d)
+    rng = np.random.default_rng(12)
+    sizes[:, :kc] = 3
+    sizes[:, 17] = 0
+    for h in range(H):
+        # 40 groups of 12 duplicates each, members spread over the whole list
+        ids = rng.permutation(kc)[:480].reshape(40, 12)
+        for g in ids:
+            kcent[h, g] = kcent[h, g[0]]
+    full = np.zeros(H, dtype=np.int32)
+    p = B.Params(H=H, N=100000, d=d, q_clusters=Cq, k_m0=m0, k_m_min=4, k_max_clusters=nmax, topk=topk)
+    c = lambda a: torch.from_numpy(a).cuda()
+    si, sc = B.adacluster_select(p, c(qc), c(mean_norm), c(kcent), None, None, c(sizes), c(kcount), c(full))
+    got = sel_from_dev(si, sc)
+    for h in range(H):
+        S = orc.cluster_scores(B.SCORE_TQ, qc[h].astype(np.float64), kcent[h, :kc].astype(np.float64), None, None,
+                               sizes[h, :kc])
+        ref = orc.select_topk(S, topk)
+        for i in range(Cq):
+            assert np.array_equal(got[h][i], ref[i]), (h, i)
