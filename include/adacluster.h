@@ -219,7 +219,8 @@ int adacluster_compactness(const adacluster_params* p, const void* K, const int3
  * selection (stand-alone sparse_attn: the two label sorts), K/V permutation, planning, and the
  * attention kernel; -1 for a stage the call did not run.  In adacluster_attn the two clusterings
  * run side by side and each is timed from the start of the call, so their sum exceeds the time
- * the pair takes.  Not thread-safe.
+ * the pair takes; the K/V permutation is timed from the final key sort, after which it runs on the
+ * second stream beside the tail of Algorithm 1, the selection and the planning.  Not thread-safe.
  */
 int adacluster_profile_enable(int on);
 int adacluster_profile_read(float* ms);
