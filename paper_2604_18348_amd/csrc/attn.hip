@@ -21,31 +21,48 @@ static constexpr int SPLIT_SLOTS = 64;   // partial slots per head for the chunk
 // ------------------------------------------------------------------------------------------
 // permutation of K and V rows
 // ------------------------------------------------------------------------------------------
-// dst[h][i][:] = src[h][perm[h][i]][:], 16-byte pieces, one row per group of ROWB/16 lanes.
+// dst[h][i][:] = src[h][perm[h][i]][:], 16-byte pieces, one row per group of ROWB/16 lanes; a thread
+// moves its piece of RPT rows of both tensors, all loads issued before the first store.
+#ifndef GATHER_RPT
+#define GATHER_RPT 4
+#endif
 template <int ROWB>
 __global__ __launch_bounds__(256) void gather_rows2(const uint8_t* __restrict__ a, const uint8_t* __restrict__ b,
                                                     const int32_t* __restrict__ perm, int N,
                                                     uint8_t* __restrict__ ao, uint8_t* __restrict__ bo) {
-  constexpr int LPR = ROWB / 16;
+  constexpr int LPR = ROWB / 16, RPB = 256 / LPR, RPT = GATHER_RPT;
   const int h = blockIdx.y;
-  const int r = blockIdx.x * (256 / LPR) + threadIdx.x / LPR;
+  const int r0 = blockIdx.x * (RPB * RPT) + threadIdx.x / LPR;
   const int q = threadIdx.x % LPR;
-  if (r >= N) return;
-  const int src = perm[(size_t)h * N + r];
-  const size_t so = ((size_t)h * N + src) * ROWB + q * 16;
-  const size_t dd = ((size_t)h * N + r) * ROWB + q * 16;
-  const uint4 va = *reinterpret_cast<const uint4*>(a + so);
-  const uint4 vb = *reinterpret_cast<const uint4*>(b + so);
-  *reinterpret_cast<uint4*>(ao + dd) = va;
-  *reinterpret_cast<uint4*>(bo + dd) = vb;
+  const int32_t* pm = perm + (size_t)h * N;
+  int src[RPT];
+#pragma unroll
+  for (int k = 0; k < RPT; ++k) { const int r = r0 + k * RPB; src[k] = r < N ? pm[r] : 0; }
+  uint4 va[RPT], vb[RPT];
+#pragma unroll
+  for (int k = 0; k < RPT; ++k) {
+    const size_t so = ((size_t)h * N + src[k]) * ROWB + q * 16;
+    va[k] = *reinterpret_cast<const uint4*>(a + so);
+    vb[k] = *reinterpret_cast<const uint4*>(b + so);
+  }
+#pragma unroll
+  for (int k = 0; k < RPT; ++k) {
+    const int r = r0 + k * RPB;
+    if (r >= N) continue;
+    const size_t dd = ((size_t)h * N + r) * ROWB + q * 16;
+    *reinterpret_cast<uint4*>(ao + dd) = va[k];
+    *reinterpret_cast<uint4*>(bo + dd) = vb[k];
+  }
 }
 
 int launch_permute_kv(hipStream_t s, int H, int N, int row_bytes, const void* K, const void* V,
                       const int32_t* perm, void* Kp, void* Vp) {
   auto A = (const uint8_t*)K; auto B = (const uint8_t*)V; auto Ao = (uint8_t*)Kp; auto Bo = (uint8_t*)Vp;
-  if (row_bytes == 128) gather_rows2<128><<<dim3((N + 31) / 32, H), 256, 0, s>>>(A, B, perm, N, Ao, Bo);
-  else if (row_bytes == 256) gather_rows2<256><<<dim3((N + 15) / 16, H), 256, 0, s>>>(A, B, perm, N, Ao, Bo);
-  else if (row_bytes == 512) gather_rows2<512><<<dim3((N + 7) / 8, H), 256, 0, s>>>(A, B, perm, N, Ao, Bo);
+  const int rows_per_block = 256 / (row_bytes / 16) * GATHER_RPT;
+  const dim3 g((N + rows_per_block - 1) / rows_per_block, H);
+  if (row_bytes == 128) gather_rows2<128><<<g, 256, 0, s>>>(A, B, perm, N, Ao, Bo);
+  else if (row_bytes == 256) gather_rows2<256><<<g, 256, 0, s>>>(A, B, perm, N, Ao, Bo);
+  else if (row_bytes == 512) gather_rows2<512><<<g, 256, 0, s>>>(A, B, perm, N, Ao, Bo);
   else return ADACLUSTER_E_BADSHAPE;
   return hipGetLastError() == hipSuccess ? 0 : ADACLUSTER_E_INTERNAL;
 }
