@@ -16,7 +16,7 @@
 namespace adac {
 
 static constexpr int TILE_REC = 6;       // ints per query-tile record
-static constexpr int SPLIT_SLOTS = 64;   // partial slots per head for the chunks of cut key lists
+static constexpr int SPLIT_SLOTS = 128;  // partial slots per head for the chunks of cut key lists
 
 // ------------------------------------------------------------------------------------------
 // permutation of K and V rows
@@ -144,9 +144,11 @@ __global__ __launch_bounds__(256) void plan_tiles(int Cq, int maxr, int maxtiles
       int pieces = 1;
       if (allow_split && T > 2 * chunk) {
         pieces = min(16, (T + chunk - 1) / chunk);
+        if (used + pieces * s_nq[c] > slots) pieces = max(1, (slots - used) / max(s_nq[c], 1));   // fewer, longer chunks
+      }
+      if (pieces > 1) {
         const int per = (T + pieces - 1) / pieces;
         pieces = max(1, (T + per - 1) / max(per, 1));          // no empty chunk
-        if (used + pieces * s_nq[c] > slots) pieces = 1;
       }
       s_pieces[c] = pieces; s_tile0[c] = nt; s_slot0[c] = used; s_merge0[c] = nm;
       nt += s_nq[c] * pieces;

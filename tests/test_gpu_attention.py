@@ -135,6 +135,24 @@ def test_skewed_selection_cuts_the_long_key_list(d):
         print("skewed", d, h, check(got[h], ref, B.BF16))
 
 
+def test_more_cut_lists_than_partial_slots():
+    """Ten query clusters of three query tiles select every key; the rest select one small cluster.  The
+    chunks wanted (10 x 3 x 5) exceed the partial slots of a head, so the last lists are cut into fewer
+    chunks or stay whole; every row must still match."""
+    H, N, d, Cq, Ck = 1, 36000, 64, 60, 300
+    Q, K, V = wl.make_small(14, N, d, 16, dtype="bf16", H=H)
+    rng = np.random.default_rng(15)
+    sizes = np.array([380] * 10 + [644] * 50)
+    assert sizes.sum() == N
+    ql = np.repeat(np.arange(Cq), sizes).astype(np.int32)
+    ql = ql[rng.permutation(N)][None, :]
+    kl = rng.integers(0, Ck, (H, N)).astype(np.int32)
+    sel = [[np.arange(Ck, dtype=np.int64) if i < 10 else np.array([i], dtype=np.int64) for i in range(Cq)]]
+    got = run_sparse(Q, K, V, ql, kl, sel, B.BF16, Cq, Ck)
+    ref = orc.sparse_attention_gather(Q[0], K[0], V[0], ql[0], kl[0], sel[0])
+    print("slot shortage", check(got[0], ref, B.BF16))
+
+
 def test_empty_selection_gives_zero_rows_and_custom_scale():
     Cq, Ck = 5, 23
     Q, K, V, ql, kl, sel = make_case(4, 600, 64, B.BF16)
