@@ -128,6 +128,8 @@ int check_params(const adacluster_params* p) {
   return 0;
 }
 
+constexpr int STAGE_SUM_BLOCKS = 128;   // a stage of at most this many 256-point blocks may update from block sums
+
 inline int capacity(const adacluster_params* p) { return p->k_max_clusters + p->k_m0; }
 inline size_t esize(const adacluster_params* p) { return p->dtype == ADACLUSTER_BF16 ? 2 : 4; }
 // upper bound of the number of 128-row parts of n rows in m clusters
@@ -145,7 +147,7 @@ struct WS {
   void* cent_lp; float* bias; float* master;
   int32_t* labels_tmp; float* dist2; int32_t* ulist[2]; int32_t* blockcnt; double* tau_part;
   SortScratch sort; int32_t* perm_tmp; int32_t* offs_tmp; int32_t* poff;
-  float* psum; float* pnorm; float* pmin; float* pmax;
+  float* psum; float* pnorm; float* pmin; float* pmax; int32_t* bcnt;
   int32_t* perm_q; int32_t* offs_q; int32_t* perm_k; int32_t* offs_k;
   // scratch of the query clustering (its own set: it runs beside the key clustering)
   void* q_cent_lp; float* q_bias; SortScratch q_sort; int32_t* q_poff; float* q_psum; float* q_pnorm;
@@ -202,6 +204,7 @@ size_t layout(const adacluster_params* p, WS* w, unsigned char* base) {
   TAKE(offs_tmp, int32_t*, H * (size_t)(D.capmax + 1) * 4);
   TAKE(poff, int32_t*, H * (size_t)(D.capmax + 1) * 4);
   TAKE(psum, float*, H * (size_t)D.prow * d * 4);
+  TAKE(bcnt, int32_t*, H * (size_t)STAGE_SUM_BLOCKS * assign_block_sum_centres() * 4);
   TAKE(pnorm, float*, H * (size_t)D.prow * 4);
   TAKE(pmin, float*, H * (size_t)D.prow * d * 4);
   TAKE(pmax, float*, H * (size_t)D.prow * d * 4);
@@ -357,10 +360,25 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
     RET_IF(launch_init_centroids(st, p->dtype, D.d, D.H, D.N, 1, 0, m_bound, w.kstate, ul, 0, 0, D.cap, p->k_m0, K,
                                  w.master, w.cent_lp, k_assign, w.bias));
     const int P = parts_for(n_bound, m_bound);
+    // A small stage (few blocks of points, few centres) updates its centres from sums that the
+    // assignment kernel leaves per block: no label sort and no segmented reduction in between.
+    const int nblk = (n_bound + 255) / 256;
+    const bool block_sums = p->dtype == ADACLUSTER_BF16 && nblk <= STAGE_SUM_BLOCKS &&
+                            m_bound <= assign_block_sum_centres() && (long long)m_bound * nblk <= D.prow;
+    const int Pb = m_bound * nblk;     // rows of the part-sum table the block sums take per head
     for (int it = 0; it < p->k_iters; ++it) {
+      const bool update = it < p->k_iters - 1;
+      if (block_sums && update) {
+        RET_IF(launch_assign(st, p->dtype, D.d, D.H, D.N, n_bound, 1, 0, D.cap, w.kstate, ul, K, w.cent_lp, w.bias,
+                             w.labels_tmp, w.dist2, w.psum, w.bcnt, Pb));
+        RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 1, 0, m_bound, Pb, D.cap, p->k_m0, w.kstate, 0, 1, 0,
+                               nullptr, 0, nullptr, w.psum, w.pnorm, w.pmin, w.pmax, w.master, w.cent_lp,
+                               k_assign, w.bias, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, w.bcnt, nblk));
+        continue;
+      }
       RET_IF(launch_assign(st, p->dtype, D.d, D.H, D.N, n_bound, 1, 0, D.cap, w.kstate, ul, K, w.cent_lp, w.bias,
                            w.labels_tmp, w.dist2));
-      if (it < p->k_iters - 1) {
+      if (update) {
         RET_IF(launch_sort(st, D.H, D.N, n_bound, m_bound, w.labels_tmp, ul, &w.kstate->ucount,
                            sizeof(KState) / 4, &w.kstate->m_t, sizeof(KState) / 4, &w.kstate->active,
                            sizeof(KState) / 4, w.perm_tmp, w.offs_tmp, D.capmax + 1, w.sort, w.poff, reduce_part_rows(), &poff_done));

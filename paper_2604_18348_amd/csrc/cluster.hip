@@ -37,11 +37,25 @@ __device__ __forceinline__ bool assign_setup(const AssignCfg& c, int h, int& n, 
 // two half-waves are merged once at the end.  Two workgroups per CU in the launch bounds keep the
 // register budget at 256, so the accumulators are ordinary VGPRs that the arg-max reads directly (with
 // 512 the compiler parks them in AGPRs and copies every value out first).
-template <int D>
-__global__ __launch_bounds__(256, 2) void assign_mfma(const bf16raw* __restrict__ X, AssignCfg cfg,
-                                                   const bf16raw* __restrict__ cent,
-                                                   const float* __restrict__ bias,
-                                                   int32_t* __restrict__ labels, float* __restrict__ dist2) {
+//
+// ACC (small stages of Algorithm 1): the workgroup also leaves, per centre, the sum and the count of the
+// points of its block that chose it, so that the centroid update needs neither a label sort nor a
+// segmented reduction.  The sums are a second MFMA product, S^T[32 dims x 32 centres] +=
+// X^T[32 dims x 16 points] . E[16 points x 32 centres] with E the one-hot label matrix: exact products,
+// fp32 accumulation in a fixed order.  Block b of head h writes row j * nb_stride + b of the head's
+// part-sum table and bcnt[(h * nb_stride + b) * ACC_MAXM + j].
+struct AccumOut { float* psum; int32_t* bcnt; int P; int nb_stride; };
+constexpr int ACC_MAXM = 128;          // most centres the block sums are kept for
+
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4_t;
+typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
+
+template <int D, bool ACC>
+__global__ __launch_bounds__(256, (ACC && D == 128) ? 1 : 2) void assign_mfma(const bf16raw* __restrict__ X, AssignCfg cfg,
+                                                                const bf16raw* __restrict__ cent,
+                                                                const float* __restrict__ bias,
+                                                                int32_t* __restrict__ labels, float* __restrict__ dist2,
+                                                                AccumOut acc_out) {
   constexpr int CB = D == 128 ? 64 : 128;   // centres per LDS chunk (about 17 KB either way; larger chunks measured slower)
   constexpr int LDW = D + 8;            // padded row (bf16 elements): conflict-free 16-byte reads
   constexpr int KS = D / 16;
@@ -141,6 +155,7 @@ __global__ __launch_bounds__(256, 2) void assign_mfma(const bf16raw* __restrict_
       }
     }
   }
+  int blab[PB];
 #pragma unroll
   for (int pb = 0; pb < PB; ++pb) {
     // accumulator value v of a tile is centre  32*tile + 8*(v/4) + 4*hb + v%4
@@ -153,6 +168,70 @@ __global__ __launch_bounds__(256, 2) void assign_mfma(const bf16raw* __restrict_
     if (hb == 0 && pos[pb] < n) {
       labels[(size_t)h * cfg.N + pos[pb]] = bidx;
       if (dist2) dist2[(size_t)h * cfg.N + pos[pb]] = fmaxf(xn2[pb] - 2.f * bv, 0.f);
+    }
+    if (ACC) blab[pb] = pos[pb] < n ? bidx : -1;
+  }
+  if constexpr (ACC) {
+    constexpr int ROWB = D * 2, DT = D / 32;
+    __shared__ __attribute__((aligned(16))) bf16raw xs[256 * D];     // the block's points, row-major
+    __shared__ __attribute__((aligned(16))) int32_t lab_s[256];
+#pragma unroll
+    for (int pb = 0; pb < PB; ++pb) {
+      const int pr = wave * (PB * 32) + pb * 32 + c;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) *reinterpret_cast<bf16x8_t*>(&xs[pr * D + ks * 16 + hb * 8]) = xf[pb][ks];
+      if (hb == 0) lab_s[pr] = blab[pb];
+    }
+    __syncthreads();
+    const int b = blockIdx.x;
+    // output tiles (centre tile ct, dim tile db) dealt to the four waves; one more "dim tile" per centre
+    // tile has X^T replaced by ones, so that its rows are the member counts (exact: at most 256)
+    const int CT = (m + 31) >> 5;
+    // X^T operand by transpose reads (see the V operand of the attention kernel): this lane addresses
+    // point 4*hb + (lane%16)/4 of a 16-point group, dims 16*((lane/16)%2) + 4*(lane%4) .. +3
+    const int i16 = lane & 15, blk = lane >> 4;
+    const int vrow = 4 * hb + (i16 >> 2);
+    const int gl = 2 * (blk & 1) + ((i16 & 3) >> 1);
+    const char* xsb = reinterpret_cast<const char*>(xs);
+    for (int t = wave; t < CT * (DT + 1); t += 4) {
+      const int ct = t / (DT + 1), db = t % (DT + 1);
+      const bool counting = db == DT;
+      const int cid = ct * 32 + c;
+      f32x16_t sacc;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
+      const int xoff = vrow * ROWB + ((counting ? 0 : db) * 4 + gl) * 16 + 8 * (i16 & 1);
+#pragma unroll
+      for (int g = 0; g < 16; ++g) {
+        const char* xp = xsb + g * 16 * ROWB + xoff;
+        const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)xp);
+        const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(xp + 8 * ROWB));
+        const s16x4_t both[2] = {lo, hi};
+        bf16x8_t xa = *reinterpret_cast<const bf16x8_t*>(both);
+        if (counting) { const uint4 o = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u}; xa = *reinterpret_cast<const bf16x8_t*>(&o); }
+        // one-hot rows of the points this lane's eight operand elements stand for
+        const int4 l0 = *reinterpret_cast<const int4*>(&lab_s[g * 16 + 4 * hb]);
+        const int4 l1 = *reinterpret_cast<const int4*>(&lab_s[g * 16 + 8 + 4 * hb]);
+        uint4 e;
+        e.x = (l0.x == cid ? 0x3F80u : 0u) | (l0.y == cid ? 0x3F800000u : 0u);
+        e.y = (l0.z == cid ? 0x3F80u : 0u) | (l0.w == cid ? 0x3F800000u : 0u);
+        e.z = (l1.x == cid ? 0x3F80u : 0u) | (l1.y == cid ? 0x3F800000u : 0u);
+        e.w = (l1.z == cid ? 0x3F80u : 0u) | (l1.w == cid ? 0x3F800000u : 0u);
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, *reinterpret_cast<const bf16x8_t*>(&e), sacc, 0, 0, 0);
+      }
+      if (counting) {
+        if (cid < m && hb == 0) acc_out.bcnt[((size_t)h * acc_out.nb_stride + b) * ACC_MAXM + cid] = (int)sacc[0];
+        continue;
+      }
+      // value v of the tile is dim db*32 + 8*(v/4) + 4*hb + v%4 of centre cid
+      if (cid < m) {
+        float* out = acc_out.psum + ((size_t)h * acc_out.P + (size_t)cid * acc_out.nb_stride + b) * D + db * 32 + 4 * hb;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float4 o4 = {sacc[4 * i], sacc[4 * i + 1], sacc[4 * i + 2], sacc[4 * i + 3]};
+          *reinterpret_cast<float4*>(out + 8 * i) = o4;
+        }
+      }
     }
   }
 }
@@ -422,6 +501,7 @@ struct FinalizeCfg {
   int mode; int m_const; int P; int m_bound; int cap; int master_stride;
   const KState* st;
   int spherical; int update_assign; int lp_is_bf16; int want_box;
+  const int32_t* bcnt; int nb_stride;     // block sums of the assignment kernel instead of cluster parts (stage mode)
 };
 
 template <int D>
@@ -449,14 +529,40 @@ __global__ __launch_bounds__(64) void finalize_centroids(FinalizeCfg cfg, const 
     if (!cfg.update_assign && out_sizes && j < cfg.cap) out_sizes[(size_t)h * cfg.cap + j] = 0;
     return;
   }
-  const int nj = offs[(size_t)h * offs_stride + j + 1] - offs[(size_t)h * offs_stride + j];
+  int nj, p_beg, p_end;
+  if (cfg.bcnt) {
+    // the blocks of 256 points of the assignment kernel, in block order
+    const int nb = (cfg.st[h].ucount + 255) >> 8;
+    nj = 0;
+    for (int b = lane; b < nb; b += 64) nj += cfg.bcnt[((size_t)h * cfg.nb_stride + b) * ACC_MAXM + j];
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) nj += __shfl_xor(nj, o);
+    p_beg = j * cfg.nb_stride; p_end = p_beg + nb;
+  } else {
+    nj = offs[(size_t)h * offs_stride + j + 1] - offs[(size_t)h * offs_stride + j];
+    p_beg = poff[(size_t)h * offs_stride + j]; p_end = poff[(size_t)h * offs_stride + j + 1];
+  }
   const size_t pbase = (size_t)h * cfg.P;
-  const int p_beg = poff[(size_t)h * offs_stride + j], p_end = poff[(size_t)h * offs_stride + j + 1];
   float s[CPL], mn[CPL], mx[CPL];
 #pragma unroll
   for (int q = 0; q < CPL; ++q) { s[q] = 0.f; mn[q] = INFINITY; mx[q] = -INFINITY; }
   float ns = 0.f;
-  for (int p = p_beg; p < p_end; ++p) {
+  int p = p_beg;
+  if (!cfg.want_box && !cfg.spherical) {
+    // sums only: eight parts' loads in flight, added in part order all the same
+    for (; p + 8 <= p_end; p += 8) {
+      float t[8][CPL];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int q = 0; q < CPL; ++q) t[u][q] = psum[(pbase + p + u) * D + lane + 64 * q];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int q = 0; q < CPL; ++q) s[q] += t[u][q];
+    }
+  }
+  for (; p < p_end; ++p) {
 #pragma unroll
     for (int q = 0; q < CPL; ++q) {
       s[q] += psum[(pbase + p) * D + lane + 64 * q];
@@ -901,16 +1007,24 @@ __global__ __launch_bounds__(256) void mse_final(const double* __restrict__ part
 static inline int chk() { return hipGetLastError() == hipSuccess ? 0 : ADACLUSTER_E_INTERNAL; }
 
 int reduce_part_rows() { return REDUCE_ROWS; }
+int assign_block_sum_centres() { return ACC_MAXM; }
 
 int launch_assign(hipStream_t s, int dtype, int d, int H, int N, int n_bound, int mode, int m_const, int cap,
                   const KState* st, const int32_t* ulist, const void* X, const void* cent_lp, const float* bias,
-                  int32_t* labels, float* dist2) {
+                  int32_t* labels, float* dist2, float* blk_sum, int32_t* blk_cnt, int P) {
   AssignCfg c{mode, m_const, N, cap, st, ulist};
   if (dtype == ADACLUSTER_BF16) {
     dim3 g((n_bound + 255) / 256, H);
-    if (d == 64) assign_mfma<64><<<g, 256, 0, s>>>((const bf16raw*)X, c, (const bf16raw*)cent_lp, bias, labels, dist2);
-    else assign_mfma<128><<<g, 256, 0, s>>>((const bf16raw*)X, c, (const bf16raw*)cent_lp, bias, labels, dist2);
+    const AccumOut ao{blk_sum, blk_cnt, P, (int)g.x};
+    if (blk_sum) {
+      if (d == 64) assign_mfma<64, true><<<g, 256, 0, s>>>((const bf16raw*)X, c, (const bf16raw*)cent_lp, bias, labels, dist2, ao);
+      else assign_mfma<128, true><<<g, 256, 0, s>>>((const bf16raw*)X, c, (const bf16raw*)cent_lp, bias, labels, dist2, ao);
+    } else {
+      if (d == 64) assign_mfma<64, false><<<g, 256, 0, s>>>((const bf16raw*)X, c, (const bf16raw*)cent_lp, bias, labels, dist2, ao);
+      else assign_mfma<128, false><<<g, 256, 0, s>>>((const bf16raw*)X, c, (const bf16raw*)cent_lp, bias, labels, dist2, ao);
+    }
   } else {
+    if (blk_sum) return ADACLUSTER_E_INTERNAL;     // block sums exist for bf16 only
     dim3 g((n_bound + 127) / 128, H);
     if (d == 64) assign_f32<64><<<g, 128, 0, s>>>((const float*)X, c, (const float*)cent_lp, bias, labels, dist2);
     else assign_f32<128><<<g, 128, 0, s>>>((const float*)X, c, (const float*)cent_lp, bias, labels, dist2);
@@ -940,9 +1054,9 @@ int launch_finalize(hipStream_t s, int dtype, int d, int H, int mode, int m_cons
                     const int32_t* offs, int offs_stride, const int32_t* poff, const float* psum, const float* pnorm,
                     const float* pmin, const float* pmax, float* master, void* assign_lp, float* assign_f32,
                     float* bias, float* out_cent, const float* fallback, int32_t* out_sizes,
-                    float* out_mean_norm, float* out_bmin, float* out_bmax) {
+                    float* out_mean_norm, float* out_bmin, float* out_bmax, const int32_t* blk_cnt, int nb_stride) {
   FinalizeCfg c{mode, m_const, P, m_bound, cap, master_stride, st, spherical, update_assign,
-                dtype == ADACLUSTER_BF16, want_box};
+                dtype == ADACLUSTER_BF16, want_box, blk_cnt, nb_stride};
   // in final mode every row of the output (up to cap) gets a size, so cover cap rows
   dim3 g(update_assign ? m_bound : cap, H);
   if (d == 64)

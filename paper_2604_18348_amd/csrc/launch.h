@@ -24,7 +24,8 @@ int launch_sort(hipStream_t st, int H, int N, int n_bound, int m_bound, const in
 
 int launch_assign(hipStream_t s, int dtype, int d, int H, int N, int n_bound, int mode, int m_const, int cap,
                   const KState* st, const int32_t* ulist, const void* X, const void* cent_lp, const float* bias,
-                  int32_t* labels, float* dist2);
+                  int32_t* labels, float* dist2, float* blk_sum = nullptr, int32_t* blk_cnt = nullptr, int P = 0);
+int assign_block_sum_centres();   // most centres the assignment kernel keeps block sums for
 int launch_seg_reduce(hipStream_t s, int dtype, int d, int H, int N, int mode, int m_const, int m_bound, int P,
                       const KState* st, int normalize, int want_box, const void* X, const int32_t* perm,
                       const int32_t* offs, int offs_stride, int32_t* poff, float* psum, float* pnorm, float* pmin, float* pmax,
@@ -35,7 +36,8 @@ int launch_finalize(hipStream_t s, int dtype, int d, int H, int mode, int m_cons
                     const int32_t* offs, int offs_stride, const int32_t* poff, const float* psum, const float* pnorm,
                     const float* pmin, const float* pmax, float* master, void* assign_lp, float* assign_f32,
                     float* bias, float* out_cent, const float* fallback, int32_t* out_sizes,
-                    float* out_mean_norm, float* out_bmin, float* out_bmax);
+                    float* out_mean_norm, float* out_bmin, float* out_bmax, const int32_t* blk_cnt = nullptr,
+                    int nb_stride = 0);
 int launch_init_centroids(hipStream_t s, int dtype, int d, int H, int N, int mode, int m_const, int m_bound,
                           const KState* st, const int32_t* ulist, int spherical, int source_master, int cap,
                           int master_stride, const void* X, float* master, void* assign_lp, float* assign_f32,

@@ -221,6 +221,31 @@ def test_kcluster_fp32_stage_centres_follow_the_oracle_trajectory():
     assert bool(out["full_flag"][0]) == ref["full_flag"]
 
 
+@pytest.mark.parametrize("d,N,tau", [(64, 1600, 3.0), (128, 2900, 4.5)])
+def test_kcluster_bf16_stage_centres_follow_the_oracle_trajectory(d, N, tau):
+    """bf16 stages this small update their centres from the per-block sums of the assignment kernel (no
+    sort, no segmented reduction): stage structure, stage centres and labels must follow the oracle run
+    with bf16-rounded assignment centres."""
+    H = 1
+    _, K, _ = wl.make_small(29, N, d, 14, dtype="bf16", H=H)
+    p = B.Params(H=H, N=N, d=d, dtype=B.BF16, q_clusters=4, k_iters=3, k_m0=14, k_m_min=4, k_max_clusters=64,
+                 tau_abs=tau)
+    out = B.adacluster_kcluster(p, to_dev(K, B.BF16))
+    ref = orc.multistage_kmeans(K[0], tau, 64, 14, 4, 3, round_fn=orc.round_to_bf16)
+    kc = int(out["k_count"][0])
+    print("k_count", kc, "oracle", ref["assign_centroids"].shape[0])
+    assert kc == ref["assign_centroids"].shape[0]
+    assert np.array_equal(out["k_stage_offs"].cpu().numpy()[0][:len(ref["stage_offs"])], ref["stage_offs"])
+    got = to_np(out["k_assign_centroids"])[0, :kc]
+    # both sides round the centres to bf16: allow one bf16 step where the fp32 and fp64 means straddle a tie
+    assert np.all(np.abs(got - ref["assign_centroids"]) <= 2.0 ** -7 * np.maximum(np.abs(got), 1e-3)), \
+        float(np.abs(got - ref["assign_centroids"]).max())
+    assert float((got == ref["assign_centroids"]).mean()) > 0.99
+    # a centre that differs by one bf16 step moves the points on its boundary
+    assert float((out["k_labels"].cpu().numpy()[0] == ref["labels"]).mean()) > 0.99
+    assert bool(out["full_flag"][0]) == ref["full_flag"]
+
+
 @pytest.mark.parametrize("dtype,d", [(B.BF16, 64), (B.BF16, 128), (B.F32, 64)])
 def test_kcluster_warm_start_chained(dtype, d):
     """Warm start: count fixed, previous centres as the start, k_iters passes; labels are the
