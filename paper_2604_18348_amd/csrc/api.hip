@@ -147,7 +147,7 @@ struct WS {
   void* cent_lp; float* bias; float* master;
   int32_t* labels_tmp; float* dist2; int32_t* ulist[2]; int32_t* blockcnt; double* tau_part;
   SortScratch sort; int32_t* perm_tmp; int32_t* offs_tmp; int32_t* poff;
-  float* psum; float* pnorm; float* pmin; float* pmax; int32_t* bcnt;
+  float* psum; float* pnorm; float* pmin; float* pmax; int32_t* bcnt; float* bsum;
   int32_t* perm_q; int32_t* offs_q; int32_t* perm_k; int32_t* offs_k;
   // scratch of the query clustering (its own set: it runs beside the key clustering)
   void* q_cent_lp; float* q_bias; SortScratch q_sort; int32_t* q_poff; float* q_psum; float* q_pnorm;
@@ -162,7 +162,7 @@ struct WS {
 };
 
 struct Dims {
-  int H, N, d, Cq, cap, capmax, nblk, nseg, maxtiles, maxr, prow, BM;
+  int H, N, d, Cq, cap, capmax, nblk, nseg, maxtiles, maxr, prow, brow, BM;
 };
 
 Dims dims_of(const adacluster_params* p) {
@@ -175,6 +175,10 @@ Dims dims_of(const adacluster_params* p) {
   D.maxtiles = p->N / D.BM + D.Cq + 1 + attn_split_slots();
   D.maxr = D.cap;
   D.prow = p->N / 128 + D.capmax + 34;
+  {  // rows of the block-sum table of small stages: (blocks of 256 points) x (centres), both capped
+    const int nb = (p->N + 255) / 256, mb = p->k_m0 < assign_block_sum_centres() ? p->k_m0 : assign_block_sum_centres();
+    D.brow = (nb < STAGE_SUM_BLOCKS ? nb : STAGE_SUM_BLOCKS) * mb;
+  }
   return D;
 }
 
@@ -205,6 +209,7 @@ size_t layout(const adacluster_params* p, WS* w, unsigned char* base) {
   TAKE(poff, int32_t*, H * (size_t)(D.capmax + 1) * 4);
   TAKE(psum, float*, H * (size_t)D.prow * d * 4);
   TAKE(bcnt, int32_t*, H * (size_t)STAGE_SUM_BLOCKS * assign_block_sum_centres() * 4);
+  TAKE(bsum, float*, H * (size_t)D.brow * d * 4);
   TAKE(pnorm, float*, H * (size_t)D.prow * 4);
   TAKE(pmin, float*, H * (size_t)D.prow * d * 4);
   TAKE(pmax, float*, H * (size_t)D.prow * d * 4);
@@ -364,15 +369,15 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
     // assignment kernel leaves per block: no label sort and no segmented reduction in between.
     const int nblk = (n_bound + 255) / 256;
     const bool block_sums = p->dtype == ADACLUSTER_BF16 && nblk <= STAGE_SUM_BLOCKS &&
-                            m_bound <= assign_block_sum_centres() && (long long)m_bound * nblk <= D.prow;
+                            m_bound <= assign_block_sum_centres() && (long long)m_bound * nblk <= D.brow;
     const int Pb = m_bound * nblk;     // rows of the part-sum table the block sums take per head
     for (int it = 0; it < p->k_iters; ++it) {
       const bool update = it < p->k_iters - 1;
       if (block_sums && update) {
         RET_IF(launch_assign(st, p->dtype, D.d, D.H, D.N, n_bound, 1, 0, D.cap, w.kstate, ul, K, w.cent_lp, w.bias,
-                             w.labels_tmp, w.dist2, w.psum, w.bcnt, Pb));
+                             w.labels_tmp, w.dist2, w.bsum, w.bcnt, Pb));
         RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 1, 0, m_bound, Pb, D.cap, p->k_m0, w.kstate, 0, 1, 0,
-                               nullptr, 0, nullptr, w.psum, w.pnorm, w.pmin, w.pmax, w.master, w.cent_lp,
+                               nullptr, 0, nullptr, w.bsum, w.pnorm, w.pmin, w.pmax, w.master, w.cent_lp,
                                k_assign, w.bias, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, w.bcnt, nblk));
         continue;
       }
