@@ -55,9 +55,10 @@ __global__ __launch_bounds__(256) void select_kernel(SelectCfg cfg, const float*
   double* sval = reinterpret_cast<double*>(smem);                        // [cap] score, then weight
   uint64_t* skey = reinterpret_cast<uint64_t*>(smem + (size_t)cfg.lds_cap * 8);   // [lds_cap]
   int32_t* sflag = reinterpret_cast<int32_t*>(smem + (size_t)cfg.lds_cap * 16);   // [lds_cap]
-  __shared__ double qrow[128], qpos[128], qneg[128];
+  __shared__ double qrow[128];
+  __shared__ uint64_t qneg_mask[2];
   __shared__ int32_t wsum[4], wsum2[4];
-  __shared__ int32_t s_take, s_digit, s_krem;
+  __shared__ int32_t s_take, s_digit, s_krem, s_all;
   __shared__ int32_t hist[256];
   __shared__ double s_max;
 
@@ -69,11 +70,21 @@ __global__ __launch_bounds__(256) void select_kernel(SelectCfg cfg, const float*
   int thr_rem = 0;
   const int kc = min(k_count[h], cfg.lds_cap);
   const bool all = full_flag[h] != 0;
-  if (tid < d) {
-    const double q = (double)q_cent[((size_t)h * cfg.Cq + i) * d + tid];
-    qrow[tid] = q; qpos[tid] = fmax(q, 0.0); qneg[tid] = fmin(q, 0.0);
+  {
+    const double q = tid < d ? (double)q_cent[((size_t)h * cfg.Cq + i) * d + tid] : 0.0;
+    if (tid < d) qrow[tid] = q;
+    const uint64_t neg = __ballot(__double2hiint(q) < 0);        // sign bits of 64 dimensions
+    if (lane == 0 && wave < 2) qneg_mask[wave] = neg;
   }
   __syncthreads();
+  // wave-uniform sign masks of the query centroid, kept in scalar registers
+  const uint64_t nm0 = qneg_mask[0], nm1 = qneg_mask[1];
+  auto uniform64 = [](uint64_t v) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
+    return ((uint64_t)hi << 32) | (uint64_t)lo;
+  };
+  const uint64_t neg0 = uniform64(nm0), neg1 = uniform64(nm1);
 
   // ---- scores (a thread owns a key cluster; its row is read 16 bytes at a time)
   for (int j = tid; j < kc; j += 256) {
@@ -104,10 +115,19 @@ __global__ __launch_bounds__(256) void select_kernel(SelectCfg cfg, const float*
         const float pv[4] = {p4.x, p4.y, p4.z, p4.w}, nv[4] = {n4.x, n4.y, n4.z, n4.w};
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-          double kp = (double)pv[u], kn = (double)nv[u];
-          if (!box) { kp = fmax(kp, 0.0); kn = fmin(kn, 0.0); }
-          sp = sp + qpos[4 * t4 + u] * kp;
-          sn = sn + qneg[4 * t4 + u] * kn;
+          // The sign of q is the same for the whole workgroup.  The term of the other sign is an exact
+          // zero, and adding a zero leaves a running sum as it is, so only one of the two is formed
+          // (fp64 conversions, min/max, multiplies and adds are what this kernel spends its time on).
+          const double q = qrow[4 * t4 + u];
+          const int t = 4 * t4 + u;
+          const bool qpos_ = !(((t < 64 ? neg0 : neg1) >> (t & 63)) & 1ull);
+          if (qpos_) {
+            const float kp = box ? pv[u] : fmaxf(pv[u], 0.f);
+            sp = sp + q * (double)kp;
+          } else {
+            const float kn = box ? nv[u] : fminf(nv[u], 0.f);
+            sn = sn + q * (double)kn;
+          }
         }
       }
       s = sp + sn;
@@ -161,10 +181,12 @@ __global__ __launch_bounds__(256) void select_kernel(SelectCfg cfg, const float*
         __syncthreads();
         for (int w = 0; w < wave; ++w) incl += wsum[w];
         const int excl = incl - cnt;
-        if (excl < krem && krem <= incl) { s_digit = bin; s_krem = krem - excl; }
+        if (excl < krem && krem <= incl) { s_digit = bin; s_krem = krem - excl; s_all = (krem == incl); }
         __syncthreads();
         prefix |= (uint64_t)s_digit << shift;
         krem = s_krem;
+        // every key of the chosen bin is wanted: the threshold is the bin's lower edge, no ties to split
+        if (s_all && prefix != 0) { prefix -= 1; krem = 0; break; }
       }
       thr_key = prefix; thr_rem = krem;
     }
