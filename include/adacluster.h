@@ -17,10 +17,11 @@
  *     are undefined after a call.  Output buffers are fully overwritten.
  *   - All work is ordered by `stream` (a hipStream_t passed as void*; NULL is
  *     the default stream): it is enqueued there, except that adacluster_attn puts
- *     the query clustering on a second, library-owned stream per device (created
- *     on first use, default priority), forked from `stream` at the start of the
- *     call and joined back to it before the selection step, so work queued on
- *     `stream` after the call still waits for all of it.  Calls are asynchronous
+ *     the query clustering and the K/V permutation on a second, library-owned stream
+ *     (one per calling thread and device, created on first use, default priority),
+ *     forked from `stream` and joined back to it before the step that needs the
+ *     result, so work queued on `stream` after the call still waits for all of it.
+ *     Calls are asynchronous
  *     except adacluster_kcluster and adacluster_attn with k_init_mode 0, which block
  *     the calling thread once per clustering stage on an event, to read a few
  *     integers back through pinned host memory the library keeps per thread (the

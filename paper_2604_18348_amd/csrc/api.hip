@@ -39,15 +39,16 @@ void prof_mark(int which, hipStream_t st, int from = -1) {
   g_prof.from[which] = from;
 }
 
-// A second stream per device, for work of a call that does not depend on what the caller's
-// stream is doing (default priority, like every stream here), and the two events that fork it
-// from and join it to the caller's stream.
+// A second stream per calling thread and device, for work of a call that does not depend on what
+// the caller's stream is doing (default priority, like every stream here), and the events that fork
+// it from and join it to the caller's stream.  Per thread, so that calls of different host threads
+// on one device do not share events.
 struct AuxStream {
   bool ready = false;
   hipStream_t s = nullptr;
   hipEvent_t fork = nullptr, join = nullptr, join2 = nullptr;
 };
-AuxStream g_aux[64];
+thread_local AuxStream g_aux[64];
 
 // Pinned host slots for the per-stage report of Algorithm 1 and two events to wait on, per thread.
 struct StageReadback {

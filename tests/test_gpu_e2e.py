@@ -141,3 +141,42 @@ def test_fused_warm_start_call_chained():
         sel_ref = oracle_selection_from_gpu_centroids(outs, pw, h)
         for i in range(p.q_clusters):
             assert np.array_equal(sel_gpu[h][i], sel_ref[i])
+
+
+def test_two_host_threads_on_one_device():
+    """Two host threads run the fused call at the same time, each on a stream and a workspace of its own;
+    the library's second stream, its events and the stage read-back slots are per thread, so both must
+    reproduce what the same calls give one after the other (the call is deterministic)."""
+    import threading
+    H, N, d = 2, 2600, 64
+    cases = []
+    for seed in (41, 42):
+        Q, K, V = wl.make_small(seed, N, d, 10, dtype="bf16", H=H)
+        cases.append((to_dev(Q, B.BF16), to_dev(K, B.BF16), to_dev(V, B.BF16)))
+    p = B.Params(H=H, N=N, d=d, dtype=B.BF16, q_clusters=9, q_iters=3, k_iters=3, k_m0=16, k_m_min=4,
+                 k_max_clusters=64, min_unassigned_frac=0.03, topk=5)
+    ref = [B.adacluster_attn(p, *c).clone() for c in cases]
+    torch.cuda.synchronize()
+    got = [None, None]
+    errs = []
+
+    def work(i):
+        try:
+            s = torch.cuda.Stream()
+            with torch.cuda.stream(s):
+                ws = B.workspace(p)
+                for _ in range(5):
+                    out = B.adacluster_attn(p, *cases[i], ws=ws)
+                s.synchronize()
+            got[i] = out
+        except Exception as e:      # surfaced in the main thread
+            errs.append(e)
+
+    ts = [threading.Thread(target=work, args=(i,)) for i in range(2)]
+    for t in ts:
+        t.start()
+    for t in ts:
+        t.join()
+    assert not errs, errs
+    for i in range(2):
+        assert torch.equal(got[i], ref[i])
