@@ -213,6 +213,26 @@ int adacluster_compactness(const adacluster_params* p, const void* K, const int3
                            const float* k_centroids, float* k_mse, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Quest scores of query rows against key pages (Sec. 3.2.3), in either of the two forms whose speed the
+ * paper compares (Sec. 4.3, "TensorQuest reformulation benefits"):
+ *   form ADACLUSTER_QUEST_ALU   Eq. 1 as written, S[h,i,j] = sum_d max(q_d R+_jd, q_d R-_jd), fp32 vector
+ *                               arithmetic (any dtype);
+ *   form ADACLUSTER_QUEST_MFMA  Eq. 2 / Algorithm 2, S = Q+ (R+)^T + Q- (R-)^T with Q+ = max(Q,0),
+ *                               Q- = min(Q,0), two matrix products on the matrix cores, fp32 accumulation
+ *                               (bf16 inputs only: ADACLUSTER_E_UNSUPPORTED otherwise).
+ * R_pos and R_neg [H,Lk,d] are the per-dimension maxima and minima of every page (Eq. 1); with clamp != 0
+ * they are taken as max(R_pos, 0) and min(R_neg, 0) on the fly, which for R_pos == R_neg == a tensor of
+ * single vectors per page (cluster centroids) is Algorithm 2 as written.  The two forms agree exactly in
+ * real arithmetic whenever R_pos >= R_neg elementwise.
+ *   Q [H,Lq,d], R_pos, R_neg in `dtype`; S [H,Lq,Lk] fp32 out, fully overwritten.  d is 64 or 128.
+ * Device pointers; asynchronous on `stream`; needs no workspace.
+ */
+#define ADACLUSTER_QUEST_ALU  0
+#define ADACLUSTER_QUEST_MFMA 1
+int adacluster_quest_scores(int32_t H, int32_t Lq, int32_t Lk, int32_t d, int32_t dtype, int32_t form, int32_t clamp,
+                            const void* Q, const void* R_pos, const void* R_neg, float* S, void* stream);
+
+/*
  * Stage timing for benchmarks.  adacluster_profile_enable(1) creates HIP events; while enabled,
  * adacluster_attn, adacluster_sparse_attn and adacluster_dense_attn record them on the call's
  * stream at their stage boundaries.  adacluster_profile_read waits for the last recorded call

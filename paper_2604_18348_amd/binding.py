@@ -100,10 +100,11 @@ def load_library():
     lib.adacluster_attn.argtypes = [P] + [vp] * 4 + [ctypes.POINTER(COutputs), vp, sz, vp]
     lib.adacluster_dense_attn.argtypes = [P] + [vp] * 4 + [vp, sz, vp]
     lib.adacluster_compactness.argtypes = [P] + [vp] * 4 + [vp, sz, vp]
+    lib.adacluster_quest_scores.argtypes = [ctypes.c_int32] * 7 + [vp] * 5
     lib.adacluster_profile_enable.argtypes = [ctypes.c_int]
     lib.adacluster_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float)]
     for n in ("profile_enable", "profile_read", "centroid_capacity", "workspace_bytes", "last_error", "qcluster", "kcluster", "select",
-              "sparse_attn", "attn", "dense_attn", "compactness"):
+              "sparse_attn", "attn", "dense_attn", "compactness", "quest_scores"):
         getattr(lib, "adacluster_" + n).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -112,6 +113,7 @@ def load_library():
 EXPORTED = ["adacluster_centroid_capacity", "adacluster_workspace_bytes", "adacluster_last_error",
             "adacluster_qcluster", "adacluster_kcluster", "adacluster_select",
             "adacluster_sparse_attn", "adacluster_attn", "adacluster_dense_attn", "adacluster_compactness",
+            "adacluster_quest_scores",
             "adacluster_profile_enable", "adacluster_profile_read"]
 
 STAGES = ["qcluster", "kcluster", "select", "permute", "plan", "attention"]
@@ -266,6 +268,24 @@ def adacluster_compactness(p: Params, K, k_labels, k_centroids, ws=None):
         ctypes.byref(cp), _ptr(K), _ptr(k_labels), _ptr(k_centroids), _ptr(mse), _ptr(ws), ws.numel(), _stream()),
         "adacluster_compactness")
     return mse
+
+
+QUEST_ALU, QUEST_MFMA = 0, 1
+
+
+def adacluster_quest_scores(Q, R_pos, R_neg, form, clamp=False, out=None):
+    """Quest scores (Eq. 1 / Eq. 2) of query rows Q [H,Lq,d] against pages with maxima R_pos and minima
+    R_neg [H,Lk,d] -> float32 [H,Lq,Lk]."""
+    H, Lq, d = Q.shape
+    Lk = R_pos.shape[1]
+    assert R_pos.shape == (H, Lk, d) and R_neg.shape == (H, Lk, d)
+    assert Q.dtype == R_pos.dtype == R_neg.dtype and Q.dtype in (torch.float32, torch.bfloat16)
+    assert Q.is_contiguous() and R_pos.is_contiguous() and R_neg.is_contiguous()
+    S = torch.empty((H, Lq, Lk), dtype=torch.float32, device=Q.device) if out is None else out
+    _check(load_library().adacluster_quest_scores(
+        H, Lq, Lk, d, BF16 if Q.dtype == torch.bfloat16 else F32, int(form), 1 if clamp else 0,
+        _ptr(Q), _ptr(R_pos), _ptr(R_neg), _ptr(S), _stream()), "adacluster_quest_scores")
+    return S
 
 
 def alloc_outputs(p: Params, dev, want_box=False, want_stage=True):

@@ -523,6 +523,23 @@ int adacluster_compactness(const adacluster_params* p, const void* K, const int3
   return 0;
 }
 
+int adacluster_quest_scores(int32_t H, int32_t Lq, int32_t Lk, int32_t d, int32_t dtype, int32_t form, int32_t clamp,
+                            const void* Q, const void* R_pos, const void* R_neg, float* S, void* stream) {
+  if (H < 1 || Lq < 1 || Lk < 1) return fail(ADACLUSTER_E_BADSHAPE, "quest_scores: H, Lq and Lk must be >= 1");
+  if (H > 65535) return fail(ADACLUSTER_E_BADSHAPE, "quest_scores: H must be <= 65535");
+  if (d != 64 && d != 128) return fail(ADACLUSTER_E_BADSHAPE, "quest_scores: d must be 64 or 128 (d=%d)", d);
+  if (dtype != ADACLUSTER_F32 && dtype != ADACLUSTER_BF16) return fail(ADACLUSTER_E_BADDTYPE, "quest_scores: unknown dtype %d", dtype);
+  if (form != ADACLUSTER_QUEST_ALU && form != ADACLUSTER_QUEST_MFMA) return fail(ADACLUSTER_E_BADARG, "quest_scores: unknown form %d", form);
+  if (form == ADACLUSTER_QUEST_MFMA && dtype != ADACLUSTER_BF16)
+    return fail(ADACLUSTER_E_UNSUPPORTED, "quest_scores: the matrix-core form takes bf16 inputs");
+  if ((long long)Lq * Lk >= (1ll << 40) || (long long)Lq * d >= (1ll << 40) || (long long)Lk * d >= (1ll << 40))
+    return fail(ADACLUSTER_E_BADSHAPE, "quest_scores: problem too large");
+  if ((Lq + 63) / 64 > 2147483647 / 2 || (Lk + 63) / 64 > 65535) return fail(ADACLUSTER_E_BADSHAPE, "quest_scores: Lk must be <= 4194240");
+  if (!Q || !R_pos || !R_neg || !S) return fail(ADACLUSTER_E_BADARG, "quest_scores: NULL pointer");
+  RET_IF(launch_quest_scores((hipStream_t)stream, dtype, form, clamp ? 1 : 0, H, Lq, Lk, d, Q, R_pos, R_neg, S));
+  return 0;
+}
+
 int adacluster_select(const adacluster_params* p, const float* q_centroids, const float* q_mean_norm,
                       const float* k_centroids, const float* k_box_min, const float* k_box_max,
                       const int32_t* k_sizes, const int32_t* k_count, const int32_t* full_flag,

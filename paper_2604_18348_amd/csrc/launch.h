@@ -66,6 +66,8 @@ int launch_select(hipStream_t s, int H, int Cq, int cap, int d, int score_mode, 
 int attn_block_rows(int dtype, int d);
 int launch_permute_kv(hipStream_t s, int H, int N, int row_bytes, const void* K, const void* V,
                       const int32_t* perm, void* Kp, void* Vp);
+int launch_quest_scores(hipStream_t s, int dtype, int form, int clamp, int H, int Lq, int Lk, int d, const void* Q,
+                        const void* Rp, const void* Rn, float* S);
 int attn_split_slots();      // partial slots per head for the chunks of cut key lists (also extra tile records)
 int launch_plan_sparse(hipStream_t s, int dtype, int H, int Cq, int cap, int maxr, int maxtiles, int BM,
                        const int32_t* q_offs, int q_offs_stride, const int32_t* k_offs, int k_offs_stride,

@@ -81,3 +81,15 @@ def test_null_tensor_and_workspace_errors_launch_nothing(lib):
     buf = ctypes.create_string_buffer(256)
     lib.adacluster_last_error(buf, 256)
     assert b"too small" in buf.value
+
+
+def test_quest_scores_argument_errors_launch_nothing(lib):
+    z, one = ctypes.c_void_p(0), ctypes.c_void_p(256)
+    f = lib.adacluster_quest_scores
+    assert f(1, 8, 8, 64, B.BF16, B.QUEST_MFMA, 0, z, one, one, one, z) == -1          # NULL tensor
+    assert f(0, 8, 8, 64, B.BF16, B.QUEST_ALU, 0, one, one, one, one, z) == -2          # H < 1
+    assert f(1, 8, 0, 64, B.BF16, B.QUEST_ALU, 0, one, one, one, one, z) == -2          # no pages
+    assert f(1, 8, 8, 96, B.BF16, B.QUEST_ALU, 0, one, one, one, one, z) == -2          # head width
+    assert f(1, 8, 8, 64, 9, B.QUEST_ALU, 0, one, one, one, one, z) == -3               # dtype
+    assert f(1, 8, 8, 64, B.BF16, 2, 0, one, one, one, one, z) == -1                    # form
+    assert f(1, 8, 8, 64, B.F32, B.QUEST_MFMA, 0, one, one, one, one, z) == -5          # matrix cores: bf16 only
