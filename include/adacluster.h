@@ -88,6 +88,9 @@ typedef struct adacluster_params {
   int32_t topk;                 /* clusters kept per query cluster (top-k mode), >= 1           */
   float   top_p;                /* mass share (top-p mode), in (0,1]                            */
   float   softmax_scale;        /* <= 0 means 1/sqrt(d)                                         */
+  int32_t q_no_norm;            /* 0 (the paper): queries are clustered by angle, as q/|q|;      */
+                                /* 1: ablation "w/o Norm" (App. component ablation): Euclidean   */
+                                /* k-means on the raw queries, scores from the raw centroids      */
 } adacluster_params;
 
 /* rows of every per-head key-centre buffer: k_max_clusters + k_m0 */

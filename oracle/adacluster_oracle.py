@@ -102,19 +102,37 @@ def _spherical_update(Xn, labels, C_old):
     return C, sizes
 
 
-def query_kmeans(Q, n_clusters, n_iters, init_centroids=None, round_fn=None):
-    """Angle-based clustering of queries.
+def query_kmeans(Q, n_clusters, n_iters, init_centroids=None, round_fn=None, normalize=True):
+    """Clustering of the queries (Sec. 3.1; Alg. 3 line 1: KMeans(Normalize(Q))).
 
-    Points are the unit-normalised queries; label = arg-max cosine to a unit
-    centre; update = re-normalised member sum.  Returns a dict with
+    normalize=True (the method): points are the unit-normalised queries; label =
+    arg-max cosine to a unit centre; update = re-normalised member sum.
+    normalize=False (the "w/o Norm" row of the component ablation): the same Lloyd
+    iterations as `euclid_kmeans` on the raw queries, centres = member means.
+    Returns a dict with
       labels            int64 [N]
-      assign_centroids  [Cq,d]  centres the labels are the arg-max of
-      centroids         [Cq,d]  normalised member means under `labels`
+      assign_centroids  [Cq,d]  centres the labels are the arg-max (arg-min) of
+      centroids         [Cq,d]  normalised member means (member means) under `labels`
       sizes             int64 [Cq]
-      mean_norm         [Cq]    mean ||q|| of the members (0 when empty)
+      mean_norm         [Cq]    mean ||q|| of the members (1 without normalisation; 0 when empty)
     """
     Q = np.asarray(Q, dtype=F64)
     N = Q.shape[0]
+    if not normalize:
+        if init_centroids is None:
+            C = Q[strided_indices(N, n_clusters)].copy()
+        else:
+            C = np.asarray(init_centroids, dtype=F64).copy()
+        labels = None
+        Ca = C
+        for it in range(n_iters):
+            Ca = round_fn(C) if round_fn is not None else C
+            labels = euclid_assign(Q, Ca)
+            if it < n_iters - 1:
+                C, _ = _mean_update(Q, labels, C)
+        cent, sizes = _mean_update(Q, labels, C)
+        return dict(labels=labels.astype(np.int64), assign_centroids=Ca.copy(), centroids=cent,
+                    sizes=sizes.astype(np.int64), mean_norm=(sizes > 0).astype(F64))
     Xn = normalize_rows(Q)
     if init_centroids is None:
         C = Xn[strided_indices(N, n_clusters)].copy()
@@ -534,7 +552,7 @@ def adacluster_attention(Q, K, V, *, q_clusters, q_iters, k_iters, k_m0, k_m_min
                          k_max_clusters, k_max_stages=10, tau_abs=0.0, tau_factor=1.5,
                          min_unassigned_frac=0.0, score_mode=SCORE_TQ, select_mode=0,
                          topk=64, top_p=0.9, softmax_scale=None, round_fn=None,
-                         use_gather=False):
+                         use_gather=False, q_no_norm=0):
     """Q,K,V [H,N,d].  Returns (O [H,N,d], per-head info list, tau)."""
     Q = np.asarray(Q, dtype=F64)
     K = np.asarray(K, dtype=F64)
@@ -548,7 +566,7 @@ def adacluster_attention(Q, K, V, *, q_clusters, q_iters, k_iters, k_m0, k_m_min
     O = np.zeros_like(Q)
     infos = []
     for h in range(H):
-        qc = query_kmeans(Q[h], q_clusters, q_iters, round_fn=round_fn)
+        qc = query_kmeans(Q[h], q_clusters, q_iters, round_fn=round_fn, normalize=not q_no_norm)
         kc = multistage_kmeans(K[h], tau, k_max_clusters, k_m0, k_m_min, k_iters,
                                k_max_stages, min_unassigned_frac, round_fn)
         if kc["full_flag"]:

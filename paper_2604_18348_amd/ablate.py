@@ -8,7 +8,8 @@ PSNR/SSIM of generated videos, which need the models).
 
 Variants: the adaptive call as configured; Eq. 1 scoring on the per-cluster box instead of Alg. 2 on
 centroids; mean-based scoring ("w/o Quest"); a fixed cluster count equal to the mean adaptive count
-("AvgClus": one plain k-means stage); half and twice the top-k.  Prints one JSON line per variant.
+("AvgClus": one plain k-means stage); query clustering without normalisation ("w/o Norm"); half and
+twice the top-k.  Prints one JSON line per variant.
 Runs on the GPU only (there is no CPU path)."""
 import argparse
 import dataclasses
@@ -71,6 +72,7 @@ def main():
     avg = max(1, min(int(round(first["k_clusters_mean"])), base.k_max_clusters))
     run("fixed_count_avgclus", dataclasses.replace(base, k_m0=avg, k_m_min=min(base.k_m_min, avg), k_max_stages=1,
                                                    tau_abs=1e30))
+    run("queries_not_normalised", dataclasses.replace(base, q_no_norm=1))
     if base.select_mode == B.SELECT_TOPK:
         run("topk_half", dataclasses.replace(base, topk=max(1, base.topk // 2)))
         run("topk_double", dataclasses.replace(base, topk=base.topk * 2))

@@ -32,7 +32,7 @@ class CParams(ctypes.Structure):
                 ("tau_factor", ctypes.c_float), ("min_unassigned_frac", ctypes.c_float),
                 ("score_mode", ctypes.c_int32), ("select_mode", ctypes.c_int32),
                 ("topk", ctypes.c_int32), ("top_p", ctypes.c_float),
-                ("softmax_scale", ctypes.c_float)]
+                ("softmax_scale", ctypes.c_float), ("q_no_norm", ctypes.c_int32)]
 
 
 class COutputs(ctypes.Structure):
@@ -66,6 +66,7 @@ class Params:
     topk: int = 64
     top_p: float = 0.9
     softmax_scale: float = 0.0
+    q_no_norm: int = 0
 
     def c(self) -> CParams:
         return CParams(**asdict(self))

@@ -126,6 +126,7 @@ int check_params(const adacluster_params* p) {
   if (p->select_mode < 0 || p->select_mode > 1) return fail(ADACLUSTER_E_BADARG, "unknown select_mode %d", p->select_mode);
   if (p->topk < 1) return fail(ADACLUSTER_E_BADARG, "topk must be >= 1");
   if (!(p->top_p > 0.f) || p->top_p > 1.f) return fail(ADACLUSTER_E_BADARG, "top_p must be in (0,1]");
+  if (p->q_no_norm != 0 && p->q_no_norm != 1) return fail(ADACLUSTER_E_BADARG, "q_no_norm must be 0 or 1");
   return 0;
 }
 
@@ -276,22 +277,23 @@ int run_qcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
   const Dims D = dims_of(p);
   const int P = parts_for(D.N, D.Cq);
   int poff_done = 0;   // set when the sort has already cut the clusters into reduction parts
-  RET_IF(launch_init_centroids(st, p->dtype, D.d, D.H, D.N, 0, D.Cq, D.Cq, nullptr, nullptr, 1, p->q_init_mode,
+  const int sph = p->q_no_norm ? 0 : 1;      // by angle on q/|q| (the paper), or Euclidean on raw queries (ablation)
+  RET_IF(launch_init_centroids(st, p->dtype, D.d, D.H, D.N, 0, D.Cq, D.Cq, nullptr, nullptr, sph, p->q_init_mode,
                                D.Cq, D.Cq, Q, q_centroids, w.q_cent_lp, q_assign, w.q_bias));
   for (int it = 0; it < p->q_iters; ++it) {
     RET_IF(launch_assign(st, p->dtype, D.d, D.H, D.N, D.N, 0, D.Cq, D.Cq, nullptr, nullptr, Q, w.q_cent_lp, w.q_bias,
                          q_labels, nullptr));
     RET_IF(launch_sort(st, D.H, D.N, D.N, D.Cq, q_labels, nullptr, nullptr, 0, nullptr, 0, nullptr, 0, w.perm_q,
                        w.offs_q, D.Cq + 1, w.q_sort, w.q_poff, reduce_part_rows(), &poff_done));
-    RET_IF(launch_seg_reduce(st, p->dtype, D.d, D.H, D.N, 0, D.Cq, D.Cq, P, nullptr, 1, 0, Q, w.perm_q, w.offs_q,
+    RET_IF(launch_seg_reduce(st, p->dtype, D.d, D.H, D.N, 0, D.Cq, D.Cq, P, nullptr, sph, 0, Q, w.perm_q, w.offs_q,
                              D.Cq + 1, w.q_poff, w.q_psum, w.q_pnorm, nullptr, nullptr, poff_done));
     const bool last = it == p->q_iters - 1;
     if (!last) {
-      RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 0, D.Cq, D.Cq, P, D.Cq, D.Cq, nullptr, 1, 1, 0, w.offs_q,
+      RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 0, D.Cq, D.Cq, P, D.Cq, D.Cq, nullptr, sph, 1, 0, w.offs_q,
                              D.Cq + 1, w.q_poff, w.q_psum, w.q_pnorm, nullptr, nullptr, q_centroids, w.q_cent_lp, q_assign, w.q_bias,
                              nullptr, nullptr, nullptr, nullptr, nullptr, nullptr));
     } else {
-      RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 0, D.Cq, D.Cq, P, D.Cq, D.Cq, nullptr, 1, 0, 0, w.offs_q,
+      RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 0, D.Cq, D.Cq, P, D.Cq, D.Cq, nullptr, sph, 0, 0, w.offs_q,
                              D.Cq + 1, w.q_poff, w.q_psum, w.q_pnorm, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
                              q_centroids, nullptr, q_sizes, q_mean_norm, nullptr, nullptr));
     }

@@ -630,7 +630,8 @@ __global__ __launch_bounds__(64) void finalize_centroids(FinalizeCfg cfg, const 
   }
   if (lane == 0) {
     if (out_sizes) out_sizes[(size_t)h * cfg.cap + j] = nj;
-    if (out_mean_norm) out_mean_norm[(size_t)h * cfg.cap + j] = nj > 0 ? ns / (float)nj : 0.f;
+    // mean member norm, the factor that brings unit-centroid scores back to logits; 1 for raw centroids
+    if (out_mean_norm) out_mean_norm[(size_t)h * cfg.cap + j] = nj > 0 ? (cfg.spherical ? ns / (float)nj : 1.f) : 0.f;
   }
 }
 

@@ -62,6 +62,38 @@ def test_qcluster_chained(dtype, d, N, Cq):
             assert math.isclose(mn[h, j], qn[lab[h] == j].mean(), rel_tol=1e-5)
 
 
+@pytest.mark.parametrize("dtype,d,N,Cq", [(B.BF16, 64, 3000, 17), (B.F32, 128, 900, 9)])
+def test_qcluster_without_normalisation_chained(dtype, d, N, Cq):
+    """q_no_norm = 1 (component ablation "w/o Norm"): Euclidean k-means on the raw queries.  Labels are
+    the arg-min to the exported assignment centres, centroids the member means, the norm factor 1."""
+    H = 2
+    Q, _, _ = wl.make_small(13, N, d, 10, dtype=dt_name(dtype), H=H)
+    p = B.Params(H=H, N=N, d=d, dtype=dtype, q_clusters=Cq, q_iters=3, k_m0=4, k_m_min=1, k_max_clusters=8,
+                 q_no_norm=1)
+    out = B.adacluster_qcluster(p, to_dev(Q, dtype))
+    torch.cuda.synchronize()
+    lab = out["q_labels"].cpu().numpy()
+    ca = to_np(out["q_assign_centroids"]).astype(np.float64)
+    cen = to_np(out["q_centroids"])
+    sizes = out["q_sizes"].cpu().numpy()
+    mn = to_np(out["q_mean_norm"])
+    for h in range(H):
+        X = Q[h].astype(np.float64)
+        G = (ca[h] ** 2).sum(1)[None, :] - 2.0 * X @ ca[h].T
+        best = G.min(axis=1)
+        mine = G[np.arange(N), lab[h]]
+        margin = (mine - best) / np.maximum(np.abs(best), 1e-9)
+        assert np.all(margin < 1e-5), float(margin.max())          # exact except near-ties
+        assert (lab[h] != G.argmin(axis=1)).sum() <= max(2, N // 500)
+        assert np.array_equal(sizes[h], np.bincount(lab[h], minlength=Cq))
+        for j in range(Cq):
+            if sizes[h, j] == 0:
+                assert mn[h, j] == 0
+                continue
+            assert np.allclose(cen[h, j], X[lab[h] == j].mean(0), atol=2e-6, rtol=1e-5)
+            assert mn[h, j] == 1.0
+
+
 def test_qcluster_free_running_fp32_matches_oracle_trajectory():
     H, N, d, Cq = 1, 2000, 64, 12
     Q, _, _ = wl.make_small(12, N, d, 12, dtype="f32", H=H)

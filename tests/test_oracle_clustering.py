@@ -131,6 +131,33 @@ def test_query_labels_invariant_under_positive_row_scaling():
     assert np.allclose(a["centroids"], b["centroids"], atol=1e-12)
 
 
+def test_query_kmeans_without_normalisation_is_plain_kmeans_and_feels_the_norms():
+    """Component ablation "w/o Norm": on well-separated blobs with one seed per blob it returns the blob
+    ids and the sample means (textbook k-means); on the wild-norm data above it no longer finds the four
+    directions, which is what normalisation is for."""
+    rng = np.random.default_rng(14)
+    means = 10.0 * rng.standard_normal((5, 6))
+    comp = np.repeat(np.arange(5), 40)
+    Q = means[comp] + 0.1 * rng.standard_normal((200, 6))
+    out = orc.query_kmeans(Q, 5, 3, init_centroids=Q[[0, 40, 80, 120, 160]], normalize=False)
+    assert np.array_equal(out["labels"], comp)
+    for j in range(5):
+        assert np.allclose(out["centroids"][j], Q[comp == j].mean(axis=0), atol=1e-13)
+    assert np.array_equal(out["mean_norm"], np.ones(5))
+    d2 = ((Q[:, None, :] - out["assign_centroids"][None]) ** 2).sum(-1)
+    assert np.array_equal(out["labels"], np.argmin(d2, axis=1))
+    # the same routine as the stage k-means of Algorithm 1
+    lab2, ca2, _ = orc.euclid_kmeans(Q, 5, 3, init_centroids=Q[[0, 40, 80, 120, 160]])
+    assert np.array_equal(out["labels"], lab2) and np.array_equal(out["assign_centroids"], ca2)
+    # wild norms: directions are lost without normalisation
+    rng = np.random.default_rng(4)
+    dirs = np.linalg.qr(rng.standard_normal((8, 8)))[0][:4]
+    comp = np.repeat(np.arange(4), 25)
+    Qw = (dirs[comp] + 0.02 * rng.standard_normal((100, 8))) * rng.uniform(0.1, 20.0, size=(100, 1))
+    raw = orc.query_kmeans(Qw, 4, 3, init_centroids=Qw[[0, 25, 50, 75]], normalize=False)
+    assert not np.array_equal(raw["labels"], comp)
+
+
 def test_zero_query_goes_to_cluster_zero():
     rng = np.random.default_rng(6)
     Q = rng.standard_normal((50, 4))
