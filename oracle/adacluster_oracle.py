@@ -14,10 +14,12 @@ blocking, fusion or reordering.  All arithmetic is IEEE double precision.
 Pins (tests/test_oracle_*.py): brute-force dense softmax attention and its
 closed forms, select-all == dense, argmin / member-mean invariants recomputed
 by explicit loops, the structural invariants of Algorithm 1, Eq. 1 written as
-loops against its GEMM form, brute-force sorting for the selections.
+loops against its GEMM form, brute-force sorting for the selections, and one
+eight-token call of the whole algorithm worked out by hand
+(tests/test_oracle_hand_worked.py).
 The end-to-end numbers of the whole call have no printed example in the paper:
-they are pinned only through those properties ("parity unpinned by a worked
-example").
+they are pinned only through those properties and that hand calculation
+("parity unpinned by a worked example of the paper's").
 
 Conventions used where the paper is silent (each is a stated reading):
   * k-means: deterministic strided initialisation over the current point list,

@@ -180,3 +180,35 @@ def test_two_host_threads_on_one_device():
     assert not errs, errs
     for i in range(2):
         assert torch.equal(got[i], ref[i])
+
+
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+def test_hand_worked_call_on_the_device(dtype):
+    """The eight-token call worked out by hand in tests/test_oracle_hand_worked.py, its two dimensions
+    zero-padded to 64: the device must land on the hand-derived stages, centres, selections and rows."""
+    from tests import test_oracle_hand_worked as hw
+    d = 64
+    pad = lambda X: np.concatenate([X, np.zeros((8, d - 2))], axis=1)[None].astype(np.float32)
+    Q, K, V = pad(hw.Q), pad(hw.K), pad(hw.V)
+    p = B.Params(H=1, N=8, d=d, dtype=dtype, score_mode=0, select_mode=0, **hw.PARAMS)
+    outs = B.alloc_outputs(p, "cuda")
+    O = to_np(B.adacluster_attn(p, to_dev(Q, dtype), to_dev(K, dtype), to_dev(V, dtype), outs=outs))[0]
+    torch.cuda.synchronize()
+    assert int(outs["k_count"][0]) == 3 and not bool(outs["full_flag"][0])
+    assert outs["k_labels"].cpu().numpy()[0].tolist() == [0, 0, 0, 0, 1, 1, 1, 2]
+    assert outs["q_labels"].cpu().numpy()[0].tolist() == [0, 0, 0, 0, 1, 1, 1, 1]
+    assert outs["k_sizes"].cpu().numpy()[0, :3].tolist() == [4, 3, 1]
+    kc = to_np(outs["k_centroids"])[0, :3]
+    assert np.array_equal(kc[:, :2], np.array([[4.5, 1], [-4, 1], [-12, 5]])) and np.all(kc[:, 2:] == 0)
+    qc = to_np(outs["q_centroids"])[0]
+    assert np.allclose(qc[:, :2], [[hw.S2, hw.S2], [-hw.S2, hw.S2]], atol=1e-6) and np.all(qc[:, 2:] == 0)
+    assert np.allclose(to_np(outs["q_mean_norm"])[0], 7.5, atol=1e-5)
+    sel = sel_from_dev(outs["sel_idx"], outs["sel_cnt"])[0]
+    assert [s.tolist() for s in sel] == [[0, 2], [1, 2]]
+    tol = 1e-5 if dtype == B.F32 else 1e-2
+    den0 = 3392 + 2.0 ** -8
+    assert abs(O[0, 0] - 3392 / den0) < tol and abs(O[0, 1] - 2.0 ** -8 / den0) < tol
+    den4 = 1344 + 2.0 ** 28
+    assert abs(O[4, 0] - 100 * 1344 / den4) < tol and abs(O[4, 1] - (100 * 1344 + 2.0 ** 28) / den4) < tol
+    assert np.all(O[:, 2:] == 0)
+    assert np.allclose(O[:4, :2].sum(axis=1), 1.0, atol=tol)
