@@ -363,6 +363,15 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
       kc_bound += m_bound;
     }
     if (t == p->k_max_stages) break;           // the stage head has just closed every head
+    if (t > 0 && p->dtype == ADACLUSTER_BF16 && n_bound <= small_stage_points() && m_bound <= small_stage_centres()) {
+      // few points and few centres left in every head: one launch runs this and every later stage
+      // (|U| and m_t never grow, so the bounds hold for all of them)
+      RET_IF(launch_kstages_small(st, D.d, D.H, D.N, D.cap, p->k_max_clusters, p->k_m0, p->k_m_min, p->k_max_stages,
+                                  u_min, p->k_iters, w.kstate, w.tau, w.ulist[0], w.ulist[1], K, w.cent_lp, k_assign,
+                                  w.bias, k_stage_of));
+      kc_bound += m_bound * (p->k_max_stages - t);
+      break;
+    }
     const int32_t* ul = (t == 0) ? nullptr : w.ulist[t & 1];
     int32_t* ul_next = w.ulist[(t + 1) & 1];
     RET_IF(launch_init_centroids(st, p->dtype, D.d, D.H, D.N, 1, 0, m_bound, w.kstate, ul, 0, 0, D.cap, p->k_m0, K,

@@ -934,6 +934,365 @@ __global__ __launch_bounds__(1024) void filter_small(KState* __restrict__ st, co
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// The late stages of Algorithm 1 in one launch.
+// ------------------------------------------------------------------------------------------
+// Once every head has few unassigned points left (|U| <= SMALL_NU) and at most SMALL_M centres per
+// stage, a stage is eight launches of a few microseconds each with next to no work in them, and
+// Algorithm 1 may run ten such stages.  Heads are independent, so here ONE workgroup per head runs
+// every remaining stage from the loop head to the threshold filter: strided initial sample, `iters`
+// assignment passes with the centre update in between, filter and compaction of U, stage
+// bookkeeping - the same arithmetic as the separate kernels (same scores, same arg-max, same
+// distance, same centre rounding), with the centres, their bias and the member counts in LDS.
+//   assignment: as assign_mfma, D[32 centres x 32 points]; a wave takes every NW-th tile of 32 points and
+//               runs free of the other waves, with the rows of its next tile in flight;
+//   update:     the wave stages its 32 points in LDS and adds S^T[32 dims x 32 centres] += X^T E for
+//               them, E the one-hot labels (see assign_mfma<D, true>), into accumulators it keeps for
+//               the whole pass; the waves' partial sums are then added in a fixed order, so the result
+//               is deterministic;
+//   filter:     squared distances of the last pass stay in LDS; U is compacted in ascending order.
+constexpr int SMALL_NU = 8192;
+constexpr int SMALL_M = 32;
+
+struct SmallStageCfg {
+  int N, cap, n_max, m0, m_min, max_stages, u_min, iters;
+  const float* tau;               // [1] = tau^2
+  int32_t* ulist[2];              // U of stage t is ulist[t & 1]
+  bf16raw* cent_lp; float* assign_f32; float* bias;
+  int32_t* stage_of;              // may be NULL
+};
+
+template <int D> struct SmallStage { static constexpr int NW = D == 64 ? 16 : 8; };   // waves (register budget 128 / 256)
+
+template <int D>
+__global__ __launch_bounds__(SmallStage<D>::NW * 64) void kstages_small(const bf16raw* __restrict__ X, KState* __restrict__ st,
+                                                                       SmallStageCfg cfg) {
+  constexpr int LDW = D + 8, KS = D / 16, DT = D / 32, CPL = D / 64;
+  constexpr int NW = SmallStage<D>::NW, NT = NW * 64;
+  constexpr int SROWB = D * 2 + 16;                  // staged row, padded: the 16-byte pieces of 8 rows fall in 8 bank groups
+  constexpr int JPW = SMALL_M / NW;                  // centres a wave finalises
+  const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = lane & 31, hb = lane >> 5;
+  // a wave's staged tile, row-major; between the tile loop and the next pass the partial centre sums of
+  // GW waves at a time (rows padded by four floats: the float4 pieces of 8 centres fall in 8 bank groups)
+  constexpr int GW = D == 64 ? 8 : 4, PROW = D + 4;
+  __shared__ __attribute__((aligned(16))) char xs[NW][32 * SROWB];
+  static_assert(sizeof(float) * GW * SMALL_M * PROW <= sizeof(char) * NW * 32 * SROWB, "the partial sums reuse the staging area");
+  float* ps = reinterpret_cast<float*>(&xs[0][0]);
+  __shared__ __attribute__((aligned(16))) int32_t lab_s[NW][32];
+  __shared__ __attribute__((aligned(16))) float fs[SMALL_NU];       // squared distances of the last pass
+  __shared__ __attribute__((aligned(16))) bf16raw cs[SMALL_M * LDW];
+  __shared__ __attribute__((aligned(16))) float bs[SMALL_M];
+  __shared__ int32_t cnt_s[SMALL_M];
+  __shared__ int32_t ws[NW];
+  __shared__ KState s_st;
+  if (tid == 0) s_st = st[h];
+  __syncthreads();
+  if (!s_st.active) return;                 // the stage head that ran before this launch closed the head
+  const float t2 = cfg.tau[1];
+  // transpose-read addressing of the X^T operand (see assign_mfma<D, true>)
+  const int i16 = lane & 15;
+  const int vrow = 4 * hb + (i16 >> 2);
+  const int gl = 2 * ((lane >> 4) & 1) + ((i16 & 3) >> 1);
+  const char* xw = xs[wave] + vrow * SROWB + gl * 16 + 8 * (i16 & 1);
+
+  for (bool first = true;; first = false) {
+    if (!first) {
+      // head of the while-loop of Algorithm 1 (as kstage_begin)
+      if (tid == 0) {
+        KState s = s_st;
+        if (s.ucount == 0) s.done = 1;
+        else if (s.ccount >= cfg.n_max) { s.full = 1; s.done = 1; }
+        else if (s.stage >= cfg.max_stages || s.ucount <= cfg.u_min) s.done = 1;
+        s.active = !s.done;
+        if (s.active) {
+          int m = (int)(((long long)cfg.m0 * s.ucount + cfg.N - 1) / cfg.N);
+          m = max(cfg.m_min, min(cfg.m0, m));
+          s.m_t = min(m, s.ucount);
+        } else {
+          s.m_t = 0;
+        }
+        s_st = s;
+      }
+      __syncthreads();
+    }
+    if (!s_st.active) break;
+    const int n = min(s_st.ucount, SMALL_NU), m = min(s_st.m_t, SMALL_M), row_off = s_st.ccount, stage = s_st.stage;
+    const int32_t* uin = cfg.ulist[stage & 1] + (size_t)h * cfg.N;
+    int32_t* uout = cfg.ulist[(stage + 1) & 1] + (size_t)h * cfg.N;
+    const bf16raw* Xh = X + (size_t)h * cfg.N * D;
+
+    // initial centres: strided sample of U (as init_centroids); rows past m are zero with a bias that never wins
+    if (tid < SMALL_M) cnt_s[tid] = 0;
+    for (int j = wave; j < SMALL_M; j += NW) {
+      if (j < m) {
+        const long long pos = ((2ll * j + 1) * (long long)n) / (2ll * m);
+        const int tok = uin[pos];
+        const bf16raw* row = Xh + (size_t)tok * D;
+        float bsum = 0.f;
+#pragma unroll
+        for (int q = 0; q < CPL; ++q) {
+          const int col = lane + 64 * q;
+          const bf16raw r = row[col];
+          const float img = bf16_to_f32(r);
+          cs[j * LDW + col] = r;
+          const size_t ao = ((size_t)h * cfg.cap + row_off + j) * D + col;
+          cfg.cent_lp[ao] = r;          // an empty cluster keeps this centre to the end of the stage
+          cfg.assign_f32[ao] = img;
+          bsum = fmaf(img, img, bsum);
+        }
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) bsum += __shfl_xor(bsum, o);
+        if (lane == 0) { bs[j] = -0.5f * bsum; cfg.bias[(size_t)h * cfg.cap + row_off + j] = -0.5f * bsum; }
+      } else {
+#pragma unroll
+        for (int q = 0; q < CPL; ++q) cs[j * LDW + lane + 64 * q] = 0;
+        if (lane == 0) bs[j] = -3.0e38f;
+      }
+    }
+    __syncthreads();
+
+    const int ntiles = (n + 31) >> 5;
+    // Rows of a tile: every lane loads its 16-byte pieces of point c.  Both loads are unconditional
+    // (positions past the end are clamped to the last point, whose result is then ignored): a load
+    // under a branch would make every later wait a wait for all loads in flight.
+    auto load_tok = [&](int tile) { return uin[min(tile * 32 + c, n - 1)]; };
+    auto load_rows = [&](int tok, bf16x8_t (&x)[KS]) {
+      const bf16raw* row = Xh + (size_t)tok * D + hb * 8;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const uint4 raw = *reinterpret_cast<const uint4*>(row + ks * 16);
+        x[ks] = *reinterpret_cast<const bf16x8_t*>(&raw);
+      }
+    };
+
+    for (int it = 0; it < cfg.iters; ++it) {
+      const bool update = it < cfg.iters - 1;
+      f32x16_t sacc[DT];
+#pragma unroll
+      for (int b = 0; b < DT; ++b)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sacc[b][v] = 0.f;
+      // One tile of 32 points: scores, arg-max, and in an update pass the tile's share of the centre sums.
+      auto process = [&](int tile, const bf16x8_t (&x)[KS]) {
+        const int p = tile * 32 + c;
+        const bool valid = p < n;
+        // scores against every centre, arg-max (as assign_mfma)
+        f32x16_t acc;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float4 b4 = *reinterpret_cast<const float4*>(&bs[8 * i + 4 * hb]);
+          acc[4 * i + 0] = b4.x; acc[4 * i + 1] = b4.y; acc[4 * i + 2] = b4.z; acc[4 * i + 3] = b4.w;
+        }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          const bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(&cs[c * LDW + ks * 16 + hb * 8]);
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, x[ks], acc, 0, 0, 0);
+        }
+        float pk[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) pk[v] = __uint_as_float((__float_as_uint(acc[v]) & 0xFFFFFFF0u) | (uint32_t)(15 - v));
+        float best = fmaxf(fmaxf(pk[0], pk[1]), pk[2]);
+#pragma unroll
+        for (int v = 3; v < 15; v += 2) best = fmaxf(fmaxf(best, pk[v]), pk[v + 1]);
+        best = fmaxf(best, pk[15]);
+        const int v = 15 - (int)(__float_as_uint(best) & 15u);
+        int bidx = 8 * (v >> 2) + 4 * hb + (v & 3);
+        float bv = __uint_as_float(__float_as_uint(best) & 0xFFFFFFF0u);
+        {
+          const float ob = __shfl_xor(bv, 32);
+          const int oi = __shfl_xor(bidx, 32);
+          if (ob > bv || (ob == bv && oi < bidx)) { bv = ob; bidx = oi; }
+        }
+        if (!update) {
+          // last pass: squared distance to the chosen centre, kept for the filter
+          float ss = 0.f;
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) {
+            const uint4 raw = *reinterpret_cast<const uint4*>(&x[ks]);
+            const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const float a = __uint_as_float(w[q] << 16), b = __uint_as_float(w[q] & 0xFFFF0000u);
+              ss = fmaf(a, a, ss); ss = fmaf(b, b, ss);
+            }
+          }
+          const float xn2 = ss + __shfl_xor(ss, 32);
+          if (hb == 0 && valid) fs[p] = fmaxf(xn2 - 2.f * bv, 0.f);
+        } else {
+          // update pass: stage the tile (this wave's own LDS, read back by this wave only), count the
+          // members, add the tile's share of the centre sums
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) *reinterpret_cast<bf16x8_t*>(xs[wave] + c * SROWB + (ks * 16 + hb * 8) * 2) = x[ks];
+          if (hb == 0) {
+            lab_s[wave][c] = valid ? bidx : -1;
+            if (valid) atomicAdd(&cnt_s[bidx], 1);
+          }
+          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+          __builtin_amdgcn_wave_barrier();
+          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+          for (int g = 0; g < 2; ++g) {
+            const int4 l0 = *reinterpret_cast<const int4*>(&lab_s[wave][g * 16 + 4 * hb]);
+            const int4 l1 = *reinterpret_cast<const int4*>(&lab_s[wave][g * 16 + 8 + 4 * hb]);
+            uint4 e;
+            e.x = (l0.x == c ? 0x3F80u : 0u) | (l0.y == c ? 0x3F800000u : 0u);
+            e.y = (l0.z == c ? 0x3F80u : 0u) | (l0.w == c ? 0x3F800000u : 0u);
+            e.z = (l1.x == c ? 0x3F80u : 0u) | (l1.y == c ? 0x3F800000u : 0u);
+            e.w = (l1.z == c ? 0x3F80u : 0u) | (l1.w == c ? 0x3F800000u : 0u);
+#pragma unroll
+            for (int db = 0; db < DT; ++db) {
+              const char* xp = xw + g * 16 * SROWB + db * 64;
+              const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)xp);
+              const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(xp + 8 * SROWB));
+              const s16x4_t both[2] = {lo, hi};
+              sacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t*>(both),
+                                                                 *reinterpret_cast<const bf16x8_t*>(&e), sacc[db], 0, 0, 0);
+            }
+          }
+          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+          __builtin_amdgcn_wave_barrier();      // the next tile overwrites the staged rows
+        }
+      };
+      if constexpr (NW == 16) {
+        // Four waves per SIMD hide the latency of the row loads between them, and 128 registers do not
+        // hold a second row buffer: only the token ids run one tile ahead.
+        bf16x8_t x0[KS];
+        int tk = load_tok(wave);
+        for (int tile = wave; tile < ntiles; tile += NW) {
+          const int tkn = load_tok(tile + NW);
+          load_rows(tk, x0);
+          process(tile, x0);
+          tk = tkn;
+        }
+      } else {
+        // Software pipeline over this wave's tiles, unrolled twice so that the two row buffers keep
+        // their names (a rotating copy would wait for the newest load): rows one tile ahead, token
+        // ids two ahead, each token load issued before the row loads of its step.
+        bf16x8_t x0[KS], x1[KS];
+        int tk = load_tok(wave + NW);
+        load_rows(load_tok(wave), x0);
+        for (int tile = wave; tile < ntiles; tile += 2 * NW) {
+          const int tkn = load_tok(tile + 2 * NW);
+          load_rows(tk, x1);
+          process(tile, x0);
+          if (tile + NW >= ntiles) break;
+          tk = load_tok(tile + 3 * NW);
+          load_rows(tkn, x0);
+          process(tile + NW, x1);
+        }
+      }
+      if (!update) break;
+      // The waves' partial sums, GW at a time through LDS, added in wave order by the thread that
+      // finalises the element: wave w owns centres w, w+NW, ..., a lane the columns lane, lane+64.
+      float tot[JPW][CPL];
+#pragma unroll
+      for (int a = 0; a < JPW; ++a)
+#pragma unroll
+        for (int q = 0; q < CPL; ++q) tot[a][q] = 0.f;
+#pragma unroll
+      for (int grp = 0; grp < NW / GW; ++grp) {
+        __syncthreads();                     // the area is free (first group: every wave is out of its tile loop)
+        if (wave / GW == grp) {
+          // value v of tile db is dim db*32 + 8*(v/4) + 4*hb + v%4 of centre c
+#pragma unroll
+          for (int db = 0; db < DT; ++db) {
+            float* out = ps + ((size_t)((wave % GW) * SMALL_M + c)) * PROW + db * 32 + 4 * hb;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float4 o4 = {sacc[db][4 * i], sacc[db][4 * i + 1], sacc[db][4 * i + 2], sacc[db][4 * i + 3]};
+              *reinterpret_cast<float4*>(out + 8 * i) = o4;
+            }
+          }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int a = 0; a < JPW; ++a) {
+          const int j = wave + NW * a;
+#pragma unroll
+          for (int u = 0; u < GW; ++u)
+#pragma unroll
+            for (int q = 0; q < CPL; ++q) tot[a][q] += ps[((size_t)(u * SMALL_M + j)) * PROW + lane + 64 * q];
+        }
+      }
+      // new centres: member mean, rounded to the I/O type; an empty cluster keeps its centre.  Only the
+      // centres of the stage's last assignment are its result: they alone go to global memory.
+      const bool last_update = it == cfg.iters - 2;
+#pragma unroll
+      for (int a = 0; a < JPW; ++a) {
+        const int j = wave + NW * a;
+        if (j >= m) continue;
+        const int nj = cnt_s[j];
+        if (lane == 0) cnt_s[j] = 0;
+        if (nj > 0) {
+          float bsum = 0.f;
+#pragma unroll
+          for (int q = 0; q < CPL; ++q) {
+            const bf16raw r = f32_to_bf16(tot[a][q] / (float)nj);
+            const float img = bf16_to_f32(r);
+            cs[j * LDW + lane + 64 * q] = r;
+            bsum = fmaf(img, img, bsum);
+          }
+#pragma unroll
+          for (int o = 1; o < 64; o <<= 1) bsum += __shfl_xor(bsum, o);
+          if (lane == 0) bs[j] = -0.5f * bsum;
+        }
+        if (last_update) {
+#pragma unroll
+          for (int q = 0; q < CPL; ++q) {
+            const int col = lane + 64 * q;
+            const bf16raw r = cs[j * LDW + col];          // written by this lane, now or in an earlier pass
+            const size_t ao = ((size_t)h * cfg.cap + row_off + j) * D + col;
+            cfg.cent_lp[ao] = r;
+            cfg.assign_f32[ao] = bf16_to_f32(r);
+          }
+          if (lane == 0) cfg.bias[(size_t)h * cfg.cap + row_off + j] = bs[j];
+        }
+      }
+      __syncthreads();
+    }
+
+    // threshold filter: points with d < tau leave U; U stays ascending (as filter_small)
+    __syncthreads();
+    int run = 0;
+    for (int base = 0; base < n; base += 4 * NT) {
+      const int p0 = base + 4 * tid;
+      bool keep[4]; int tok[4]; int cnt = 0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int p = p0 + i;
+        const bool valid = p < n;
+        keep[i] = valid && !(fs[valid ? p : 0] < t2);
+        tok[i] = valid ? uin[p] : -1;
+        cnt += keep[i] ? 1 : 0;
+      }
+      int incl = cnt;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) { const int v = __shfl_up(incl, o); if (lane >= o) incl += v; }
+      __syncthreads();
+      if (lane == 63) ws[wave] = incl;
+      __syncthreads();
+      int before = 0, total = 0;
+      for (int w = 0; w < NW; ++w) { const int v = ws[w]; if (w < wave) before += v; total += v; }
+      int pos = run + before + incl - cnt;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (keep[i]) uout[pos++] = tok[i];
+        else if (tok[i] >= 0 && cfg.stage_of) cfg.stage_of[(size_t)h * cfg.N + tok[i]] = stage;
+      }
+      run += total;
+    }
+    __syncthreads();          // U of the next stage is written, and nobody reads the state any more
+    if (tid == 0) {
+      s_st.ucount = run;
+      s_st.ccount += m;
+      s_st.stage += 1;
+      s_st.stage_offs[s_st.stage] = s_st.ccount;
+    }
+  }
+  if (tid == 0) st[h] = s_st;
+}
+
 __global__ void fill_i32(int32_t* p, size_t n, int32_t v) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
@@ -1137,6 +1496,21 @@ int launch_filter(hipStream_t s, KState* st, int H, int N, int n_bound, const fl
   filter_scan<<<H, 64, 0, s>>>(st, nb, nblk, blockcnt, u_prev);
   filter_scatter<<<dim3(nb, H), 256, 0, s>>>(st, u_prev, dist2, N, nblk, tau, blockcnt, ulist_in, ulist_out,
                                              stage_of, stage);
+  return chk();
+}
+
+int small_stage_points() { return SMALL_NU; }
+int small_stage_centres() { return SMALL_M; }
+
+int launch_kstages_small(hipStream_t s, int d, int H, int N, int cap, int n_max, int m0, int m_min, int max_stages,
+                         int u_min, int iters, KState* st, const float* tau, int32_t* ulist0, int32_t* ulist1,
+                         const void* X, void* cent_lp, float* assign_f32, float* bias, int32_t* stage_of) {
+  SmallStageCfg cfg;
+  cfg.N = N; cfg.cap = cap; cfg.n_max = n_max; cfg.m0 = m0; cfg.m_min = m_min; cfg.max_stages = max_stages;
+  cfg.u_min = u_min; cfg.iters = iters; cfg.tau = tau; cfg.ulist[0] = ulist0; cfg.ulist[1] = ulist1;
+  cfg.cent_lp = (bf16raw*)cent_lp; cfg.assign_f32 = assign_f32; cfg.bias = bias; cfg.stage_of = stage_of;
+  if (d == 64) kstages_small<64><<<H, SmallStage<64>::NW * 64, 0, s>>>((const bf16raw*)X, st, cfg);
+  else kstages_small<128><<<H, SmallStage<128>::NW * 64, 0, s>>>((const bf16raw*)X, st, cfg);
   return chk();
 }
 

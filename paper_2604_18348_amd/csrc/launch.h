@@ -52,6 +52,14 @@ int launch_tau(hipStream_t s, int H, int N, const float* dist2, double* part, fl
 int launch_filter(hipStream_t s, KState* st, int H, int N, int n_bound, const float* dist2, const float* tau,
                   int32_t* blockcnt, int32_t* u_prev, const int32_t* ulist_in, int32_t* ulist_out,
                   int32_t* stage_of, int stage);
+// Every remaining stage of Algorithm 1 in one launch, one workgroup per head (bf16 only).  Valid once every
+// active head has at most small_stage_points() unassigned points and small_stage_centres() centres per
+// stage, and never for stage 0 (it needs a list of U and a known tau).
+int small_stage_points();
+int small_stage_centres();
+int launch_kstages_small(hipStream_t s, int d, int H, int N, int cap, int n_max, int m0, int m_min, int max_stages,
+                         int u_min, int iters, KState* st, const float* tau, int32_t* ulist0, int32_t* ulist1,
+                         const void* X, void* cent_lp, float* assign_f32, float* bias, int32_t* stage_of);
 int launch_mse(hipStream_t s, int dtype, int d, int H, int N, int cap, const void* X, const int32_t* labels,
                const float* cent, double* part, float* mse);
 int launch_fill_i32(hipStream_t s, int32_t* p, size_t n, int32_t v);
