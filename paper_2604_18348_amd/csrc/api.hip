@@ -412,9 +412,7 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
                          k_stage_of, t));
   }
   if (kc_bound_out) *kc_bound_out = kc_bound < D.cap ? kc_bound : D.cap;
-  RET_IF(launch_kstate_export(st, w.kstate, D.H, k_count, full_flag, k_stage_offs));
-  if (tau_used && hipMemcpyAsync(tau_used, w.tau, 4, hipMemcpyDeviceToDevice, st) != hipSuccess)
-    return fail(ADACLUSTER_E_INTERNAL, "tau copy failed");
+  RET_IF(launch_kstate_export(st, w.kstate, D.H, k_count, full_flag, k_stage_offs, w.tau, tau_used));
   // last step of Algorithm 1: nearest centre among all stage centres, then member statistics
   RET_IF(launch_assign(st, p->dtype, D.d, D.H, D.N, D.N, 2, 0, D.cap, w.kstate, nullptr, K, w.cent_lp, w.bias,
                        k_labels, nullptr));

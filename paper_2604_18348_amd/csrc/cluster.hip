@@ -1298,10 +1298,11 @@ __global__ void fill_i32(int32_t* p, size_t n, int32_t v) {
   if (i < n) p[i] = v;
 }
 
-// k_count, full_flag and stage offsets out of the state
+// k_count, full_flag and stage offsets out of the state; the threshold in use, if asked for
 __global__ void kstate_export(const KState* __restrict__ st, int H, int32_t* k_count, int32_t* full_flag,
-                              int32_t* stage_offs) {
+                              int32_t* stage_offs, const float* __restrict__ tau, float* __restrict__ tau_used) {
   const int h = blockIdx.x * blockDim.x + threadIdx.x;
+  if (h == 0 && tau_used) tau_used[0] = tau[0];
   if (h >= H) return;
   const KState& s = st[h];
   if (k_count) k_count[h] = s.ccount;
@@ -1536,8 +1537,8 @@ int launch_fill_i32(hipStream_t s, int32_t* p, size_t n, int32_t v) {
 }
 
 int launch_kstate_export(hipStream_t s, const KState* st, int H, int32_t* k_count, int32_t* full_flag,
-                         int32_t* stage_offs) {
-  kstate_export<<<(H + 63) / 64, 64, 0, s>>>(st, H, k_count, full_flag, stage_offs);
+                         int32_t* stage_offs, const float* tau, float* tau_used) {
+  kstate_export<<<(H + 63) / 64, 64, 0, s>>>(st, H, k_count, full_flag, stage_offs, tau, tau_used);
   return chk();
 }
 

@@ -64,7 +64,7 @@ int launch_mse(hipStream_t s, int dtype, int d, int H, int N, int cap, const voi
                const float* cent, double* part, float* mse);
 int launch_fill_i32(hipStream_t s, int32_t* p, size_t n, int32_t v);
 int launch_kstate_export(hipStream_t s, const KState* st, int H, int32_t* k_count, int32_t* full_flag,
-                         int32_t* stage_offs);
+                         int32_t* stage_offs, const float* tau = nullptr, float* tau_used = nullptr);
 
 int launch_select(hipStream_t s, int H, int Cq, int cap, int d, int score_mode, int select_mode, int topk,
                   float top_p, float scale, const float* q_cent, const float* q_mean_norm, const float* k_cent,
