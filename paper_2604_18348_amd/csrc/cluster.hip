@@ -193,6 +193,55 @@ __global__ __launch_bounds__(256, (ACC && D == 128) ? 1 : 2) void assign_mfma(co
     const int vrow = 4 * hb + (i16 >> 2);
     const int gl = 2 * (blk & 1) + ((i16 & 3) >> 1);
     const char* xsb = reinterpret_cast<const char*>(xs);
+    if (CT >= 4) {
+      // Many centre tiles: a wave takes whole centre tiles, so that the one-hot operand of a group of
+      // 16 points (twenty vector instructions, more than the product it feeds) is built once and serves
+      // every dim tile and the counting tile.
+      const uint4 ones4 = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+      const bf16x8_t ones = *reinterpret_cast<const bf16x8_t*>(&ones4);
+      for (int ct = wave; ct < CT; ct += 4) {
+        const int cid = ct * 32 + c;
+        f32x16_t sacc[DT + 1];
+#pragma unroll
+        for (int t = 0; t <= DT; ++t)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) sacc[t][v] = 0.f;
+        const int xoff = vrow * ROWB + gl * 16 + 8 * (i16 & 1);
+#pragma unroll 4
+        for (int g = 0; g < 16; ++g) {
+          const int4 l0 = *reinterpret_cast<const int4*>(&lab_s[g * 16 + 4 * hb]);
+          const int4 l1 = *reinterpret_cast<const int4*>(&lab_s[g * 16 + 8 + 4 * hb]);
+          uint4 e;
+          e.x = (l0.x == cid ? 0x3F80u : 0u) | (l0.y == cid ? 0x3F800000u : 0u);
+          e.y = (l0.z == cid ? 0x3F80u : 0u) | (l0.w == cid ? 0x3F800000u : 0u);
+          e.z = (l1.x == cid ? 0x3F80u : 0u) | (l1.y == cid ? 0x3F800000u : 0u);
+          e.w = (l1.z == cid ? 0x3F80u : 0u) | (l1.w == cid ? 0x3F800000u : 0u);
+          const bf16x8_t eb = *reinterpret_cast<const bf16x8_t*>(&e);
+#pragma unroll
+          for (int db = 0; db < DT; ++db) {
+            const char* xp = xsb + g * 16 * ROWB + xoff + db * 64;
+            const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)xp);
+            const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(xp + 8 * ROWB));
+            const s16x4_t both[2] = {lo, hi};
+            sacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t*>(both), eb, sacc[db], 0, 0, 0);
+          }
+          sacc[DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, eb, sacc[DT], 0, 0, 0);
+        }
+        if (cid < m) {
+          if (hb == 0) acc_out.bcnt[((size_t)h * acc_out.nb_stride + b) * ACC_MAXM + cid] = (int)sacc[DT][0];
+#pragma unroll
+          for (int db = 0; db < DT; ++db) {
+            float* out = acc_out.psum + ((size_t)h * acc_out.P + (size_t)cid * acc_out.nb_stride + b) * D + db * 32 + 4 * hb;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float4 o4 = {sacc[db][4 * i], sacc[db][4 * i + 1], sacc[db][4 * i + 2], sacc[db][4 * i + 3]};
+              *reinterpret_cast<float4*>(out + 8 * i) = o4;
+            }
+          }
+        }
+      }
+      return;
+    }
     for (int t = wave; t < CT * (DT + 1); t += 4) {
       const int ct = t / (DT + 1), db = t % (DT + 1);
       const bool counting = db == DT;
