@@ -49,6 +49,7 @@ constexpr int ACC_MAXM = 128;          // most centres the block sums are kept f
 
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4_t;
 typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
+typedef __attribute__((address_space(3))) void lds_void_t;
 
 template <int D, bool ACC>
 __global__ __launch_bounds__(256, (ACC && D == 128) ? 1 : 2) void assign_mfma(const bf16raw* __restrict__ X, AssignCfg cfg,
@@ -56,10 +57,10 @@ __global__ __launch_bounds__(256, (ACC && D == 128) ? 1 : 2) void assign_mfma(co
                                                                 const float* __restrict__ bias,
                                                                 int32_t* __restrict__ labels, float* __restrict__ dist2,
                                                                 AccumOut acc_out) {
-  constexpr int CB = D == 128 ? 64 : 128;   // centres per LDS chunk (about 17 KB either way; larger chunks measured slower)
-  constexpr int LDW = D + 8;            // padded row (bf16 elements): conflict-free 16-byte reads
+  constexpr int CB = D == 128 ? 64 : 128;   // centres per LDS chunk (16 KB either way; larger chunks measured slower)
   constexpr int KS = D / 16;
   constexpr int PB = 2;                 // 32-point blocks per wave
+  constexpr int CROWB = D * 2, CH = D / 8;  // bytes and 16-byte pieces of a centre row
   const int h = blockIdx.y;
   int n, m, row_off;
   if (!assign_setup(cfg, h, n, m, row_off)) return;
@@ -68,8 +69,16 @@ __global__ __launch_bounds__(256, (ACC && D == 128) ? 1 : 2) void assign_mfma(co
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c = lane & 31, hb = lane >> 5;
 
-  __shared__ __attribute__((aligned(16))) bf16raw cs[CB * LDW];
-  __shared__ __attribute__((aligned(16))) float bs[CB];
+  // Centre chunks go global -> LDS directly (no registers), one chunk ahead, in two buffers that are LDS
+  // objects of their own (the compiler orders an LDS read behind an outstanding direct load only when
+  // both may touch the same object, so the load of chunk i+1 runs under the arithmetic of chunk i).
+  // Rows are unpadded; piece g of row r sits in slot g ^ swz(r), which keeps the 16-byte operand
+  // reads of 16 consecutive rows in 16 different bank groups.
+  __shared__ __attribute__((aligned(16))) char cs0[CB * CROWB];
+  __shared__ __attribute__((aligned(16))) char cs1[CB * CROWB];
+  __shared__ __attribute__((aligned(16))) float bs0[CB];
+  __shared__ __attribute__((aligned(16))) float bs1[CB];
+  auto swz = [](int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); };
 
   // B operand: this lane's point rows
   bf16x8_t xf[PB][KS];
@@ -110,18 +119,25 @@ __global__ __launch_bounds__(256, (ACC && D == 128) ? 1 : 2) void assign_mfma(co
   const bf16raw* ch = cent + ((size_t)h * cfg.cap + row_off) * D;
   const float* bh = bias + (size_t)h * cfg.cap + row_off;
 
-  for (int c0 = 0; c0 < m; c0 += CB) {
-    __syncthreads();
-    // stage CB centre rows (zero rows and -inf bias beyond m)
-    constexpr int CHUNKS = D / 8;                      // 16-byte chunks per row
-    for (int i = tid; i < CB * CHUNKS; i += 256) {
-      const int r = i / CHUNKS, q = i % CHUNKS;
-      uint4 v = {0, 0, 0, 0};
-      if (c0 + r < m) v = *reinterpret_cast<const uint4*>(ch + (size_t)(c0 + r) * D + q * 8);
-      *reinterpret_cast<uint4*>(&cs[r * LDW + q * 8]) = v;
+  // operand addresses inside a chunk (bytes), fixed for the whole kernel
+  int kaddr[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) kaddr[ks] = c * CROWB + (((ks * 2 + hb) ^ swz(c)) * 16);
+  // thread -> (row, slot) of its pieces of a chunk; rows past m repeat the last centre (their bias never wins)
+  constexpr int PT = CB * CH / 256;
+  auto issue_chunk = [&](int c0, char* dst_base) {
+#pragma unroll
+    for (int i = 0; i < PT; ++i) {
+      const int item = tid + i * 256;
+      const int r = item / CH, sl = item % CH;
+      const int row = min(c0 + r, m - 1);
+      const char* src = reinterpret_cast<const char*>(ch) + (size_t)row * CROWB + ((sl ^ swz(r)) * 16);
+      const int dst = (wave * 64 + i * 256) * 16;     // wave-uniform; the lane offset is implicit
+      __builtin_amdgcn_global_load_lds(src, (lds_void_t*)(dst_base + dst), 16, 0, 0);
     }
-    if (tid < CB) bs[tid] = (c0 + tid < m) ? bh[c0 + tid] : -3.0e38f;   // finite: survives the bit packing
-    __syncthreads();
+  };
+  auto load_bias = [&](int c0) { return (tid < CB && c0 + tid < m) ? bh[c0 + tid] : -3.0e38f; };   // finite: survives the bit packing
+  auto compute_chunk = [&](int c0, const char* cs, const float* bs) {
     const int rbmax = min(CB / 32, (m - c0 + 31) / 32);
     for (int rb = 0; rb < rbmax; ++rb) {
       f32x16_t acc[PB];
@@ -136,7 +152,7 @@ __global__ __launch_bounds__(256, (ACC && D == 128) ? 1 : 2) void assign_mfma(co
       }
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(&cs[(rb * 32 + c) * LDW + ks * 16 + hb * 8]);
+        const bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(cs + rb * 32 * CROWB + kaddr[ks]);
 #pragma unroll
         for (int pb = 0; pb < PB; ++pb)
           acc[pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xf[pb][ks], acc[pb], 0, 0, 0);
@@ -154,6 +170,27 @@ __global__ __launch_bounds__(256, (ACC && D == 128) ? 1 : 2) void assign_mfma(co
         if (tm > best[pb]) { best[pb] = tm; btile[pb] = tile_id; }
       }
     }
+  };
+  // one step: request the next chunk, work on this one, then let the request land
+  auto step = [&](int c0, const char* cs, const float* bs, char* csn, float* bsn) {
+    const bool more = c0 + CB < m;
+    float bnext = 0.f;
+    if (more) { bnext = load_bias(c0 + CB); issue_chunk(c0 + CB, csn); }
+    compute_chunk(c0, cs, bs);
+    if (more && tid < CB) bsn[tid] = bnext;
+    __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's pieces of the next chunk are in LDS
+    __syncthreads();
+  };
+  {
+    const float b0 = load_bias(0);
+    issue_chunk(0, cs0);
+    if (tid < CB) bs0[tid] = b0;
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+  }
+  for (int c0 = 0; c0 < m; c0 += 2 * CB) {
+    step(c0, cs0, bs0, cs1, bs1);
+    if (c0 + CB < m) step(c0 + CB, cs1, bs1, cs0, bs0);
   }
   int blab[PB];
 #pragma unroll
