@@ -278,8 +278,9 @@ def test_kcluster_bf16_stage_centres_follow_the_oracle_trajectory(d, N, tau):
     assert bool(out["full_flag"][0]) == ref["full_flag"]
 
 
-@pytest.mark.parametrize("d,N,tau", [(64, 7000, 2.2), (128, 5000, 3.3)])
-def test_kcluster_many_late_stages_in_one_launch(d, N, tau):
+@pytest.mark.parametrize("d,N,tau,iters", [(64, 7000, 2.2, 3), (128, 5000, 3.3, 3), (64, 7000, 2.2, 1),
+                                          (128, 5000, 3.3, 2)])
+def test_kcluster_many_late_stages_in_one_launch(d, N, tau, iters):
     """A tight threshold leaves thousands of points unassigned stage after stage: from the second stage
     on, one workgroup per head runs all the remaining stages in a single launch.  One more or one less
     point in U moves every strided initial sample of the next stage, so a free-running comparison over
@@ -289,7 +290,7 @@ def test_kcluster_many_late_stages_in_one_launch(d, N, tau):
     H = 3
     _, K, _ = wl.make_small(29, N, d, 14, dtype="bf16", H=H)
     K[1] = wl.round_bf16_f32(0.05 * K[1])                       # everything within tau of a first-stage centre
-    p = B.Params(H=H, N=N, d=d, dtype=B.BF16, q_clusters=4, k_iters=3, k_m0=30, k_m_min=6, k_max_clusters=300,
+    p = B.Params(H=H, N=N, d=d, dtype=B.BF16, q_clusters=4, k_iters=iters, k_m0=30, k_m_min=6, k_max_clusters=300,
                  k_max_stages=8, tau_abs=tau)
     out = B.adacluster_kcluster(p, to_dev(K, B.BF16))
     torch.cuda.synchronize()
@@ -298,12 +299,18 @@ def test_kcluster_many_late_stages_in_one_launch(d, N, tau):
     offs = out["k_stage_offs"].cpu().numpy()
     stage_of = out["k_stage_of"].cpu().numpy()
     assert kc[1] == 30 and offs[1, 1] == 30 and offs[1, 2] == 30
+    if iters == 1:
+        # a single pass assigns to the strided sample itself: the stage centres are rows of K
+        for h in (0, 2):
+            U = np.flatnonzero(stage_of[h] != 0)
+            pos = orc.strided_indices(U.size, offs[h, 2] - offs[h, 1])
+            assert np.array_equal(to_np(out["k_assign_centroids"])[h, offs[h, 1]:offs[h, 2]], K[h][U[pos]])
     for h in (0, 2):
         assert np.all(np.diff(offs[h][:9]) > 0) and not bool(out["full_flag"][h])      # eight stages ran
         for t in range(1, 8):
             U = np.flatnonzero((stage_of[h] >= t) | (stage_of[h] == -1))
             assert 1000 < U.size <= 8192 and offs[h, t + 1] - offs[h, t] <= 32
-        check_stages_against_oracle(K[h], out, h, 8, 3, tau)
+        check_stages_against_oracle(K[h], out, h, 8, iters, tau)
 
 
 def check_stages_against_oracle(Kh, out, h, n_stages, iters, tau):
