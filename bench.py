@@ -3,7 +3,8 @@
 
 A step is one adacluster_attn call (query clustering, Algorithm 1, selection, permutation,
 block-sparse attention) over one synthetic Q/K/V batch of the chosen configuration, inputs
-resident in HBM.  Prints ONE JSON line (see the design doc for every field).
+resident in HBM.  Prints ONE JSON line: the call's latency, its stage times, the dense call beside
+it, the attention kernel against the bf16 MFMA peak, and the CPU oracle timed on the host.
 """
 import argparse
 import json
@@ -105,8 +106,8 @@ def main():
     ap.add_argument("--no-dense", action="store_true")
     a = ap.parse_args()
     if a.gpus != 1:
-        print("bench.py: this build runs on one GPU only (heads shard without communication; "
-              "see DESIGN.md); --gpus must be 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (heads would shard over GPUs without any "
+              "communication, but nothing here launches a second one); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
