@@ -1,8 +1,9 @@
 """Measured variants of the clustered sparse-attention call (the paper's ablations, Sec. 4.3 and
 App. A.5, restated on synthetic inputs): for each variant the time of a call, the executed density,
-the mean key-cluster count, the per-layer compactness score (Sec. 3.2.1) and the error of the output
-against dense attention computed by the same library (relative L2 and max-abs; the paper reports
-PSNR/SSIM of generated videos, which need the models).
+the mean key-cluster count, the per-layer compactness score (Sec. 3.2.1), the share of the dense soft-max
+mass that the selection keeps (sampled queries) and the error of the output against dense attention
+computed by the same library (relative L2 and max-abs; the paper reports PSNR/SSIM of generated videos,
+which need the models).
 
     python -m paper_2604_18348_amd.ablate --config c2
 
@@ -18,6 +19,28 @@ import sys
 import time
 
 import numpy as np
+
+
+def attention_mass_kept(torch, Q, K, outs, p, scale, per_head=128, seed=0):
+    """Share of the dense soft-max mass that falls on the selected keys, averaged over `per_head` sampled
+    queries of every head: what a selection keeps of the attention it approximates, whatever V holds.
+    Evaluation only (plain torch on the device; not part of the call)."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    H, N, _ = Q.shape
+    cap = outs["sel_idx"].shape[2]
+    tot = 0.0
+    for h in range(H):
+        idx = torch.randperm(N, generator=g)[:min(per_head, N)].to(Q.device)
+        logits = (Q[h, idx].float() @ K[h].float().T) * scale
+        P = torch.softmax(logits, dim=1)
+        cnt = outs["sel_cnt"][h].long()                                       # [Cq]
+        pos = torch.arange(cap, device=Q.device)[None, :] < cnt[:, None]      # valid entries of sel_idx
+        mask = torch.zeros((p.q_clusters, cap + 1), dtype=torch.bool, device=Q.device)
+        mask.scatter_(1, torch.where(pos, outs["sel_idx"][h].long(), torch.full_like(pos, cap, dtype=torch.long)), True)
+        allowed = mask[:, :cap][outs["q_labels"][h, idx].long()][:, outs["k_labels"][h].long()]   # [S, N]
+        tot += float((P * allowed).sum(dim=1).mean())
+    return tot / H
 
 
 def main():
@@ -37,6 +60,7 @@ def main():
     dtype = B.BF16 if cfg["dtype"] == "bf16" else B.F32
     base = B.Params(H=H, N=N, d=d, dtype=dtype, **cfg["params"])
 
+    scale = base.softmax_scale if base.softmax_scale > 0 else 1.0 / float(d) ** 0.5
     dense = B.adacluster_dense_attn(base, Q, K, V).float()
     torch.cuda.synchronize()
     dense_norm = float(torch.linalg.vector_norm(dense))
@@ -61,6 +85,7 @@ def main():
                "k_clusters_mean": float(outs["k_count"].float().mean()),
                "heads_full_attention": int(outs["full_flag"].sum()),
                "compactness": float(1.0 / np.mean(mse)),
+               "attention_mass_kept": attention_mass_kept(torch, Q, K, outs, p, scale),
                "rel_l2_vs_dense": float(torch.linalg.vector_norm(diff)) / dense_norm,
                "max_abs_vs_dense": float(diff.abs().max())}
         print(json.dumps(rec), flush=True)

@@ -212,3 +212,35 @@ def test_hand_worked_call_on_the_device(dtype):
     assert abs(O[4, 0] - 100 * 1344 / den4) < tol and abs(O[4, 1] - (100 * 1344 + 2.0 ** 28) / den4) < tol
     assert np.all(O[:, 2:] == 0)
     assert np.allclose(O[:4, :2].sum(axis=1), 1.0, atol=tol)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_concentrated_attention_is_kept_by_a_small_selection(d):
+    """What the method is for: when a query's soft-max mass sits on the keys of a few clusters (here the
+    query means are the key means of the same component, scaled up), the centroid scores must find them:
+    a selection of 4 clusters out of about 30 keeps nearly all of the dense soft-max mass, and the output is
+    close to dense attention although three quarters of the keys are skipped."""
+    from paper_2604_18348_amd.ablate import attention_mass_kept
+    H, N, M = 2, 3000, 24
+    rng = np.random.default_rng(77)
+    comp = rng.integers(0, M, (H, N))
+    mu = rng.standard_normal((H, M, d)).astype(np.float32)
+    K = wl.round_bf16_f32(np.take_along_axis(mu, comp[..., None], 1) + 0.2 * rng.standard_normal((H, N, d)).astype(np.float32))
+    Q = wl.round_bf16_f32(2.0 * np.take_along_axis(mu, comp[..., None], 1) + 0.2 * rng.standard_normal((H, N, d)).astype(np.float32))
+    V = wl.round_bf16_f32(rng.standard_normal((H, N, d)).astype(np.float32))
+    p = B.Params(H=H, N=N, d=d, dtype=B.BF16, q_clusters=24, q_iters=3, k_iters=3, k_m0=24, k_m_min=4,
+                 k_max_clusters=96, tau_factor=1.5, min_unassigned_frac=0.03, topk=4)
+    outs = B.alloc_outputs(p, "cuda")
+    Qd, Kd, Vd = to_dev(Q, B.BF16), to_dev(K, B.BF16), to_dev(V, B.BF16)
+    O = B.adacluster_attn(p, Qd, Kd, Vd, outs=outs)
+    dense = B.adacluster_dense_attn(p, Qd, Kd, Vd)
+    torch.cuda.synchronize()
+    assert int(outs["full_flag"].sum()) == 0
+    qs, ks = outs["q_sizes"].cpu().numpy().astype(np.int64), outs["k_sizes"].cpu().numpy().astype(np.int64)
+    sel = sel_from_dev(outs["sel_idx"], outs["sel_cnt"])
+    pairs = sum(int(qs[h, i]) * int(ks[h, sel[h][i]].sum()) for h in range(H) for i in range(p.q_clusters))
+    density = pairs / (H * float(N) * float(N))
+    mass = attention_mass_kept(torch, Qd, Kd, outs, p, 1.0 / np.sqrt(d), per_head=256)
+    rel = float(torch.linalg.vector_norm(O.float() - dense.float()) / torch.linalg.vector_norm(dense.float()))
+    print("density", density, "mass kept", mass, "rel-L2 vs dense", rel, "k_count", outs["k_count"].cpu().tolist())
+    assert density < 0.3 and mass > 0.97 and rel < 0.1
