@@ -363,6 +363,19 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
       kc_bound += m_bound;
     }
     if (t == p->k_max_stages) break;           // the stage head has just closed every head
+    if (t == 1 && !(p->dtype == ADACLUSTER_BF16 && (n_bound + 255) / 256 <= STAGE_SUM_BLOCKS &&
+                    m_bound <= assign_block_sum_centres())) {
+      // Stage 0 removes most points, so its figures (all N points, m_0 centres) are poor bounds for
+      // stage 1: unless they still allow the short update (block sums), they would send a few thousand
+      // points through the launch chain sized for all of them (two radix passes, segmented
+      // reduction).  Then, once per call, the host waits for the report of the stage it is about to
+      // enqueue; the other stream keeps the device busy meanwhile.
+      if (hipEventSynchronize(rb->ev[1]) != hipSuccess)
+        return fail(ADACLUSTER_E_INTERNAL, "stage read-back failed: %s", hipGetErrorString(hipGetLastError()));
+      const int32_t* cur = rb->host + 4;
+      if (cur[0] == 0) break;                  // no head needs a second stage
+      n_bound = cur[1]; m_bound = cur[2];
+    }
     if (t > 0 && p->dtype == ADACLUSTER_BF16 && n_bound <= small_stage_points() && m_bound <= small_stage_centres()) {
       // few points and few centres left in every head: one launch runs this and every later stage
       // (|U| and m_t never grow, so the bounds hold for all of them)
