@@ -25,12 +25,14 @@ __device__ double exp_det(double x) {
   if (x < -700.0) return 0.0;
   const double k = rint(x * 1.4426950408889634);
   const double r = (x - k * 0.693147180369123816490) - k * 1.90821492927058770002e-10;
-  double fact = 6227020800.0;          // 13!
-  double p = 1.0 / fact;
-  for (int n = 12; n >= 0; --n) {
-    fact = fact / (double)(n + 1);     // n!
-    p = p * r + 1.0 / fact;
-  }
+  // 1/n!, each the correctly rounded quotient of 1 and the (exact) double n!; folded at compile time,
+  // which rounds as the device would
+  constexpr double c[14] = {1.0 / 1.0, 1.0 / 1.0, 1.0 / 2.0, 1.0 / 6.0, 1.0 / 24.0, 1.0 / 120.0, 1.0 / 720.0,
+                            1.0 / 5040.0, 1.0 / 40320.0, 1.0 / 362880.0, 1.0 / 3628800.0, 1.0 / 39916800.0,
+                            1.0 / 479001600.0, 1.0 / 6227020800.0};
+  double p = c[13];
+#pragma unroll
+  for (int n = 12; n >= 0; --n) p = p * r + c[n];
   return ldexp(p, (int)k);
 }
 
@@ -61,6 +63,7 @@ __global__ __launch_bounds__(256) void select_kernel(SelectCfg cfg, const float*
   __shared__ int32_t s_take, s_digit, s_krem, s_all;
   __shared__ int32_t hist[256];
   __shared__ double s_max;
+  __shared__ double swmax[4];
 
   const int h = blockIdx.y, i = blockIdx.x, tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -109,24 +112,37 @@ __global__ __launch_bounds__(256) void select_kernel(SelectCfg cfg, const float*
       const float4* rpos = reinterpret_cast<const float4*>((box ? k_bmax : k_cent) + ((size_t)h * cfg.cap + j) * d);
       const float4* rneg = reinterpret_cast<const float4*>((box ? k_bmin : k_cent) + ((size_t)h * cfg.cap + j) * d);
       double sp = 0.0, sn = 0.0;
-      for (int t4 = 0; t4 < d / 4; ++t4) {
-        const float4 p4 = rpos[t4];
-        const float4 n4 = box ? rneg[t4] : p4;
-        const float pv[4] = {p4.x, p4.y, p4.z, p4.w}, nv[4] = {n4.x, n4.y, n4.z, n4.w};
+      // 64 dimensions per step: the sixteen 16-byte loads of a step are in flight together (the rows come
+      // from L2 or further away, and the wait for them is most of this loop), the chain of adds runs on
+      // registers (d is 64 or 128)
+      for (int t64 = 0; t64 < d / 64; ++t64) {
+        float4 pb[16], nb[16];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          // The sign of q is the same for the whole workgroup.  The term of the other sign is an exact
-          // zero, and adding a zero leaves a running sum as it is, so only one of the two is formed
-          // (fp64 conversions, min/max, multiplies and adds are what this kernel spends its time on).
-          const double q = qrow[4 * t4 + u];
-          const int t = 4 * t4 + u;
-          const bool qpos_ = !(((t < 64 ? neg0 : neg1) >> (t & 63)) & 1ull);
-          if (qpos_) {
-            const float kp = box ? pv[u] : fmaxf(pv[u], 0.f);
-            sp = sp + q * (double)kp;
-          } else {
-            const float kn = box ? nv[u] : fminf(nv[u], 0.f);
-            sn = sn + q * (double)kn;
+        for (int u4 = 0; u4 < 16; ++u4) pb[u4] = rpos[t64 * 16 + u4];
+        if (box) {
+#pragma unroll
+          for (int u4 = 0; u4 < 16; ++u4) nb[u4] = rneg[t64 * 16 + u4];
+        } else {
+#pragma unroll
+          for (int u4 = 0; u4 < 16; ++u4) nb[u4] = pb[u4];
+        }
+#pragma unroll
+        for (int u4 = 0; u4 < 16; ++u4) {
+          const float pv[4] = {pb[u4].x, pb[u4].y, pb[u4].z, pb[u4].w}, nv[4] = {nb[u4].x, nb[u4].y, nb[u4].z, nb[u4].w};
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            // The sign of q is the same for the whole workgroup.  The term of the other sign is an exact
+            // zero, and adding a zero leaves a running sum as it is, so only one of the two is formed.
+            const int t = 64 * t64 + 4 * u4 + u;
+            const double q = qrow[t];
+            const bool qpos_ = !(((t64 == 0 ? neg0 : neg1) >> (t & 63)) & 1ull);
+            if (qpos_) {
+              const float kp = box ? pv[u] : fmaxf(pv[u], 0.f);
+              sp = sp + q * (double)kp;
+            } else {
+              const float kn = box ? nv[u] : fminf(nv[u], 0.f);
+              sn = sn + q * (double)kn;
+            }
           }
         }
       }
@@ -193,12 +209,17 @@ __global__ __launch_bounds__(256) void select_kernel(SelectCfg cfg, const float*
   } else {
     // weights w_j = n_j exp(alpha (S_j - max S)); order by (w desc, j asc); shortest prefix
     // whose running sum reaches top_p * total
-    if (tid == 0) {
-      double mx = -INFINITY;
-      for (int j = 0; j < kc; ++j) mx = fmax(mx, sval[j]);
-      s_max = mx;
+    {
+      // the maximum does not depend on the order it is taken in
+      double m = -INFINITY;
+      for (int j = tid; j < kc; j += 256) m = fmax(m, sval[j]);
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) m = fmax(m, __shfl_xor(m, o));
+      if (lane == 0) swmax[wave] = m;
+      __syncthreads();
+      if (tid == 0) s_max = fmax(fmax(swmax[0], swmax[1]), fmax(swmax[2], swmax[3]));
+      __syncthreads();
     }
-    __syncthreads();
     const double alpha = (double)q_mean_norm[(size_t)h * cfg.Cq + i] * cfg.scale;
     const double mx = s_max;
     for (int j = tid; j < kc; j += 256) {
@@ -213,42 +234,72 @@ __global__ __launch_bounds__(256) void select_kernel(SelectCfg cfg, const float*
     }
     __syncthreads();
     // rank of every valid cluster, stored in place of the flag: sflag = rank+1, 0 = invalid
-    for (int j = tid; j < kc; j += 256) {
-      if (!sflag[j]) continue;
-      const uint64_t kj = skey[j];
-      int rank = 0;
+    // (a thread ranks its clusters two at a time, so that a key read serves both)
+    for (int j = tid; j < kc; j += 512) {
+      const int j2 = j + 256;
+      const bool v1 = sflag[j] != 0, v2 = j2 < kc && sflag[j2] != 0;
+      const uint64_t k1 = skey[j], k2 = j2 < kc ? skey[j2] : 0ull;
+      int r1 = 0, r2 = 0;
       for (int t = 0; t < kc; ++t) {
         const uint64_t kt = skey[t];
-        rank += (kt > kj) || (kt == kj && t < j);
+        r1 += (kt > k1) || (kt == k1 && t < j);
+        r2 += (kt > k2) || (kt == k2 && t < j2);
       }
-      sflag[j] = rank + 1;
+      if (v1) sflag[j] = r1 + 1;
+      if (v2) sflag[j2] = r2 + 1;
     }
     __syncthreads();
-    // inverse permutation into skey (as ints), then the sequential prefix by one thread
-    int32_t* order = reinterpret_cast<int32_t*>(skey);
-    __syncthreads();
-    int nvalid_local = 0;
-    for (int j = tid; j < kc; j += 256) if (sflag[j]) ++nvalid_local;
-    // (skey is dead after the ranks are known; every thread finished reading it at the barrier)
-    for (int j = tid; j < kc; j += 256) if (sflag[j]) order[sflag[j] - 1] = j;
+    // The weights in rank order go into skey (dead once the ranks are known), then one thread takes
+    // the two sums, each a chain of rounded adds in a fixed order: the total in ascending index, the
+    // running sum in rank order.  It reads eight values at a time, so that the LDS reads of a batch
+    // are in flight together and only the adds wait for one another.
+    double* sw = reinterpret_cast<double*>(skey);
+    int nv_local = 0;
+    for (int j = tid; j < kc; j += 256) nv_local += sflag[j] != 0;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) nv_local += __shfl_xor(nv_local, o);
+    if (lane == 0) wsum[wave] = nv_local;
+    __syncthreads();                // every thread has read its keys: skey may be overwritten
+    for (int j = tid; j < kc; j += 256) if (sflag[j]) sw[sflag[j] - 1] = sval[j];
     __syncthreads();
     if (tid == 0) {
-      int nvalid = 0;
+      const int nvalid = wsum[0] + wsum[1] + wsum[2] + wsum[3];
       double total = 0.0;
-      for (int j = 0; j < kc; ++j) { total = total + sval[j]; nvalid += sflag[j] != 0; }
+      int j = 0;
+      for (; j + 8 <= kc; j += 8) {
+        double v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = sval[j + u];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) total = total + v[u];
+      }
+      for (; j < kc; ++j) total = total + sval[j];
       const double target = cfg.top_p * total;
       double cum = 0.0;
       int take = nvalid;
-      for (int r = 0; r < nvalid; ++r) {
-        cum = cum + sval[order[r]];
-        if (cum >= target) { take = r + 1; break; }
+      bool found = false;
+      int r = 0;
+      for (; r + 8 <= nvalid && !found; r += 8) {
+        double v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = sw[r + u];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          if (!found) {
+            cum = cum + v[u];
+            if (cum >= target) { take = r + u + 1; found = true; }
+          }
+        }
+      }
+      for (; r < nvalid && !found; ++r) {
+        cum = cum + sw[r];
+        if (cum >= target) { take = r + 1; found = true; }
       }
       s_take = take;
     }
     __syncthreads();
     const int take = s_take;
     for (int j = tid; j < kc; j += 256) sflag[j] = sflag[j] != 0 && sflag[j] <= take;
-    (void)nvalid_local;
   }
   __syncthreads();
 
