@@ -26,7 +26,7 @@ FP32_VALU_PEAK_TFLOPS = 157.3
 # reads for a plain copy of known size) + WRITE_SIZE of the two rocprofv3 --pmc passes summarised in
 # profiles/attn_pipeline_<config>.txt.  A counter cannot be read from inside this script, so the
 # figures are stored; a config without a profile reports null.
-PROFILED_ATTN_TRAFFIC_BYTES = {"c2": 699.8e6, "c3": 289.5e6, "c4": 2676.6e6, "c5": 4326.7e6}
+PROFILED_ATTN_TRAFFIC_BYTES = {"c2": 707.7e6, "c3": 289.0e6, "c4": 2670.6e6, "c5": 4324.2e6}
 
 
 def gen_inputs(name, torch, B, wl):
