@@ -26,7 +26,8 @@
  *     the calling thread once per clustering stage on an event, to read a few
  *     integers back through pinned host memory the library keeps per thread (the
  *     stage loop of Algorithm 1 has a data-dependent trip count; the host runs one
- *     stage behind the device, so the stream is not drained).
+ *     stage behind the device, so the stream is not drained, except once, before the
+ *     second stage, when the first stage's sizes would be a poor bound for it).
  *   - Every function returns 0 on success or a negative ADACLUSTER_E_* code.  On
  *     an argument error nothing is launched.  adacluster_last_error() returns a
  *     message for the calling thread's last failure.  No function throws, aborts
