@@ -64,3 +64,28 @@ def test_random_configuration(seed):
             assert rel < 1e-2 and mx < 2e-2, (rel, mx)
         else:
             assert mx < 1e-4, (rel, mx)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_key_clustering_keeps_the_structure_of_algorithm_1(seed):
+    """Seeded random sizes, centre counts, pass counts, stage limits and thresholds of the key clustering
+    alone (bf16), with a noisier first head half of the time: stage counts follow the rule, removals agree
+    with the reported centres and the threshold, labels are the arg-min, member statistics match."""
+    from tests.test_gpu_cluster import check_kcluster
+    r = np.random.default_rng(7000 + seed)
+    d = int(r.choice([64, 128]))
+    N = int(r.choice([900, 2500, 6000, 9000, 14000]))
+    H = int(r.integers(1, 4))
+    m0 = int(r.choice([8, 24, 32, 60, 100, 128, 200]))
+    m_min = int(min(m0, r.choice([1, 4, 16, 30])))
+    p = B.Params(H=H, N=N, d=d, dtype=B.BF16, q_clusters=4, k_iters=int(r.integers(1, 4)), k_m0=m0, k_m_min=m_min,
+                 k_max_clusters=int(r.choice([m0, 3 * m0, 10 * m0])), k_max_stages=int(r.integers(1, 9)),
+                 tau_factor=float(r.choice([0.7, 0.9, 1.2, 1.5])),
+                 min_unassigned_frac=float(r.choice([0.0, 0.02, 0.2])))
+    _, K, _ = wl.make_small(9000 + seed, N, d, int(r.choice([6, 20, 60])), dtype="bf16", H=H)
+    if r.integers(0, 2):
+        K[0] = wl.round_bf16_f32(K[0] + float(r.choice([0.3, 1.0])) * r.standard_normal((N, d)).astype(np.float32))
+    print("case", seed, "H", H, "N", N, "d", d, p, flush=True)
+    out = B.adacluster_kcluster(p, to_dev(K, B.BF16))
+    torch.cuda.synchronize()
+    check_kcluster(K, p, out, B.BF16)
