@@ -34,7 +34,11 @@ __global__ __launch_bounds__(64) void radix_count(const int32_t* __restrict__ la
   if (beg < n) {
     const int end = min(beg + SEG, n);
     const int32_t* lab = labels + (size_t)h * N;
-    for (int p = beg + lane; p < end; p += 64) atomicAdd(&cnt[(lab[p] >> shift) & (RBINS - 1)], 1);
+    int lv[SEG / 64];
+#pragma unroll
+    for (int k = 0; k < SEG / 64; ++k) { const int p = beg + 64 * k + lane; lv[k] = p < end ? lab[p] : -1; }
+#pragma unroll
+    for (int k = 0; k < SEG / 64; ++k) if (lv[k] >= 0) atomicAdd(&cnt[(lv[k] >> shift) & (RBINS - 1)], 1);
   }
   __syncthreads();
   int32_t* out = hist + ((size_t)h * nseg + seg) * RBINS;
@@ -83,11 +87,21 @@ __global__ __launch_bounds__(64) void radix_scatter(const int32_t* __restrict__ 
   int32_t* lo = labels_out + (size_t)h * N;
   int32_t* vo = vals_out + (size_t)h * N;
   const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-  for (int p0 = beg; p0 < end; p0 += 64) {
-    const int p = p0 + lane;
+  // the segment's items, all loads in flight at once (a load per step of the loop below would leave
+  // the wave waiting on memory eight times over)
+  int lv[SEG / 64], vv[SEG / 64];
+#pragma unroll
+  for (int k = 0; k < SEG / 64; ++k) {
+    const int p = beg + 64 * k + lane;
+    lv[k] = p < end ? lab[p] : 0;
+    vv[k] = p < end ? (val ? val[p] : p) : 0;
+  }
+#pragma unroll
+  for (int k = 0; k < SEG / 64; ++k) {
+    const int p = beg + 64 * k + lane;
     const bool valid = p < end;
-    const int l = valid ? lab[p] : 0;
-    const int v = valid ? (val ? val[p] : p) : 0;
+    const int l = lv[k];
+    const int v = vv[k];
     const int dig = (l >> shift) & (RBINS - 1);
     // lanes holding my digit: intersect, bit by bit, the ballots of lanes that agree with me
     uint64_t same = __ballot(valid);
