@@ -244,3 +244,26 @@ def test_concentrated_attention_is_kept_by_a_small_selection(d):
     rel = float(torch.linalg.vector_norm(O.float() - dense.float()) / torch.linalg.vector_norm(dense.float()))
     print("density", density, "mass kept", mass, "rel-L2 vs dense", rel, "k_count", outs["k_count"].cpu().tolist())
     assert density < 0.3 and mass > 0.97 and rel < 0.1
+
+
+def test_many_heads():
+    """More heads than any benchmark configuration has (the per-head kernels take one workgroup per head,
+    the attention grid deals heads to XCDs eight at a time with a remainder): a few heads checked the
+    chained way, every head's selection checked against the oracle's."""
+    H, N, d = 70, 640, 64
+    Q, K, V = wl.make_small(91, N, d, 8, dtype="bf16", H=H)
+    p = B.Params(H=H, N=N, d=d, dtype=B.BF16, q_clusters=5, q_iters=2, k_iters=2, k_m0=8, k_m_min=2,
+                 k_max_clusters=40, min_unassigned_frac=0.02, topk=3)
+    outs = B.alloc_outputs(p, "cuda")
+    O = to_np(B.adacluster_attn(p, to_dev(Q, B.BF16), to_dev(K, B.BF16), to_dev(V, B.BF16), outs=outs))
+    torch.cuda.synchronize()
+    sel_gpu = sel_from_dev(outs["sel_idx"], outs["sel_cnt"])
+    ql, kl = outs["q_labels"].cpu().numpy(), outs["k_labels"].cpu().numpy()
+    for h in range(H):
+        sel_ref = oracle_selection_from_gpu_centroids(outs, p, h)
+        for i in range(p.q_clusters):
+            assert np.array_equal(sel_gpu[h][i], sel_ref[i]), (h, i)
+    for h in (0, 7, 8, 33, 63, 64, 69):
+        ref = orc.sparse_attention_gather(Q[h], K[h], V[h], ql[h], kl[h], sel_gpu[h])
+        rel, mx = attn_errors(O[h], ref)
+        assert rel < 1e-2 and mx < 2e-2, (h, rel, mx)
