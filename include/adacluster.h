@@ -217,6 +217,19 @@ int adacluster_compactness(const adacluster_params* p, const void* K, const int3
                            const float* k_centroids, float* k_mse, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * adacluster_compactness for callers that cannot allocate device memory or size a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the workspace,
+ * same kernels, same result bit for bit.  The per-block partial sums go to a 512 KiB array that is part of the
+ * library's device image (every GPU the library runs on holds its copy until the process ends); nothing is
+ * allocated or freed by the call.  Limit: H * ceil(N / 1024) <= 65536 partial sums, else
+ * ADACLUSTER_E_UNSUPPORTED and nothing is launched.  All calls on one GPU share that array: calls that
+ * overlap in time on one GPU (different streams or threads) race and must be serialised by the caller.
+ * Asynchronous on `stream`.
+ */
+int adacluster_compactness_noalloc(const adacluster_params* p, const void* K, const int32_t* k_labels,
+                                   const float* k_centroids, float* k_mse, void* stream);
+
+/*
  * Quest scores of query rows against key pages (Sec. 3.2.3), in either of the two forms whose speed the
  * paper compares (Sec. 4.3, "TensorQuest reformulation benefits"):
  *   form ADACLUSTER_QUEST_ALU   Eq. 1 as written, S[h,i,j] = sum_d max(q_d R+_jd, q_d R-_jd), fp32 vector

@@ -101,11 +101,12 @@ def load_library():
     lib.adacluster_attn.argtypes = [P] + [vp] * 4 + [ctypes.POINTER(COutputs), vp, sz, vp]
     lib.adacluster_dense_attn.argtypes = [P] + [vp] * 4 + [vp, sz, vp]
     lib.adacluster_compactness.argtypes = [P] + [vp] * 4 + [vp, sz, vp]
+    lib.adacluster_compactness_noalloc.argtypes = [P] + [vp] * 4 + [vp]
     lib.adacluster_quest_scores.argtypes = [ctypes.c_int32] * 7 + [vp] * 5
     lib.adacluster_profile_enable.argtypes = [ctypes.c_int]
     lib.adacluster_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float)]
     for n in ("profile_enable", "profile_read", "centroid_capacity", "workspace_bytes", "last_error", "qcluster", "kcluster", "select",
-              "sparse_attn", "attn", "dense_attn", "compactness", "quest_scores"):
+              "sparse_attn", "attn", "dense_attn", "compactness", "compactness_noalloc", "quest_scores"):
         getattr(lib, "adacluster_" + n).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -114,7 +115,7 @@ def load_library():
 EXPORTED = ["adacluster_centroid_capacity", "adacluster_workspace_bytes", "adacluster_last_error",
             "adacluster_qcluster", "adacluster_kcluster", "adacluster_select",
             "adacluster_sparse_attn", "adacluster_attn", "adacluster_dense_attn", "adacluster_compactness",
-            "adacluster_quest_scores",
+            "adacluster_compactness_noalloc", "adacluster_quest_scores",
             "adacluster_profile_enable", "adacluster_profile_read"]
 
 STAGES = ["qcluster", "kcluster", "select", "permute", "plan", "attention"]
@@ -268,6 +269,17 @@ def adacluster_compactness(p: Params, K, k_labels, k_centroids, ws=None):
     _check(load_library().adacluster_compactness(
         ctypes.byref(cp), _ptr(K), _ptr(k_labels), _ptr(k_centroids), _ptr(mse), _ptr(ws), ws.numel(), _stream()),
         "adacluster_compactness")
+    return mse
+
+
+def adacluster_compactness_noalloc(p: Params, K, k_labels, k_centroids, out=None):
+    """adacluster_compactness without a workspace: partial sums in the library's own device array.  `out`
+    lets the caller pass the [H] float32 result tensor, so that the call itself allocates nothing."""
+    mse = torch.empty((p.H,), dtype=torch.float32, device=K.device) if out is None else out
+    cp = p.c()
+    _check(load_library().adacluster_compactness_noalloc(
+        ctypes.byref(cp), _ptr(K), _ptr(k_labels), _ptr(k_centroids), _ptr(mse), _stream()),
+        "adacluster_compactness_noalloc")
     return mse
 
 

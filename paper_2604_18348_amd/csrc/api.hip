@@ -8,7 +8,16 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
+
 using namespace adac;
+
+// Scratch memory that belongs to the library, for the one entry point that takes no workspace
+// (adacluster_compactness_noalloc).  Every GPU the library runs on holds its own copy of the array until
+// the process ends.  In host code the name is only a handle for hipGetSymbolAddress: kernels get the
+// address that call returns for the current device, never the name.
+constexpr size_t STATIC_SCRATCH_DOUBLES = 65536;                 // 512 KiB
+static __device__ __align__(256) double scratch[STATIC_SCRATCH_DOUBLES];
 
 namespace {
 
@@ -92,6 +101,23 @@ AuxStream* aux_stream() {
     a.ready = true;
   }
   return &a;
+}
+
+int fail(int code, const char* fmt, ...);
+
+// Device address of `scratch` on the current device, looked up once per device.
+std::mutex g_scratch_mu;
+double* g_scratch_ptr[64] = {};
+double* static_scratch() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+    g_scratch_ptr[dev] = (double*)ptr;
+  }
+  return g_scratch_ptr[dev];
 }
 
 int fail(int code, const char* fmt, ...) {
@@ -542,6 +568,22 @@ int adacluster_compactness(const adacluster_params* p, const void* K, const int3
   if ((rc = check_ws(p, ws, ws_bytes, &w))) return rc;
   RET_IF(launch_mse((hipStream_t)stream, p->dtype, p->d, p->H, p->N, capacity(p), K, k_labels, k_centroids, w.tau_part,
                     k_mse));
+  return 0;
+}
+
+int adacluster_compactness_noalloc(const adacluster_params* p, const void* K, const int32_t* k_labels,
+                                   const float* k_centroids, float* k_mse, void* stream) {
+  int rc = check_params(p);
+  if (rc) return rc;
+  if (!K || !k_labels || !k_centroids || !k_mse) return fail(ADACLUSTER_E_BADARG, "compactness_noalloc: NULL pointer");
+  const size_t need = (size_t)p->H * (size_t)((p->N + 1023) / 1024);   // one partial sum per head and 1024 rows
+  if (need > STATIC_SCRATCH_DOUBLES)
+    return fail(ADACLUSTER_E_UNSUPPORTED, "compactness_noalloc: H * ceil(N/1024) = %zu exceeds the %zu partial sums of the "
+                "library's scratch array; use adacluster_compactness with a workspace", need, STATIC_SCRATCH_DOUBLES);
+  double* part = static_scratch();
+  if (!part) return fail(ADACLUSTER_E_INTERNAL, "compactness_noalloc: hipGetSymbolAddress failed: %s", hipGetErrorString(hipGetLastError()));
+  // every partial sum the second kernel reads is written by the first: nothing has to start at zero
+  RET_IF(launch_mse((hipStream_t)stream, p->dtype, p->d, p->H, p->N, capacity(p), K, k_labels, k_centroids, part, k_mse));
   return 0;
 }
 
