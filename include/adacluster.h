@@ -199,6 +199,30 @@ int adacluster_attn(const adacluster_params* p,
                     const adacluster_outputs* outs /* host struct of device pointers, may be NULL */,
                     void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * Per-head figures of the last adacluster_attn call on a workspace (diagnostics; Alg. 1's stage loop and the
+ * executed share of the score matrix that Alg. 3 lines 8-10 leave).  adacluster_stats_fetch must follow that
+ * call with the same params and workspace, before any other call touches the workspace: it reduces what the
+ * call left there with one small kernel on `stream`, copies H records to host_stats (HOST pointer) and waits
+ * for `stream`.  After adacluster_kcluster alone the first five fields are valid, after adacluster_sparse_attn
+ * alone the last three.
+ */
+typedef struct adacluster_head_stats {
+  int32_t k_count;        /* |C|: key centres Algorithm 1 ended with                                   */
+  int32_t full_flag;      /* F                                                                         */
+  int32_t stages;         /* stages of Algorithm 1 that ran (1 for a warm start)                       */
+  int32_t q_tiles;        /* workgroups of the attention launch (query tiles, cut key lists counted per chunk) */
+  int32_t unassigned[ADACLUSTER_MAX_STAGES + 1]; /* |U| at the head of stage t for t < stages; entry
+                             [stages] = keys still beyond tau of every centre when staging stopped      */
+  int32_t reserved;
+  int64_t executed_pairs; /* sum over query clusters i of n_q(i) * sum_{j in sel(i)} n_k(j)            */
+  int64_t issued_pairs;   /* the same with the rows of every query tile rounded up to whole 32-query
+                             waves and its keys to whole 64-key tiles: what the matrix cores are fed    */
+} adacluster_head_stats;
+
+int adacluster_stats_fetch(const adacluster_params* p, void* ws, size_t ws_bytes,
+                           adacluster_head_stats* host_stats /* host, [H] */, void* stream);
+
 /* Dense softmax attention on the same attention kernel (the F = True branch of Alg. 3 and the
  * timing baseline): every query attends to every key. */
 int adacluster_dense_attn(const adacluster_params* p,
@@ -252,15 +276,24 @@ int adacluster_quest_scores(int32_t H, int32_t Lq, int32_t Lk, int32_t d, int32_
 /*
  * Stage timing for benchmarks.  adacluster_profile_enable(1) creates HIP events; while enabled,
  * adacluster_attn, adacluster_sparse_attn and adacluster_dense_attn record them on the call's
- * stream at their stage boundaries.  adacluster_profile_read waits for the last recorded call
- * and writes, to the HOST array ms[6], the milliseconds of: query clustering, Algorithm 1,
- * selection (stand-alone sparse_attn: the two label sorts), K/V permutation, planning, and the
- * attention kernel; -1 for a stage the call did not run.  In adacluster_attn the two clusterings
+ * stream at their stage boundaries (adacluster_qcluster and adacluster_kcluster record their own).
+ * adacluster_profile_read waits for the last recorded call
+ * and writes, to the HOST array ms[7], the milliseconds of: query clustering, Algorithm 1,
+ * selection (stand-alone sparse_attn: the two label sorts), K/V permutation, planning, the
+ * attention kernel, and the segmented reduction over all N keys that ends Algorithm 1 (one launch,
+ * also counted inside Algorithm 1); -1 for a stage the call did not run.  In adacluster_attn the two clusterings
  * run side by side and each is timed from the start of the call, so their sum exceeds the time
  * the pair takes; the K/V permutation is timed from the final key sort, after which it runs on the
  * second stream beside the tail of Algorithm 1, the selection and the planning.  Not thread-safe.
  */
 int adacluster_profile_enable(int on);
+
+/*
+ * Matrix-core yardstick for benchmarks: a register-only loop of bf16 MFMAs (v_mfma_f32_32x32x16_bf16, four
+ * independent chains per wave, `iters` trips) on every SIMD of the chip, enqueued on `stream`.  *flops (HOST)
+ * receives the floating-point operations of the launch; the caller times it.  sink: DEVICE, >= 256 floats.
+ */
+int adacluster_mfma_probe(int32_t iters, float* sink, size_t sink_floats, double* flops, void* stream);
 int adacluster_profile_read(float* ms);
 
 #ifdef __cplusplus

@@ -47,15 +47,17 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--config", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--aligned", action="store_true",
+                    help="queries drawn around the key mean of their component: concentrated attention")
     a = ap.parse_args()
 
     import torch
-    import bench
+    from . import harness
     from paper_2604_18348_amd import binding as B
     from paper_2604_18348_amd import workloads as wl
     B.load_library()
     torch.cuda.set_device(0)
-    cfg, Q, K, V = bench.gen_inputs(a.config, torch, B, wl)
+    cfg, Q, K, V = harness.device_inputs(a.config, aligned=a.aligned)
     H, N, d = Q.shape
     dtype = B.BF16 if cfg["dtype"] == "bf16" else B.F32
     base = B.Params(H=H, N=N, d=d, dtype=dtype, **cfg["params"])
@@ -77,10 +79,10 @@ def main():
             B.adacluster_attn(p, Q, K, V, outs=outs, out=O, ws=ws)
         torch.cuda.synchronize()
         ms = (time.perf_counter() - t0) * 1e3 / a.steps
-        pairs = bench.executed_pairs(outs, p)
+        pairs = harness.executed_pairs(outs, p)
         mse = B.adacluster_compactness(p, K, outs["k_labels"], outs["k_centroids"], ws=ws).cpu().numpy()
         diff = O.float() - dense
-        rec = {"variant": name, "config": a.config, "ms_per_call": ms,
+        rec = {"variant": name, "config": a.config, "aligned": bool(a.aligned), "ms_per_call": ms,
                "density": pairs / (H * float(N) * float(N)),
                "k_clusters_mean": float(outs["k_count"].float().mean()),
                "heads_full_attention": int(outs["full_flag"].sum()),

@@ -43,6 +43,12 @@ class COutputs(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in _names]
 
 
+class CHeadStats(ctypes.Structure):
+    _fields_ = [("k_count", ctypes.c_int32), ("full_flag", ctypes.c_int32), ("stages", ctypes.c_int32),
+                ("q_tiles", ctypes.c_int32), ("unassigned", ctypes.c_int32 * (MAX_STAGES + 1)),
+                ("reserved", ctypes.c_int32), ("executed_pairs", ctypes.c_int64), ("issued_pairs", ctypes.c_int64)]
+
+
 @dataclass
 class Params:
     H: int
@@ -102,11 +108,13 @@ def load_library():
     lib.adacluster_dense_attn.argtypes = [P] + [vp] * 4 + [vp, sz, vp]
     lib.adacluster_compactness.argtypes = [P] + [vp] * 4 + [vp, sz, vp]
     lib.adacluster_compactness_noalloc.argtypes = [P] + [vp] * 4 + [vp]
+    lib.adacluster_mfma_probe.argtypes = [ctypes.c_int32, vp, sz, ctypes.POINTER(ctypes.c_double), vp]
+    lib.adacluster_stats_fetch.argtypes = [P, vp, sz, ctypes.POINTER(CHeadStats), vp]
     lib.adacluster_quest_scores.argtypes = [ctypes.c_int32] * 7 + [vp] * 5
     lib.adacluster_profile_enable.argtypes = [ctypes.c_int]
     lib.adacluster_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float)]
     for n in ("profile_enable", "profile_read", "centroid_capacity", "workspace_bytes", "last_error", "qcluster", "kcluster", "select",
-              "sparse_attn", "attn", "dense_attn", "compactness", "compactness_noalloc", "quest_scores"):
+              "sparse_attn", "attn", "dense_attn", "compactness", "compactness_noalloc", "quest_scores", "stats_fetch", "mfma_probe"):
         getattr(lib, "adacluster_" + n).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -115,10 +123,10 @@ def load_library():
 EXPORTED = ["adacluster_centroid_capacity", "adacluster_workspace_bytes", "adacluster_last_error",
             "adacluster_qcluster", "adacluster_kcluster", "adacluster_select",
             "adacluster_sparse_attn", "adacluster_attn", "adacluster_dense_attn", "adacluster_compactness",
-            "adacluster_compactness_noalloc", "adacluster_quest_scores",
+            "adacluster_compactness_noalloc", "adacluster_quest_scores", "adacluster_stats_fetch", "adacluster_mfma_probe",
             "adacluster_profile_enable", "adacluster_profile_read"]
 
-STAGES = ["qcluster", "kcluster", "select", "permute", "plan", "attention"]
+STAGES = ["qcluster", "kcluster", "select", "permute", "plan", "attention", "kreduce"]
 
 
 def adacluster_profile_enable(on: bool):
@@ -127,7 +135,7 @@ def adacluster_profile_enable(on: bool):
 
 def adacluster_profile_read():
     """Stage times (ms) of the last profiled call as a dict; stages that did not run are absent."""
-    arr = (ctypes.c_float * 6)()
+    arr = (ctypes.c_float * len(STAGES))()
     _check(load_library().adacluster_profile_read(arr), "profile_read")
     return {n: float(arr[i]) for i, n in enumerate(STAGES) if arr[i] >= 0}
 
@@ -281,6 +289,25 @@ def adacluster_compactness_noalloc(p: Params, K, k_labels, k_centroids, out=None
         ctypes.byref(cp), _ptr(K), _ptr(k_labels), _ptr(k_centroids), _ptr(mse), _stream()),
         "adacluster_compactness_noalloc")
     return mse
+
+
+def adacluster_stats_fetch(p: Params, ws):
+    """Per-head figures of the last adacluster_attn call on `ws` -> list of dicts (waits for the stream)."""
+    arr = (CHeadStats * p.H)()
+    cp = p.c()
+    _check(load_library().adacluster_stats_fetch(ctypes.byref(cp), _ptr(ws), ws.numel(), arr, _stream()),
+           "adacluster_stats_fetch")
+    return [dict(k_count=r.k_count, full_flag=r.full_flag, stages=r.stages, q_tiles=r.q_tiles,
+                 unassigned=list(r.unassigned), executed_pairs=r.executed_pairs, issued_pairs=r.issued_pairs)
+            for r in arr]
+
+
+def adacluster_mfma_probe(iters: int, sink):
+    """Enqueues the register-only MFMA loop on the current stream; returns the flops of the launch."""
+    fl = ctypes.c_double(0.0)
+    _check(load_library().adacluster_mfma_probe(int(iters), _ptr(sink), sink.numel(), ctypes.byref(fl), _stream()),
+           "adacluster_mfma_probe")
+    return fl.value
 
 
 QUEST_ALU, QUEST_MFMA = 0, 1

@@ -57,16 +57,18 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--config", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--dense-fraction", type=float, default=0.15)
+    ap.add_argument("--aligned", action="store_true",
+                    help="queries drawn around the key mean of their component: concentrated attention")
     a = ap.parse_args()
 
     import dataclasses
     import torch
-    import bench
+    from . import harness
     from paper_2604_18348_amd import binding as B
     from paper_2604_18348_amd import workloads as wl
     B.load_library()
     torch.cuda.set_device(0)
-    cfg, Q, K, V = bench.gen_inputs(a.config, torch, B, wl)
+    cfg, Q, K, V = harness.device_inputs(a.config, aligned=a.aligned)
     H, N, d = K.shape
     dtype = B.BF16 if cfg["dtype"] == "bf16" else B.F32
     base = B.Params(H=H, N=N, d=d, dtype=dtype, **cfg["params"])

@@ -26,7 +26,7 @@ thread_local char g_err[256] = "";
 // Optional stage timing: hipEvents recorded at the stage boundaries of a call.  A stage is timed
 // from the event in from[] (default: the previous recorded stage boundary); the fused call runs
 // the two clusterings side by side, so both of those are timed from the start of the call.
-enum { EV_START = 0, EV_QCLUSTER, EV_KCLUSTER, EV_SELECT, EV_PERMUTE, EV_PLAN, EV_ATTN, EV_STAGES,
+enum { EV_START = 0, EV_QCLUSTER, EV_KCLUSTER, EV_SELECT, EV_PERMUTE, EV_PLAN, EV_ATTN, EV_KREDUCE, EV_STAGES,
        EV_JOIN = EV_STAGES, EV_JOIN2, EV_KSORT, EV_COUNT };
 struct Profiler {
   bool enabled = false;
@@ -187,6 +187,7 @@ struct WS {
   int32_t* k_labels; float* k_centroids; float* k_assign; float* k_bmin; float* k_bmax;
   int32_t* k_sizes; int32_t* k_count; int32_t* full_flag; int32_t* sel_idx; int32_t* sel_cnt;
   int32_t* one_count;   // [H] constant key-cluster count for the dense plan
+  adacluster_head_stats* stats;   // [H] staging area of adacluster_stats_fetch
 };
 
 struct Dims {
@@ -281,6 +282,7 @@ size_t layout(const adacluster_params* p, WS* w, unsigned char* base) {
   TAKE(sel_idx, int32_t*, H * (size_t)D.Cq * D.cap * 4);
   TAKE(sel_cnt, int32_t*, H * (size_t)D.Cq * 4);
   TAKE(one_count, int32_t*, H * 4);
+  TAKE(stats, adacluster_head_stats*, H * sizeof(adacluster_head_stats));
 #undef TAKE
   if (w) w->base = base;
   return L.total;
@@ -459,14 +461,13 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
   RET_IF(launch_sort(st, D.H, D.N, D.N, D.cap, k_labels, nullptr, nullptr, 0, &w.kstate->ccount, sizeof(KState) / 4,
                      nullptr, 0, w.perm_k, w.offs_k, D.cap + 1, w.sort, w.poff, reduce_part_rows(), &poff_done));
   // the key permutation is final here: work that needs nothing else of the clustering may start
-  if (sorted_ev) {
-    if (hipEventRecord(sorted_ev, st) != hipSuccess) return fail(ADACLUSTER_E_INTERNAL, "stream fork failed");
-    prof_mark(EV_KSORT, st);
-  }
+  if (sorted_ev && hipEventRecord(sorted_ev, st) != hipSuccess) return fail(ADACLUSTER_E_INTERNAL, "stream fork failed");
+  prof_mark(EV_KSORT, st);
   const int want_box = (k_bmin && k_bmax) ? 1 : 0;
   const int P = parts_for(D.N, D.cap);
   RET_IF(launch_seg_reduce(st, p->dtype, D.d, D.H, D.N, 2, 0, D.cap, P, w.kstate, 0, want_box, K, w.perm_k, w.offs_k,
                            D.cap + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax, poff_done));
+  prof_mark(EV_KREDUCE, st, EV_KSORT);
   RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 2, 0, D.cap, P, D.cap, D.cap, w.kstate, 0, 0, want_box, w.offs_k,
                          D.cap + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax, nullptr, nullptr, nullptr, nullptr, k_centroids,
                          k_assign, k_sizes, nullptr, k_bmin, k_bmax));
@@ -540,7 +541,10 @@ int adacluster_qcluster(const adacluster_params* p, const void* Q, int32_t* q_la
     return fail(ADACLUSTER_E_BADARG, "qcluster: NULL tensor pointer");
   WS w;
   if ((rc = check_ws(p, ws, ws_bytes, &w))) return rc;
-  return run_qcluster(p, w, (hipStream_t)stream, Q, q_labels, q_centroids, q_assign_centroids, q_sizes, q_mean_norm);
+  prof_begin((hipStream_t)stream);
+  rc = run_qcluster(p, w, (hipStream_t)stream, Q, q_labels, q_centroids, q_assign_centroids, q_sizes, q_mean_norm);
+  prof_mark(EV_QCLUSTER, (hipStream_t)stream, EV_START);
+  return rc;
 }
 
 int adacluster_kcluster(const adacluster_params* p, const void* K, int32_t* k_labels, float* k_centroids,
@@ -555,8 +559,11 @@ int adacluster_kcluster(const adacluster_params* p, const void* K, int32_t* k_la
     return fail(ADACLUSTER_E_BADARG, "kcluster: pass both boxes or neither");
   WS w;
   if ((rc = check_ws(p, ws, ws_bytes, &w))) return rc;
-  return run_kcluster(p, w, (hipStream_t)stream, K, k_labels, k_centroids, k_assign_centroids, k_box_min, k_box_max,
-                      k_sizes, k_count, full_flag, k_stage_offs, k_stage_of, tau_used, nullptr);
+  prof_begin((hipStream_t)stream);
+  rc = run_kcluster(p, w, (hipStream_t)stream, K, k_labels, k_centroids, k_assign_centroids, k_box_min, k_box_max,
+                    k_sizes, k_count, full_flag, k_stage_offs, k_stage_of, tau_used, nullptr);
+  prof_mark(EV_KCLUSTER, (hipStream_t)stream, EV_START);
+  return rc;
 }
 
 int adacluster_compactness(const adacluster_params* p, const void* K, const int32_t* k_labels,
@@ -731,6 +738,28 @@ int adacluster_dense_attn(const adacluster_params* p, const void* Q, const void*
   RET_IF(launch_attention(st, p->dtype, D.d, D.H, D.N, 1, D.maxtiles, 1, scale, Q, K, V, O, nullptr, w.tiles,
                           w.ntiles, w.rng_start, w.rng_pre, w.rng_cnt, nullptr, nullptr, nullptr, nullptr));
   prof_mark(EV_ATTN, st);
+  return 0;
+}
+
+int adacluster_stats_fetch(const adacluster_params* p, void* ws, size_t ws_bytes, adacluster_head_stats* host_stats,
+                           void* stream) {
+  int rc = check_params(p);
+  if (rc) return rc;
+  if (!host_stats) return fail(ADACLUSTER_E_BADARG, "stats_fetch: host_stats is NULL");
+  WS w;
+  if ((rc = check_ws(p, ws, ws_bytes, &w))) return rc;
+  const Dims D = dims_of(p);
+  hipStream_t st = (hipStream_t)stream;
+  RET_IF(launch_attn_stats(st, D.H, D.Cq, D.maxr, D.maxtiles, w.kstate, w.tiles, w.ntiles, w.rng_pre, w.rng_cnt, w.stats));
+  if (hipMemcpyAsync(host_stats, w.stats, (size_t)D.H * sizeof(adacluster_head_stats), hipMemcpyDeviceToHost, st) != hipSuccess ||
+      hipStreamSynchronize(st) != hipSuccess)
+    return fail(ADACLUSTER_E_INTERNAL, "stats_fetch: copy to the host failed: %s", hipGetErrorString(hipGetLastError()));
+  return 0;
+}
+
+int adacluster_mfma_probe(int32_t iters, float* sink, size_t sink_floats, double* flops, void* stream) {
+  if (iters < 1 || !sink || !flops) return fail(ADACLUSTER_E_BADARG, "mfma_probe: iters >= 1, sink and flops must be given");
+  RET_IF(launch_mfma_probe((hipStream_t)stream, iters, sink, sink_floats, flops));
   return 0;
 }
 

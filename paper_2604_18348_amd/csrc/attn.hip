@@ -197,6 +197,50 @@ __global__ void plan_dense(int N, int maxtiles, int BM, int32_t* __restrict__ rn
   }
 }
 
+// Per-head figures of the last clustering and the last attention plan on this workspace: |C|, F, stages and
+// |U| per stage from the Algorithm 1 state, and the (query, key) pairs the attention launch covers: executed
+// = rows x keys of every query tile, issued = the same with rows rounded up to whole 32-query waves and keys
+// to whole 64-key tiles (what the matrix cores are actually fed).
+__global__ __launch_bounds__(256) void attn_stats(int Cq, int maxr, int maxtiles, const KState* __restrict__ st,
+                                                  const int32_t* __restrict__ tiles, const int32_t* __restrict__ ntiles,
+                                                  const int32_t* __restrict__ rng_pre, const int32_t* __restrict__ rng_cnt,
+                                                  adacluster_head_stats* __restrict__ out) {
+  const int h = blockIdx.x, tid = threadIdx.x;
+  const int nt = min(ntiles[h], maxtiles);
+  const int32_t* tl = tiles + (size_t)h * maxtiles * TILE_REC;
+  long long ex = 0, is = 0;
+  for (int t = tid; t < nt; t += 256) {
+    const int32_t* t6 = tl + (size_t)t * TILE_REC;
+    const int c = t6[0], rows = t6[2], kt0 = t6[3], kt1 = t6[4];
+    const int total = rng_pre[((size_t)h * Cq + c) * (maxr + 1) + rng_cnt[(size_t)h * Cq + c]];
+    const long long keys = max(0, min(total, kt1 * 64) - kt0 * 64);
+    ex += (long long)rows * keys;
+    is += (long long)((rows + 31) / 32 * 32) * ((keys + 63) / 64 * 64);
+  }
+  __shared__ long long s_ex[256], s_is[256];
+  s_ex[tid] = ex; s_is[tid] = is;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (tid < o) { s_ex[tid] += s_ex[tid + o]; s_is[tid] += s_is[tid + o]; }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    adacluster_head_stats r;
+    const KState& k = st[h];
+    r.k_count = k.ccount; r.full_flag = k.full; r.stages = k.stage; r.q_tiles = nt;
+    for (int i = 0; i <= ADACLUSTER_MAX_STAGES; ++i) r.unassigned[i] = i <= k.stage ? k.u_hist[i] : 0;
+    r.reserved = 0;
+    r.executed_pairs = s_ex[0]; r.issued_pairs = s_is[0];
+    out[h] = r;
+  }
+}
+
+int launch_attn_stats(hipStream_t s, int H, int Cq, int maxr, int maxtiles, const KState* st, const int32_t* tiles,
+                      const int32_t* ntiles, const int32_t* rng_pre, const int32_t* rng_cnt, adacluster_head_stats* out) {
+  attn_stats<<<H, 256, 0, s>>>(Cq, maxr, maxtiles, st, tiles, ntiles, rng_pre, rng_cnt, out);
+  return hipGetLastError() == hipSuccess ? 0 : ADACLUSTER_E_INTERNAL;
+}
+
 struct AttnArgs {
   const void* Q; const void* Kp; const void* Vp; void* O;
   const int32_t* perm_q;        // sorted query position -> token (NULL: identity)

@@ -791,7 +791,8 @@ __global__ void kstate_init(KState* st, int H, int N) {
   if (h >= H) return;
   KState s;
   s.ucount = N; s.ccount = 0; s.m_t = 0; s.stage = 0; s.done = 0; s.full = 0; s.active = 0; s.pad = 0;
-  for (int i = 0; i <= ADACLUSTER_MAX_STAGES; ++i) s.stage_offs[i] = 0;
+  for (int i = 0; i <= ADACLUSTER_MAX_STAGES; ++i) { s.stage_offs[i] = 0; s.u_hist[i] = 0; }
+  s.u_hist[0] = N;
   st[h] = s;
 }
 
@@ -803,7 +804,8 @@ __global__ void kstate_warm(KState* st, int H, int N, int cap, const int32_t* __
   KState s;
   s.ucount = N; s.ccount = 0; s.m_t = max(1, min(min(k_count[h], cap), N)); s.stage = 0; s.done = 0;
   s.full = full_flag[h] != 0; s.active = 1; s.pad = 0;
-  for (int i = 0; i <= ADACLUSTER_MAX_STAGES; ++i) s.stage_offs[i] = 0;
+  for (int i = 0; i <= ADACLUSTER_MAX_STAGES; ++i) { s.stage_offs[i] = 0; s.u_hist[i] = 0; }
+  s.u_hist[0] = N;
   st[h] = s;
 }
 __global__ void kstate_commit(KState* st, int H) {
@@ -926,6 +928,7 @@ __global__ void filter_scan(KState* __restrict__ st, int nblk_used, int nblk, in
   s.ccount += s.m_t;
   s.stage += 1;
   s.stage_offs[s.stage] = s.ccount;
+  s.u_hist[s.stage] = run;
   st[h] = s;
 }
 
@@ -1016,6 +1019,7 @@ __global__ __launch_bounds__(1024) void filter_small(KState* __restrict__ st, co
     s.ccount += s.m_t;
     s.stage += 1;
     s.stage_offs[s.stage] = s.ccount;
+    s.u_hist[s.stage] = run;
     st[h] = s;
   }
 }
@@ -1374,6 +1378,7 @@ __global__ __launch_bounds__(SmallStage<D>::NW * 64) void kstages_small(const bf
       s_st.ccount += m;
       s_st.stage += 1;
       s_st.stage_offs[s_st.stage] = s_st.ccount;
+      s_st.u_hist[s_st.stage] = run;
     }
   }
   if (tid == 0) st[h] = s_st;

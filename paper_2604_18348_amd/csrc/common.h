@@ -50,6 +50,7 @@ struct KState {
   int32_t active;      // this stage runs (set by stage_begin)
   int32_t pad;
   int32_t stage_offs[ADACLUSTER_MAX_STAGES + 1];
+  int32_t u_hist[ADACLUSTER_MAX_STAGES + 1];   // |U| at the head of stage t; entry `stage` = what staging left over
 };
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }

@@ -76,6 +76,8 @@ int launch_permute_kv(hipStream_t s, int H, int N, int row_bytes, const void* K,
                       const int32_t* perm, void* Kp, void* Vp);
 int launch_quest_scores(hipStream_t s, int dtype, int form, int clamp, int H, int Lq, int Lk, int d, const void* Q,
                         const void* Rp, const void* Rn, float* S);
+// register-only loop of bf16 MFMAs on every SIMD of the chip (measures what the matrix cores sustain)
+int launch_mfma_probe(hipStream_t s, int iters, float* sink, size_t sink_floats, double* flops);
 int attn_split_slots();      // partial slots per head for the chunks of cut key lists (also extra tile records)
 int launch_plan_sparse(hipStream_t s, int dtype, int H, int Cq, int cap, int maxr, int maxtiles, int BM,
                        const int32_t* q_offs, int q_offs_stride, const int32_t* k_offs, int k_offs_stride,
@@ -84,6 +86,8 @@ int launch_plan_sparse(hipStream_t s, int dtype, int H, int Cq, int cap, int max
                        int32_t* merge, int32_t* nmerge);
 int launch_plan_dense(hipStream_t s, int H, int N, int maxtiles, int BM, int32_t* rng_start, int32_t* rng_pre,
                       int32_t* rng_cnt, int32_t* tiles, int32_t* ntiles);
+int launch_attn_stats(hipStream_t s, int H, int Cq, int maxr, int maxtiles, const KState* st, const int32_t* tiles,
+                      const int32_t* ntiles, const int32_t* rng_pre, const int32_t* rng_cnt, adacluster_head_stats* out);
 int launch_attention(hipStream_t s, int dtype, int d, int H, int N, int Cq, int maxtiles, int maxr, float scale,
                      const void* Q, const void* Kp, const void* Vp, void* O, const int32_t* perm_q,
                      const int32_t* tiles, const int32_t* ntiles, const int32_t* rng_start,

@@ -168,4 +168,39 @@ int launch_quest_scores(hipStream_t s, int dtype, int form, int clamp, int H, in
   return hipGetLastError() == hipSuccess ? 0 : ADACLUSTER_E_INTERNAL;
 }
 
+// ------------------------------------------------------------------------------------------
+// Matrix-core probe: every wave runs four independent chains of v_mfma_f32_32x32x16_bf16 on operands that
+// never leave its registers.  It moves no data, so the rate it reaches is the bf16 MFMA throughput the chip
+// sustains at the clock it holds under that load: the yardstick quoted beside the published peak.
+// ------------------------------------------------------------------------------------------
+static constexpr int PROBE_BLOCKS = 2048, PROBE_THREADS = 256, PROBE_CHAINS = 4;
+__global__ __launch_bounds__(PROBE_THREADS) void mfma_probe(int iters, float* __restrict__ sink) {
+  const int tid = threadIdx.x;
+  bf16x8_t a, b;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) { a[i] = (__bf16)(float)((tid + i) & 3); b[i] = (__bf16)(float)((tid >> 2) & 1); }
+  f32x16_t c[PROBE_CHAINS];
+#pragma unroll
+  for (int j = 0; j < PROBE_CHAINS; ++j)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) c[j][v] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int j = 0; j < PROBE_CHAINS; ++j) c[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c[j], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < PROBE_CHAINS; ++j)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s += c[j][v];
+  if (blockIdx.x == 0) sink[tid] = s;
+}
+
+int launch_mfma_probe(hipStream_t s, int iters, float* sink, size_t sink_floats, double* flops) {
+  if (sink_floats < (size_t)PROBE_THREADS) return ADACLUSTER_E_BADARG;
+  mfma_probe<<<PROBE_BLOCKS, PROBE_THREADS, 0, s>>>(iters, sink);
+  *flops = (double)PROBE_BLOCKS * (PROBE_THREADS / 64) * (double)iters * PROBE_CHAINS * (2.0 * 32 * 32 * 16);
+  return hipGetLastError() == hipSuccess ? 0 : ADACLUSTER_E_INTERNAL;
+}
+
 }  // namespace adac

@@ -21,16 +21,18 @@ def main():
     ap.add_argument("--config", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--drift", type=float, default=0.05)
+    ap.add_argument("--aligned", action="store_true",
+                    help="queries drawn around the key mean of their component: concentrated attention")
     a = ap.parse_args()
 
     import torch
-    import bench
+    from . import harness
     from paper_2604_18348_amd import binding as B
     from paper_2604_18348_amd import workloads as wl
     from paper_2604_18348_amd.ablate import attention_mass_kept
     B.load_library()
     torch.cuda.set_device(0)
-    cfg, Q, K, V = bench.gen_inputs(a.config, torch, B, wl)
+    cfg, Q, K, V = harness.device_inputs(a.config, aligned=a.aligned)
     H, N, d = Q.shape
     dtype = B.BF16 if cfg["dtype"] == "bf16" else B.F32
     cold_p = B.Params(H=H, N=N, d=d, dtype=dtype, **cfg["params"])
@@ -72,11 +74,11 @@ def main():
         ms = timed(cold_p if t == 0 else warm_p, seq, O)
         ms_ref = timed(cold_p, ref, O_ref)
         row = {"step": t, "call": "cold" if t == 0 else "warm", "ms": ms,
-               "density": bench.executed_pairs(seq, cold_p) / (H * float(N) * float(N)),
+               "density": harness.executed_pairs(seq, cold_p) / (H * float(N) * float(N)),
                "k_clusters_mean": float(seq["k_count"].float().mean()),
                "attention_mass_kept": attention_mass_kept(torch, Q, K, seq, cold_p, scale),
                "rel_l2_vs_dense": rel_l2(O),
-               "cold_beside": {"ms": ms_ref, "density": bench.executed_pairs(ref, cold_p) / (H * float(N) * float(N)),
+               "cold_beside": {"ms": ms_ref, "density": harness.executed_pairs(ref, cold_p) / (H * float(N) * float(N)),
                                "k_clusters_mean": float(ref["k_count"].float().mean()),
                                "attention_mass_kept": attention_mass_kept(torch, Q, K, ref, cold_p, scale),
                                "rel_l2_vs_dense": rel_l2(O_ref)}}

@@ -105,8 +105,10 @@ def _means(cfg, g, n_comp, d, scale):
     return (scale * mu).astype(np.float32)
 
 
-def make_head(cfg, head, M=None):
-    """Q, K, V float32 [N,d] of one head (bf16 configs: already bf16-rounded)."""
+def make_head(cfg, head, M=None, aligned=False):
+    """Q, K, V float32 [N,d] of one head (bf16 configs: already bf16-rounded).  aligned: the queries of a
+    component are drawn around the KEY mean of that component, so that attention concentrates on the
+    component's own keys (the default draws the two means independently: diffuse attention)."""
     d = cfg["d"]
     N = n_tokens(cfg)
     M = int(M if M is not None else cfg["M"])
@@ -126,6 +128,8 @@ def make_head(cfg, head, M=None):
             sig = 1.0
         muq = _means(cfg, gm, n_comp, d, mscale)
         muk = _means(cfg, gm, n_comp, d, mscale)
+        if aligned:
+            muq = muk
         Q = muq[comp] + np.float32(sig) * _rng(cfg["seed"], head, 1).standard_normal((N, d), dtype=np.float32)
         K = muk[comp] + np.float32(sig) * _rng(cfg["seed"], head, 2).standard_normal((N, d), dtype=np.float32)
         if cfg["outlier"] > 0:

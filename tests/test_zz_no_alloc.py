@@ -11,7 +11,7 @@ import torch
 from oracle import adacluster_oracle as orc
 from paper_2604_18348_amd import binding as B
 from paper_2604_18348_amd import workloads as wl
-from helpers import to_dev, to_np
+from tests.helpers import to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 
