@@ -182,6 +182,7 @@ struct WS {
   void* Kp; void* Vp;
   int32_t* rng_start; int32_t* rng_pre; int32_t* rng_cnt; int32_t* tiles; int32_t* ntiles;
   int32_t* merge; int32_t* nmerge; float* part_o; float* part_ml;   // cut key lists of the attention step
+  int32_t* krow;        // [H][Cq][kstride] byte offset of every key row of a query cluster's list
   // homes for outputs of the fused call the caller did not ask for
   int32_t* q_labels; float* q_centroids; float* q_assign; int32_t* q_sizes; float* q_mean_norm;
   int32_t* k_labels; float* k_centroids; float* k_assign; float* k_bmin; float* k_bmax;
@@ -266,6 +267,7 @@ size_t layout(const adacluster_params* p, WS* w, unsigned char* base) {
   TAKE(part_o, float*, H * (size_t)attn_split_slots() * D.BM * d * 4);
   TAKE(part_ml, float*, H * (size_t)attn_split_slots() * D.BM * 2 * 4);
   TAKE(ntiles, int32_t*, H * 4);
+  TAKE(krow, int32_t*, p->dtype == ADACLUSTER_BF16 ? H * (size_t)D.Cq * attn_krow_stride(D.N) * 4 : 256);
   TAKE(q_labels, int32_t*, H * N * 4);
   TAKE(q_centroids, float*, H * (size_t)D.Cq * d * 4);
   TAKE(q_assign, float*, H * (size_t)D.Cq * d * 4);
@@ -495,13 +497,15 @@ int run_plan_attention(const adacluster_params* p, const WS& w, hipStream_t st, 
   const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)D.d);
   RET_IF(launch_plan_sparse(st, p->dtype, D.H, D.Cq, D.cap, D.maxr, D.maxtiles, D.BM, w.offs_q, D.Cq + 1, w.offs_k,
                             D.cap + 1, k_count, sel_idx, sel_cnt, w.rng_start, w.rng_pre, w.rng_cnt, w.tiles, w.ntiles,
-                            w.merge, w.nmerge));
+                            w.merge, w.nmerge, D.d * (int)esize(p), p->dtype == ADACLUSTER_BF16 ? w.krow : nullptr,
+                            attn_krow_stride(D.N)));
   prof_mark(EV_PLAN, st, prof_from);
   if (permute_done && hipStreamWaitEvent(st, permute_done, 0) != hipSuccess)
     return fail(ADACLUSTER_E_INTERNAL, "stream join failed");
   if (permute_done) prof_mark(EV_JOIN2, st);
   RET_IF(launch_attention(st, p->dtype, D.d, D.H, D.N, D.Cq, D.maxtiles, D.maxr, scale, Q, w.Kp, w.Vp, O, w.perm_q,
-                          w.tiles, w.ntiles, w.rng_start, w.rng_pre, w.rng_cnt, w.part_o, w.part_ml, w.merge, w.nmerge));
+                          w.tiles, w.ntiles, w.rng_start, w.rng_pre, w.rng_cnt, w.part_o, w.part_ml, w.merge, w.nmerge,
+                          w.krow, attn_krow_stride(D.N)));
   prof_mark(EV_ATTN, st, permute_done ? EV_JOIN2 : -1);
   return 0;
 }
@@ -733,10 +737,12 @@ int adacluster_dense_attn(const adacluster_params* p, const void* Q, const void*
   hipStream_t st = (hipStream_t)stream;
   const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)D.d);
   prof_begin(st);
-  RET_IF(launch_plan_dense(st, D.H, D.N, D.maxtiles, D.BM, w.rng_start, w.rng_pre, w.rng_cnt, w.tiles, w.ntiles));
+  RET_IF(launch_plan_dense(st, D.H, D.N, D.maxtiles, D.BM, w.rng_start, w.rng_pre, w.rng_cnt, w.tiles, w.ntiles,
+                           D.d * (int)esize(p), p->dtype == ADACLUSTER_BF16 ? w.krow : nullptr, attn_krow_stride(D.N)));
   prof_mark(EV_PLAN, st);
   RET_IF(launch_attention(st, p->dtype, D.d, D.H, D.N, 1, D.maxtiles, 1, scale, Q, K, V, O, nullptr, w.tiles,
-                          w.ntiles, w.rng_start, w.rng_pre, w.rng_cnt, nullptr, nullptr, nullptr, nullptr));
+                          w.ntiles, w.rng_start, w.rng_pre, w.rng_cnt, nullptr, nullptr, nullptr, nullptr,
+                          w.krow, attn_krow_stride(D.N)));
   prof_mark(EV_ATTN, st);
   return 0;
 }

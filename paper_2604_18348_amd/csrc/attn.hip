@@ -17,6 +17,7 @@ namespace adac {
 
 static constexpr int TILE_REC = 6;       // ints per query-tile record
 static constexpr int SPLIT_SLOTS = 128;  // partial slots per head for the chunks of cut key lists
+static constexpr int KROW_PAD = 8 * 64;  // entries of the row-offset table a key list is padded by: the kernel reads up to 7 tiles ahead
 
 // ------------------------------------------------------------------------------------------
 // permutation of K and V rows
@@ -75,33 +76,54 @@ int launch_permute_kv(hipStream_t s, int H, int N, int row_bytes, const void* K,
 // rng_cnt   [H][Cq]
 // tiles     [H][maxtiles] x {cluster, first sorted query position, rows, first key tile, end key
 //           tile, partial slot or -1}; ntiles [H]
-__global__ void plan_sparse(int Cq, int cap, int maxr,
+__global__ __launch_bounds__(256) void plan_sparse(int Cq, int cap, int maxr, int row_bytes,
                             const int32_t* __restrict__ k_offs, int k_offs_stride,
                             const int32_t* __restrict__ k_count,
                             const int32_t* __restrict__ sel_idx, const int32_t* __restrict__ sel_cnt,
                             int32_t* __restrict__ rng_start, int32_t* __restrict__ rng_pre,
-                            int32_t* __restrict__ rng_cnt) {
-  const int h = blockIdx.y, i = blockIdx.x;
-  if (threadIdx.x != 0) return;
-  const int32_t* sel = sel_idx + ((size_t)h * Cq + i) * cap;
-  const int cnt = sel_cnt[(size_t)h * Cq + i];
-  const int32_t* ko = k_offs + (size_t)h * k_offs_stride;
-  const int kc = k_count[h];
+                            int32_t* __restrict__ rng_cnt, int32_t* __restrict__ krow, size_t kstride) {
+  const int h = blockIdx.y, i = blockIdx.x, tid = threadIdx.x;
   int32_t* rs = rng_start + ((size_t)h * Cq + i) * maxr;
   int32_t* rp = rng_pre + ((size_t)h * Cq + i) * (maxr + 1);
-  int nr = 0, total = 0, cur_s = 0, cur_e = -1;
-  for (int t = 0; t < cnt; ++t) {
-    const int j = sel[t];
-    if (j < 0 || j >= kc) continue;
-    const int s = ko[j], e = ko[j + 1];
-    if (e <= s) continue;
-    if (s == cur_e) { cur_e = e; continue; }
+  __shared__ int32_t s_nr, s_total;
+  if (tid == 0) {
+    const int32_t* sel = sel_idx + ((size_t)h * Cq + i) * cap;
+    const int cnt = sel_cnt[(size_t)h * Cq + i];
+    const int32_t* ko = k_offs + (size_t)h * k_offs_stride;
+    const int kc = k_count[h];
+    int nr = 0, total = 0, cur_s = 0, cur_e = -1;
+    for (int t = 0; t < cnt; ++t) {
+      const int j = sel[t];
+      if (j < 0 || j >= kc) continue;
+      const int s = ko[j], e = ko[j + 1];
+      if (e <= s) continue;
+      if (s == cur_e) { cur_e = e; continue; }
+      if (cur_e > cur_s) { rs[nr] = cur_s; rp[nr] = total; total += cur_e - cur_s; ++nr; }
+      cur_s = s; cur_e = e;
+    }
     if (cur_e > cur_s) { rs[nr] = cur_s; rp[nr] = total; total += cur_e - cur_s; ++nr; }
-    cur_s = s; cur_e = e;
+    rp[nr] = total;
+    rng_cnt[(size_t)h * Cq + i] = nr;
+    s_nr = nr; s_total = total;
   }
-  if (cur_e > cur_s) { rs[nr] = cur_s; rp[nr] = total; total += cur_e - cur_s; ++nr; }
-  rp[nr] = total;
-  rng_cnt[(size_t)h * Cq + i] = nr;
+  __syncthreads();        // the ranges thread 0 wrote are visible to the workgroup
+  // Byte offset of every key row of the concatenation, in order: what a key tile of the attention kernel
+  // loads its 64 rows by.  Entries past the end (up to the padding the kernel may read ahead) repeat the
+  // first row: they are loaded and never used.
+  if (!krow) return;       // (the fp32 kernel walks the ranges itself)
+  const int nr = s_nr, total = s_total;
+  int32_t* kr = krow + ((size_t)h * Cq + i) * kstride;
+  const int first = nr > 0 ? rs[0] * row_bytes : 0;
+  const int padded = (total + 63) / 64 * 64 + KROW_PAD;
+  for (int p = tid; p < padded; p += 256) {
+    int off = first;
+    if (p < total) {
+      int lo = 0, hi = nr - 1;                 // last range whose first position is <= p
+      while (lo < hi) { const int mid = (lo + hi + 1) >> 1; if (rp[mid] <= p) lo = mid; else hi = mid - 1; }
+      off = (rs[lo] + (p - rp[lo])) * row_bytes;
+    }
+    kr[p] = off;
+  }
 }
 
 // Query tiles of a head, cluster by cluster.  A query cluster whose key list is much longer than
@@ -182,10 +204,19 @@ __global__ __launch_bounds__(256) void plan_tiles(int Cq, int maxr, int maxtiles
 }
 
 // dense: one query "cluster" over all rows, one key range [0,N)
-__global__ void plan_dense(int N, int maxtiles, int BM, int32_t* __restrict__ rng_start,
+__global__ void plan_dense(int N, int maxtiles, int BM, int row_bytes, int32_t* __restrict__ rng_start,
                            int32_t* __restrict__ rng_pre, int32_t* __restrict__ rng_cnt,
-                           int32_t* __restrict__ tiles, int32_t* __restrict__ ntiles) {
+                           int32_t* __restrict__ tiles, int32_t* __restrict__ ntiles,
+                           int32_t* __restrict__ krow, size_t kstride) {
   const int h = blockIdx.x;
+  if (blockIdx.y > 0) {       // the other workgroups of a head fill its row-offset table (the identity)
+    if (!krow) return;
+    int32_t* kr = krow + (size_t)h * kstride;
+    const int padded = (N + 63) / 64 * 64 + KROW_PAD;
+    for (int p = (blockIdx.y - 1) * blockDim.x + threadIdx.x; p < padded; p += (gridDim.y - 1) * blockDim.x)
+      kr[p] = p < N ? p * row_bytes : 0;
+    return;
+  }
   if (threadIdx.x == 0) {
     rng_start[h] = 0; rng_pre[(size_t)h * 2] = 0; rng_pre[(size_t)h * 2 + 1] = N; rng_cnt[h] = 1;
     ntiles[h] = (N + BM - 1) / BM;
@@ -251,6 +282,7 @@ struct AttnArgs {
   int head_major;               // workgroup -> (head, tile) mapping, see attn_mfma
   float* part_o; float* part_ml;   // partial slots of cut key lists: [H][slots][BM][d], [H][slots][BM][2]
   int slots, BM;
+  const int32_t* krow; size_t kstride;   // byte offset of every key row of a query cluster's list: [H][Cq][kstride]
 };
 
 // position in the concatenation of ranges -> permuted key row; a cursor that only moves forward
@@ -287,15 +319,53 @@ __device__ __forceinline__ s16x4_t lds_read_tr16(const char* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)p);
 }
 
-// One workgroup = NW waves, each owning QB blocks of 32 queries; all waves share 64-key K and V
-// tiles.  Tiles go global -> LDS directly (no register staging) as 16-byte chunks, one tile
-// ahead, double buffered.  A tile row is unpadded; chunk g of row r sits in slot g ^ (r & 7), which
-// keeps the 16-byte operand reads and the transpose reads free of bank conflicts.
-template <int D, int QB, int NW, int MINB>
+// Direct global -> LDS loads, written as inline assembly on purpose.  The compiler orders every LDS read
+// behind an outstanding direct-to-LDS load that it cannot prove to touch another object (it then drains ALL
+// loads in flight: vmcnt(0)), and its proof is fragile (it fails across the branches of a four-stage ring).
+// The tile pipeline below keeps several tiles in flight and waits for exactly the one it needs, by count,
+// before a workgroup barrier; hiding the loads from the compiler leaves that protocol in charge.  Each lane
+// loads `bytes` at sbase + voff; the wave's data land at lds_addr + lane * bytes (M0 carries the LDS address).
+__device__ __forceinline__ void dma_b128(uint32_t lds_addr, uint32_t voff, const void* sbase) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+}
+__device__ __forceinline__ void dma_b32(uint32_t lds_addr, uint32_t voff, const void* sbase) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+}
+
+// s_waitcnt with only the vector-memory counter set (gfx9 encoding: vmcnt[3:0] and [15:14])
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt has six bits");
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() carries a release fence over global memory
+// as well, which makes every wave drain all of its loads in flight (vmcnt(0)) at every barrier; the tile
+// pipeline below waits for exactly the loads it needs by count and must keep the rest in flight.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // this wave's LDS reads and writes are done
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");                         // nothing that touches memory moves across
+}
+
+// One workgroup = NW waves of 32 queries each; all waves share 64-key K and V tiles.  Tiles go global -> LDS
+// directly (no register staging) as 16-byte chunks into a ring of NBUF stages, NBUF-1 tiles ahead of the
+// arithmetic, one barrier per tile.  A tile row is unpadded and its 16-byte chunks are permuted by a row-dependent
+// XOR that keeps the operand reads of either tile free of bank conflicts (see swz_k, swz_v).  The rows of a tile come
+// from the row-offset table plan_sparse / plan_dense wrote: its 64 entries for a tile are themselves loaded
+// global -> LDS, 2*(NBUF-1) tiles ahead, so that no wave walks a range list and no load waits on a register.
+// LDS layout: [K ring: NBUF tiles][V ring: NBUF tiles][row offsets: NBUF x 64]; with the K tiles (and the V
+// tiles) side by side, a stage is reached from one set of address registers by an immediate offset (< 64 KB).
+template <int D, int NW, int NBUF, int MINB, int VPRE>
 __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
   constexpr int BN = 64, NT = NW * 64, KS = D / 16, DB = D / 32, CH = D / 8, ROWB = D * 2;
-  constexpr int ITEMS = BN * CH, PT = ITEMS / NT, TILEB = BN * ROWB;
+  constexpr int ITEMS = BN * CH, PT = ITEMS / NT, TILEB = BN * ROWB, PD = NBUF - 1;
+  constexpr int VM_STEP = 2 * PT + 1;             // vector-memory operations a wave issues per tile
+  constexpr int KRING = NBUF * TILEB;             // bytes of the ring of K tiles (the ring of V tiles follows it)
   static_assert(ITEMS % NT == 0, "tile chunks must divide evenly over the threads");
+  static_assert(NBUF == 2 || NBUF == 4, "two or four stages");
+  static_assert(2 * PD + 1 <= KROW_PAD / 64, "the row-offset table is padded for the read-ahead");
+  static_assert(64 % NW == 0, "every wave loads an equal share of a tile's row offsets");
 
   // Workgroups go to the 8 XCDs round-robin in launch order (gridDim.x is a multiple of 8, so
   // XCD = blockIdx.x % 8), and each XCD has its own L2.
@@ -332,12 +402,12 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
   const int c = lane & 31, hb = lane >> 5;
 
   const int nr = a.rng_cnt[(size_t)h * a.Cq + qc];
-  const int32_t* rs = a.rng_start + ((size_t)h * a.Cq + qc) * a.maxr;
   const int32_t* rp = a.rng_pre + ((size_t)h * a.Cq + qc) * (a.maxr + 1);
   // positions below are relative to the first key of the share
   const int pbase = kt0 * BN;
   const int total = max(0, min(rp[nr], kt1 * BN) - pbase);
   const int T = (total + BN - 1) / BN;
+  const int32_t* krow = a.krow + ((size_t)h * a.Cq + qc) * a.kstride + pbase;   // byte offsets of the key rows
 
   const bf16raw* Qh = (const bf16raw*)a.Q + (size_t)h * a.N * D;
   const char* Kh = (const char*)a.Kp + (size_t)h * a.N * ROWB;
@@ -345,62 +415,73 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
   bf16raw* Oh = (bf16raw*)a.O + (size_t)h * a.N * D;
   const int32_t* pq = a.perm_q ? a.perm_q + (size_t)h * a.N : nullptr;
 
-  // Every tile buffer is an LDS object of its own, and the tile loop below is unrolled so that each
-  // access names its buffer at compile time: the compiler orders an LDS read behind an outstanding
-  // direct-to-LDS load only when both may touch the same object, so this is what lets the load of
-  // tile t+1 run under the arithmetic of tile t (with one array indexed by t & 1 it put a
-  // vmcnt(0) wait in front of the first operand read of every tile).
-  __shared__ __attribute__((aligned(16))) char K0[TILEB];
-  __shared__ __attribute__((aligned(16))) char K1[TILEB];
-  __shared__ __attribute__((aligned(16))) char V0[TILEB];
-  __shared__ __attribute__((aligned(16))) char V1[TILEB];
-  __shared__ int32_t ridx[4][BN];          // byte offset of each key row of a tile
-
-  // query tokens of this lane and the B operand of S
-  int qtok[QB];
-  bf16x8_t qf[QB][KS];
-  const bool wave_has_rows = wave * (32 * QB) < nrows;
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    const int rr = wave * (32 * QB) + qb * 32 + c;
-    qtok[qb] = -1;
-    if (rr < nrows) qtok[qb] = pq ? pq[row0 + rr] : row0 + rr;
+  // query token of this lane and the B operand of S
+  int qtok = -1;
+  bf16x8_t qf[KS];
+  const bool wave_has_rows = wave * 32 < nrows;
+  {
+    const int rr = wave * 32 + c;
+    if (rr < nrows) qtok = pq ? pq[row0 + rr] : row0 + rr;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       uint4 raw = {0, 0, 0, 0};
-      if (qtok[qb] >= 0) raw = *reinterpret_cast<const uint4*>(Qh + (size_t)qtok[qb] * D + ks * 16 + hb * 8);
-      qf[qb][ks] = *reinterpret_cast<const bf16x8_t*>(&raw);
+      if (qtok >= 0) raw = *reinterpret_cast<const uint4*>(Qh + (size_t)qtok * D + ks * 16 + hb * 8);
+      qf[ks] = *reinterpret_cast<const bf16x8_t*>(&raw);
     }
   }
 
-  f32x16_t oacc[DB][QB];
+  f32x16_t oacc[DB];
 #pragma unroll
   for (int db = 0; db < DB; ++db)
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) oacc[db][qb][v] = 0.f;
-  float mrun[QB], lrun[QB];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) { mrun[qb] = -INFINITY; lrun[qb] = 0.f; }
+    for (int v = 0; v < 16; ++v) oacc[db][v] = 0.f;
+  // Soft-max state of this lane's query: probabilities are taken relative to a reference mref that is only
+  // moved when it has to be (see soft-max below); lrun is the sum of the probabilities so far.
+  float mref = -INFINITY, lrun = 0.f;
 
-  // thread -> (row, slot) of its PT chunks; the slot holds global chunk slot ^ (row & 7)
-  auto issue_loads = [&](char* kdst, char* vdst, int rb) {
+  // Where a 16-byte chunk sits inside its (unpadded) tile row: chunk q of row r is in slot q ^ swz(r).  A row
+  // is 256 B (d=128: every row starts at bank 0) or 128 B (d=64: rows two apart do), so the slot alone decides
+  // the banks, and the two tiles are read in different shapes:
+  //   K: a 16-byte operand read takes the same chunk of 16 consecutive rows per cycle -> 16 distinct slots
+  //      (d=128), or 8 slots x the two row parities (d=64);
+  //   V: a transpose read takes 64 contiguous bytes (4 slots) of 4 consecutive rows per cycle -> the rows
+  //      must differ in the slot's upper bits; rows 8 apart share a swizzle, so the second half of an operand
+  //      is a constant offset away.
+  // Measured on the LDS alone: 3.7 and 2.2 cycles per read against 7.5 and 7.5 (3.9 at d=64) with q ^ (r & 7).
+  auto swz_k = [](int r) __attribute__((always_inline)) { return D == 128 ? (r & 15) : ((r >> 1) & 7); };
+  auto swz_v = [](int r) __attribute__((always_inline)) { return D == 128 ? ((r & 3) << 2) : (((r >> 1) & 1) << 2); };
+  // thread -> (row, slot) of its PT chunks of a tile, and the global chunk that slot holds in either tile
+  int lrow[PT], lswz_k[PT], lswz_v[PT];
+#pragma unroll
+  for (int i = 0; i < PT; ++i) {
+    const int item = tid + i * NT;
+    lrow[i] = item / CH;
+    lswz_k[i] = ((item % CH) ^ swz_k(lrow[i])) * 16;
+    lswz_v[i] = ((item % CH) ^ swz_v(lrow[i])) * 16;
+  }
+  constexpr int RIDX0 = 2 * KRING;
+  __shared__ __attribute__((aligned(16))) char lds[2 * KRING + NBUF * BN * 4];
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_void_t*)lds;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  // the 64 row offsets of tile t go to the offsets slot of stage `st`, an equal share per wave
+  const uint32_t ridx_voff = (uint32_t)((wave_u * (BN / NW) + (lane % (BN / NW))) * 4);
+  auto issue_ridx = [&](int st, int t) __attribute__((always_inline)) {
+    if (lane < BN / NW)
+      dma_b32(lds0 + RIDX0 + st * (BN * 4) + wave_u * (BN / NW) * 4, (uint32_t)(t * (BN * 4)) + ridx_voff, krow);
+  };
+  auto issue_tile = [&](int st, const int32_t* off) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
-      const int item = tid + i * NT;
-      const int r = item / CH, q = item % CH;
-      const uint32_t off = (uint32_t)ridx[rb][r] + (uint32_t)((q ^ (r & 7)) * 16);
-      const int dst = (wave * 64 + i * NT) * 16;     // wave-uniform; the lane offset is implicit
-      __builtin_amdgcn_global_load_lds(Kh + off, (lds_void_t*)(kdst + dst), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(Vh + off, (lds_void_t*)(vdst + dst), 16, 0, 0);
+      const uint32_t dst = lds0 + st * TILEB + (wave_u * 64 + i * NT) * 16;     // wave-uniform; the lane offset is implicit
+      dma_b128(dst, (uint32_t)off[i] + (uint32_t)lswz_k[i], Kh);
+      dma_b128(dst + KRING, (uint32_t)off[i] + (uint32_t)lswz_v[i], Vh);
     }
   };
 
   // operand addresses inside a tile (bytes), fixed for the whole kernel
   int kaddr[KS];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) kaddr[ks] = c * ROWB + (((ks * 2 + hb) ^ (c & 7)) * 16);
+  for (int ks = 0; ks < KS; ++ks) kaddr[ks] = c * ROWB + (((ks * 2 + hb) ^ swz_k(c)) * 16);
   // The 8 accumulator values a lane feeds to one P V step are keys 4*hb + {0..3} and
   // 8 + 4*hb + {0..3} of a 16-key group; the V operand is gathered to match by two transpose
   // reads: this lane addresses key 4*hb + (lane%16)/4, columns 16*((lane/16)%2) + 4*(lane%4) .. +3
@@ -411,86 +492,36 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
     const int vrow = 4 * hb + (i16 >> 2);
     const int gl = 2 * (blk & 1) + ((i16 & 3) >> 1);
 #pragma unroll
-    for (int db = 0; db < DB; ++db) vaddr[db] = vrow * ROWB + (((db * 4 + gl) ^ (vrow & 7)) * 16) + 8 * (i16 & 1);
-  }
+    for (int db = 0; db < DB; ++db) vaddr[db] = KRING + vrow * ROWB + (((db * 4 + gl) ^ swz_v(vrow)) * 16) + 8 * (i16 & 1);
+  }       // (the offset of the V ring sits in the register: what an LDS read adds as an immediate must stay below 64 KB)
   const bf16x2_t ones2 = {(__bf16)1.0f, (__bf16)1.0f};   // row sums use the rounded probabilities P V uses
   const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  const float sc = a.scale_log2e;
+  constexpr float P_LIMIT = 65536.f;      // a tile whose probabilities sum past this moves the reference
 
   auto compute_tile = [&](const char* ks_, const char* vs_, int nvalid /* < BN only on a masked tail tile */,
-                          auto masked) {
+                          auto masked) __attribute__((always_inline)) {
     constexpr bool MASK = decltype(masked)::value;
-    f32x16_t sacc[2][QB];
+    // All K operands of the tile are requested before the first product, and (below) the V operands before
+    // the soft-max arithmetic: an LDS read takes a hundred cycles or more to come back, and the compiler, left
+    // alone, requests an operand only one product ahead of its use.  The empty asm statements are fences for
+    // memory operations only: reads do not sink below them, the register-only MFMAs and VALU work move freely.
+    f32x16_t sacc[2];
+    bf16x8_t ka[2][KS];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      bf16x8_t ka[KS];
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
-        ka[ks] = *reinterpret_cast<const bf16x8_t*>(ks_ + kb * 32 * ROWB + kaddr[ks]);
+        ka[kb][ks] = *reinterpret_cast<const bf16x8_t*>(ks_ + kb * 32 * ROWB + kaddr[ks]);
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
+        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kb][ks], qf[ks], ks == 0 ? zero16 : sacc[kb], 0, 0, 0);
+    bf16x8_t va[VPRE > 0 ? VPRE : 1][2][2];
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-          sacc[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qf[qb][ks], ks == 0 ? zero16 : sacc[kb][qb], 0, 0, 0);
-    }
-    // accumulator value v of block kb is key  kb*32 + 8*(v/4) + 4*hb + v%4
-    if (MASK) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int key = kb * 32 + 8 * (v >> 2) + 4 * hb + (v & 3);
-          if (key >= nvalid) {
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) sacc[kb][qb][v] = -INFINITY;
-          }
-        }
-    }
-    bf16x8_t pf[QB][2][2];
-    float alpha[QB];
-    bool need_rescale = false;
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      float tmax = sacc[0][qb][0];
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, sacc[kb][qb][v]);
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-      const float mnew = fmaxf(mrun[qb], tmax);           // finite: every tile holds a valid key
-      alpha[qb] = __builtin_amdgcn_exp2f((mrun[qb] - mnew) * a.scale_log2e);
-      need_rescale = need_rescale || (mnew != mrun[qb]);
-      const float moff = mnew * a.scale_log2e;
-      mrun[qb] = mnew;
-      float rsum = 0.f;
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-          uint32_t w[4];
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][qb][8 * s2 + 2 * j], a.scale_log2e, -moff));
-            const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][qb][8 * s2 + 2 * j + 1], a.scale_log2e, -moff));
-            w[j] = pack_bf16x2(p0, p1);
-            rsum = __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<const bf16x2_t*>(&w[j]), ones2, rsum, false);
-          }
-          const uint4 pk = {w[0], w[1], w[2], w[3]};
-          pf[qb][kb][s2] = *reinterpret_cast<const bf16x8_t*>(&pk);
-        }
-      lrun[qb] = lrun[qb] * alpha[qb] + rsum;
-    }
-    // the running maximum rarely moves after the first tiles: rescale only when some lane needs it
-    if (__any(need_rescale)) {
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) oacc[db][qb][v] *= alpha[qb];
-    }
-#pragma unroll
-    for (int db = 0; db < DB; ++db) {
-      bf16x8_t va[2][2];
+    for (int db = 0; db < VPRE; ++db)
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -498,101 +529,173 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
           const char* vp = vs_ + (kb * 32 + 16 * s2) * ROWB + vaddr[db];
           const s16x4_t lo = lds_read_tr16(vp), hi = lds_read_tr16(vp + 8 * ROWB);
           const s16x4_t both[2] = {lo, hi};
-          va[kb][s2] = *reinterpret_cast<const bf16x8_t*>(both);
+          va[db][kb][s2] = *reinterpret_cast<const bf16x8_t*>(both);
         }
+    asm volatile("" ::: "memory");
+    // accumulator value v of block kb is key  kb*32 + 8*(v/4) + 4*hb + v%4
+    if (MASK) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int key = kb * 32 + 8 * (v >> 2) + 4 * hb + (v & 3);
+          if (key >= nvalid) sacc[kb][v] = -INFINITY;
+        }
+    }
+    // Soft-max.  p = 2^((s - mref) scale): any reference gives the same normalised result as long as nothing
+    // overflows, so no maximum is taken per tile.  The row sum of the tile tells when the reference is too
+    // low (or still -inf, on the first tile; a masked score against that gives NaN, caught by the same test):
+    // only then is the tile's maximum taken, the reference moved up to it and the accumulator rescaled.
+    bf16x8_t pf[2][2];
+    float rsum;
+    auto probabilities = [&]() __attribute__((always_inline)) {
+      const float moff = mref * sc;
+      float part[2][2];                    // four chains of sums, so that an add does not wait for the one before it
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          uint32_t w[4];
+          part[kb][s2] = 0.f;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][8 * s2 + 2 * j], sc, -moff));
+            const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][8 * s2 + 2 * j + 1], sc, -moff));
+            w[j] = pack_bf16x2(p0, p1);
+            part[kb][s2] = __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<const bf16x2_t*>(&w[j]), ones2, part[kb][s2], false);
+          }
+          const uint4 pk = {w[0], w[1], w[2], w[3]};
+          pf[kb][s2] = *reinterpret_cast<const bf16x8_t*>(&pk);
+        }
+      rsum = (part[0][0] + part[0][1]) + (part[1][0] + part[1][1]);
+    };
+    probabilities();
+    if (__any(!(rsum <= P_LIMIT))) {
+      float tmax = sacc[0][0];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, sacc[kb][v]);
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32));           // finite: every tile holds a valid key
+      const float mnew = fmaxf(mref, tmax);
+      const float alpha = __builtin_amdgcn_exp2f((mref - mnew) * sc);
+      mref = mnew;
+      lrun *= alpha;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) oacc[db][v] *= alpha;
+      probabilities();
+    }
+    lrun += rsum;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      bf16x8_t vb[2][2];
+      if (db >= VPRE) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int s2 = 0; s2 < 2; ++s2) {
+            const char* vp = vs_ + (kb * 32 + 16 * s2) * ROWB + vaddr[db];
+            const s16x4_t lo = lds_read_tr16(vp), hi = lds_read_tr16(vp + 8 * ROWB);
+            const s16x4_t both[2] = {lo, hi};
+            vb[kb][s2] = *reinterpret_cast<const bf16x8_t*>(both);
+          }
+      }
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-          for (int qb = 0; qb < QB; ++qb)
-            oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[kb][s2], pf[qb][kb][s2], oacc[db][qb], 0, 0, 0);
+          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(db < VPRE ? va[db < VPRE ? db : 0][kb][s2] : vb[kb][s2], pf[kb][s2], oacc[db], 0, 0, 0);
     }
   };
 
-  // prologue: row offsets of tiles 0..2 (a slot past the end repeats the first row: it is loaded
-  // but masked), tile 0 into LDS
-  // The range table of a query cluster is short (at most top-k entries): it is copied to LDS, so
-  // that walking it issues no vector-memory load (those complete in order with the tile loads and
-  // would make the walking wave wait for the tile just requested).  A longer table stays in HBM.
-  constexpr int RNG_LDS = 256;
-  __shared__ int32_t rng_s[RNG_LDS], rng_p[RNG_LDS + 1];
-  const bool rng_in_lds = nr <= RNG_LDS;
-  if (rng_in_lds) {
-    for (int i = tid; i < nr; i += NT) rng_s[i] = rs[i];
-    for (int i = tid; i <= nr; i += NT) rng_p[i] = rp[i];
-  }
-  __syncthreads();
-  RangeCursor cur;
-  RangeCursorT<lds_ci32_t*> cur_l;
-  const int first_off = nr > 0 ? rs[0] * ROWB : 0;
-  auto row_off = [&](int p) {
-    const int r = rng_in_lds ? cur_l.row(p + pbase) : cur.row(p + pbase);
-    return r < 0 ? first_off : r * ROWB;
+  // Tile t lives in stage t % NBUF; the row offsets of tile t sit in the offsets slot of stage (t + 1) % NBUF,
+  // the stage whose tile is being worked on when the loads of tile t are issued.  In step t:
+  //   loads of tile t + PD          -> stage (t + PD) % NBUF (free since step t - 1), rows from the offsets slot
+  //                                    of stage t % NBUF
+  //   row offsets of tile t + 2 PD  -> the offsets slot of stage (t + PD) % NBUF
+  //   arithmetic of tile t
+  //   wait until this wave's loads of tile t + 1 have landed, barrier.
+  // Loads are issued for tiles past the end too (the table is padded), so that the number of operations in
+  // flight is the same in every step and one constant serves the wait.
+  auto step = [&](auto stage, int t) __attribute__((always_inline)) {
+    constexpr int U = decltype(stage)::value, G = (U + PD) % NBUF;
+    int32_t off[PT];
+#pragma unroll
+    for (int i = 0; i < PT; ++i) off[i] = reinterpret_cast<const int32_t*>(lds + RIDX0 + U * (BN * 4))[lrow[i]];
+    issue_tile(G, off);
+    issue_ridx(G, t + 2 * PD);
+    if (wave_has_rows) compute_tile(lds + U * TILEB, lds + U * TILEB, BN, std::false_type{});
+    wait_vmcnt<(PD - 1) * VM_STEP>();
+    lds_barrier();
   };
-  if (tid < BN) {
-    if (rng_in_lds) cur_l.init((lds_ci32_t*)rng_s, (lds_ci32_t*)rng_p, nr);
-    else cur.init(rs, rp, nr);
-    ridx[0][tid] = row_off(tid);
-    ridx[1][tid] = row_off(BN + tid);
-    ridx[2][tid] = row_off(2 * BN + tid);
-  }
-  __syncthreads();
-  if (T > 0) issue_loads(K0, V0, 0);
-  __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's tile chunks have landed in LDS
-  __syncthreads();
 
-  // full tiles in the loop, two per trip (tile t lives in buffer t & 1); a ragged tail tile (the
-  // only one that needs masking) after it
-  const int Tfull = total / BN;
-  auto step = [&](int t, const char* kc, const char* vc, char* kn, char* vn) {
-    if (t + 1 < T) issue_loads(kn, vn, (t + 1) & 3);
-    if (tid < BN && t + 3 < T) ridx[(t + 3) & 3][tid] = row_off((t + 3) * BN + tid);
-    if (wave_has_rows) compute_tile(kc, vc, BN, std::false_type{});
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-    __syncthreads();
-  };
-  int t = 0;
-  for (; t + 2 <= Tfull; t += 2) {
-    step(t, K0, V0, K1, V1);
-    step(t + 1, K1, V1, K0, V0);
-  }
-  if (t < Tfull) { step(t, K0, V0, K1, V1); ++t; }
-  if (T > Tfull && wave_has_rows) {
-    if (Tfull & 1) compute_tile(K1, V1, total - Tfull * BN, std::true_type{});
-    else compute_tile(K0, V0, total - Tfull * BN, std::true_type{});
+  const int Tlast = T - 1;       // the loop takes tiles 0 .. Tlast-1; the last one, full or ragged, is peeled
+  if (T > 0) {
+    // tiles 0 .. PD-1: rows straight from the table; row offsets of tiles PD .. 2 PD - 1 to their slots
+#pragma unroll
+    for (int t = 0; t < PD; ++t) {
+      int32_t off[PT];
+#pragma unroll
+      for (int i = 0; i < PT; ++i) off[i] = krow[(size_t)t * BN + lrow[i]];
+      issue_tile(t, off);
+    }
+#pragma unroll
+    for (int t = PD; t < 2 * PD; ++t) issue_ridx((t + 1) % NBUF, t);
+    wait_vmcnt<0>();
+    lds_barrier();
+    if constexpr (NBUF == 2) {
+      for (int t = 0; t < Tlast; t += 2) {
+        step(std::integral_constant<int, 0>{}, t);
+        if (t + 1 >= Tlast) break;
+        step(std::integral_constant<int, 1>{}, t + 1);
+      }
+    } else {
+      for (int t = 0; t < Tlast; t += 4) {
+        step(std::integral_constant<int, 0>{}, t);
+        if (t + 1 >= Tlast) break;
+        step(std::integral_constant<int, 1>{}, t + 1);
+        if (t + 2 >= Tlast) break;
+        step(std::integral_constant<int, 2>{}, t + 2);
+        if (t + 3 >= Tlast) break;
+        step(std::integral_constant<int, 3>{}, t + 3);
+      }
+    }
+    wait_vmcnt<0>();       // nothing of this wave is still on its way to LDS when it ends
+    const int u = Tlast % NBUF;
+    if (wave_has_rows) compute_tile(lds + u * TILEB, lds + u * TILEB, total - Tlast * BN, std::true_type{});
   }
 
   // O^T accumulator value v of block db is column  db*32 + 8*(v/4) + 4*hb + v%4  of query c
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    const float l = lrun[qb] + __shfl_xor(lrun[qb], 32);
+  {
+    const float l = lrun + __shfl_xor(lrun, 32);
     if (pslot >= 0) {
-      // a chunk of a cut key list: leave the unnormalised accumulator, the running maximum and the
+      // a chunk of a cut key list: leave the unnormalised accumulator, the reference and the
       // row sum in this chunk's slot; attn_merge combines the chunks of the query tile
-      const int rr = wave * (32 * QB) + qb * 32 + c;
+      const int rr = wave * 32 + c;
       const size_t so = ((size_t)h * a.slots + pslot) * a.BM + rr;
       float* po = a.part_o + so * D;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const float4 o = {oacc[db][qb][4 * i], oacc[db][qb][4 * i + 1], oacc[db][qb][4 * i + 2], oacc[db][qb][4 * i + 3]};
+          const float4 o = {oacc[db][4 * i], oacc[db][4 * i + 1], oacc[db][4 * i + 2], oacc[db][4 * i + 3]};
           *reinterpret_cast<float4*>(po + db * 32 + 8 * i + 4 * hb) = o;
         }
-      if (hb == 0) { a.part_ml[so * 2] = mrun[qb]; a.part_ml[so * 2 + 1] = l; }
-      continue;
+      if (hb == 0) { a.part_ml[so * 2] = mref; a.part_ml[so * 2 + 1] = l; }
+      return;
     }
     const float inv = l > 0.f ? 1.0f / l : 0.f;
-    if (qtok[qb] < 0) continue;
-    bf16raw* orow = Oh + (size_t)qtok[qb] * D;
+    if (qtok < 0) return;
+    bf16raw* orow = Oh + (size_t)qtok * D;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         uint2 o;
-        o.x = pack_bf16x2(oacc[db][qb][4 * i] * inv, oacc[db][qb][4 * i + 1] * inv);
-        o.y = pack_bf16x2(oacc[db][qb][4 * i + 2] * inv, oacc[db][qb][4 * i + 3] * inv);
+        o.x = pack_bf16x2(oacc[db][4 * i] * inv, oacc[db][4 * i + 1] * inv);
+        o.y = pack_bf16x2(oacc[db][4 * i + 2] * inv, oacc[db][4 * i + 3] * inv);
         *reinterpret_cast<uint2*>(orow + db * 32 + 8 * i + 4 * hb) = o;
       }
   }
@@ -713,30 +816,40 @@ __global__ __launch_bounds__(256) void attn_merge(AttnArgs a, const int32_t* __r
 }
 
 // ------------------------------------------------------------------------------------------
-// tile shapes of the bf16 kernel: queries per wave = 32*QB, waves per block NW, blocks per CU MINB
-#ifndef A64_QB
-#define A64_QB 1
-#endif
+// tile shapes of the bf16 kernel: waves per workgroup NW (32 queries each), pipeline stages NBUF, and MINB = the
+// waves per SIMD the register budget is set for (the second __launch_bounds__ argument)
 #ifndef A64_NW
-#define A64_NW 4
+#define A64_NW 8
+#endif
+#ifndef A64_NBUF
+#define A64_NBUF 4
 #endif
 #ifndef A64_MINB
 #define A64_MINB 4
 #endif
-#ifndef A128_QB
-#define A128_QB 1
-#endif
 #ifndef A128_NW
-#define A128_NW 4
+#define A128_NW 8
+#endif
+#ifndef A128_NBUF
+#define A128_NBUF 4
 #endif
 #ifndef A128_MINB
 #define A128_MINB 2
 #endif
+// 32-column blocks of V whose operands are requested before the soft-max arithmetic (the rest follow it)
+#ifndef A64_VPRE
+#define A64_VPRE 0
+#endif
+#ifndef A128_VPRE
+#define A128_VPRE 4
+#endif
 
 int attn_block_rows(int dtype, int d) {
   if (dtype != ADACLUSTER_BF16) return 64;
-  return d == 64 ? A64_NW * 32 * A64_QB : A128_NW * 32 * A128_QB;
+  return d == 64 ? A64_NW * 32 : A128_NW * 32;
 }
+
+size_t attn_krow_stride(int N) { return (size_t)(N + 63) / 64 * 64 + KROW_PAD; }
 
 int attn_split_slots() { return SPLIT_SLOTS; }
 
@@ -744,17 +857,17 @@ int launch_plan_sparse(hipStream_t s, int dtype, int H, int Cq, int cap, int max
                        const int32_t* q_offs, int q_offs_stride, const int32_t* k_offs, int k_offs_stride,
                        const int32_t* k_count, const int32_t* sel_idx, const int32_t* sel_cnt,
                        int32_t* rng_start, int32_t* rng_pre, int32_t* rng_cnt, int32_t* tiles, int32_t* ntiles,
-                       int32_t* merge, int32_t* nmerge) {
-  plan_sparse<<<dim3(Cq, H), 64, 0, s>>>(Cq, cap, maxr, k_offs, k_offs_stride, k_count, sel_idx, sel_cnt, rng_start,
-                                        rng_pre, rng_cnt);
+                       int32_t* merge, int32_t* nmerge, int row_bytes, int32_t* krow, size_t kstride) {
+  plan_sparse<<<dim3(Cq, H), 256, 0, s>>>(Cq, cap, maxr, row_bytes, k_offs, k_offs_stride, k_count, sel_idx, sel_cnt,
+                                         rng_start, rng_pre, rng_cnt, krow, kstride);
   plan_tiles<<<H, 256, 0, s>>>(Cq, maxr, maxtiles, BM, SPLIT_SLOTS, dtype == ADACLUSTER_BF16 ? 1 : 0, q_offs,
                               q_offs_stride, rng_pre, rng_cnt, tiles, ntiles, merge, nmerge);
   return hipGetLastError() == hipSuccess ? 0 : ADACLUSTER_E_INTERNAL;
 }
 
 int launch_plan_dense(hipStream_t s, int H, int N, int maxtiles, int BM, int32_t* rng_start, int32_t* rng_pre,
-                      int32_t* rng_cnt, int32_t* tiles, int32_t* ntiles) {
-  plan_dense<<<H, 256, 0, s>>>(N, maxtiles, BM, rng_start, rng_pre, rng_cnt, tiles, ntiles);
+                      int32_t* rng_cnt, int32_t* tiles, int32_t* ntiles, int row_bytes, int32_t* krow, size_t kstride) {
+  plan_dense<<<dim3(H, 9), 256, 0, s>>>(N, maxtiles, BM, row_bytes, rng_start, rng_pre, rng_cnt, tiles, ntiles, krow, kstride);
   return hipGetLastError() == hipSuccess ? 0 : ADACLUSTER_E_INTERNAL;
 }
 
@@ -762,15 +875,15 @@ int launch_attention(hipStream_t s, int dtype, int d, int H, int N, int Cq, int 
                      const void* Q, const void* Kp, const void* Vp, void* O, const int32_t* perm_q,
                      const int32_t* tiles, const int32_t* ntiles, const int32_t* rng_start,
                      const int32_t* rng_pre, const int32_t* rng_cnt, float* part_o, float* part_ml,
-                     const int32_t* merge, const int32_t* nmerge) {
+                     const int32_t* merge, const int32_t* nmerge, const int32_t* krow, size_t kstride) {
   AttnArgs a{Q, Kp, Vp, O, perm_q, tiles, ntiles, rng_start, rng_pre, rng_cnt, N, Cq, maxtiles, maxr,
              scale * 1.4426950408889634f,
              (Cq == 1 || (size_t)4 * N * d <= ((size_t)8 << 20)) ? 1 : 0,
-             part_o, part_ml, SPLIT_SLOTS, attn_block_rows(dtype, d)};
+             part_o, part_ml, SPLIT_SLOTS, attn_block_rows(dtype, d), krow, kstride};
   dim3 g((maxtiles + 7) / 8 * 8, H);
   if (dtype == ADACLUSTER_BF16) {
-    if (d == 64) attn_mfma<64, A64_QB, A64_NW, A64_MINB><<<g, A64_NW * 64, 0, s>>>(a);
-    else attn_mfma<128, A128_QB, A128_NW, A128_MINB><<<g, A128_NW * 64, 0, s>>>(a);
+    if (d == 64) attn_mfma<64, A64_NW, A64_NBUF, A64_MINB, A64_VPRE><<<g, A64_NW * 64, 0, s>>>(a);
+    else attn_mfma<128, A128_NW, A128_NBUF, A128_MINB, A128_VPRE><<<g, A128_NW * 64, 0, s>>>(a);
     if (merge) {      // the chunks of cut key lists (none for the dense branch)
       if (d == 64) attn_merge<64><<<dim3(SPLIT_SLOTS, H), 256, 0, s>>>(a, merge, nmerge);
       else attn_merge<128><<<dim3(SPLIT_SLOTS, H), 256, 0, s>>>(a, merge, nmerge);

@@ -83,15 +83,18 @@ int launch_plan_sparse(hipStream_t s, int dtype, int H, int Cq, int cap, int max
                        const int32_t* q_offs, int q_offs_stride, const int32_t* k_offs, int k_offs_stride,
                        const int32_t* k_count, const int32_t* sel_idx, const int32_t* sel_cnt,
                        int32_t* rng_start, int32_t* rng_pre, int32_t* rng_cnt, int32_t* tiles, int32_t* ntiles,
-                       int32_t* merge, int32_t* nmerge);
+                       int32_t* merge, int32_t* nmerge, int row_bytes, int32_t* krow, size_t kstride);
 int launch_plan_dense(hipStream_t s, int H, int N, int maxtiles, int BM, int32_t* rng_start, int32_t* rng_pre,
-                      int32_t* rng_cnt, int32_t* tiles, int32_t* ntiles);
+                      int32_t* rng_cnt, int32_t* tiles, int32_t* ntiles, int row_bytes, int32_t* krow, size_t kstride);
+// entries per (head, query cluster) of the table of key-row byte offsets the bf16 attention kernel loads by
+size_t attn_krow_stride(int N);
 int launch_attn_stats(hipStream_t s, int H, int Cq, int maxr, int maxtiles, const KState* st, const int32_t* tiles,
                       const int32_t* ntiles, const int32_t* rng_pre, const int32_t* rng_cnt, adacluster_head_stats* out);
 int launch_attention(hipStream_t s, int dtype, int d, int H, int N, int Cq, int maxtiles, int maxr, float scale,
                      const void* Q, const void* Kp, const void* Vp, void* O, const int32_t* perm_q,
                      const int32_t* tiles, const int32_t* ntiles, const int32_t* rng_start,
                      const int32_t* rng_pre, const int32_t* rng_cnt, float* part_o, float* part_ml,
-                     const int32_t* merge /* NULL: no cut lists */, const int32_t* nmerge);
+                     const int32_t* merge /* NULL: no cut lists */, const int32_t* nmerge,
+                     const int32_t* krow, size_t kstride);
 
 }  // namespace adac
