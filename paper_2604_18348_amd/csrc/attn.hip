@@ -354,13 +354,15 @@ __device__ __forceinline__ void lds_barrier() {
 // XOR that keeps the operand reads of either tile free of bank conflicts (see swz_k, swz_v).  The rows of a tile come
 // from the row-offset table plan_sparse / plan_dense wrote: its 64 entries for a tile are themselves loaded
 // global -> LDS, 2*(NBUF-1) tiles ahead, so that no wave walks a range list and no load waits on a register.
-// LDS layout: [K ring: NBUF tiles][V ring: NBUF tiles][row offsets: NBUF x 64]; with the K tiles (and the V
-// tiles) side by side, a stage is reached from one set of address registers by an immediate offset (< 64 KB).
+// LDS layout: [row offsets: NBUF x 64][K ring: NBUF tiles][V ring: NBUF tiles]; with the K tiles (and the V
+// tiles) side by side, a stage is reached from one set of address registers by an immediate offset (< 64 KB;
+// the start of the V ring is part of the V address registers).
 template <int D, int NW, int NBUF, int MINB, int VPRE>
 __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
   constexpr int BN = 64, NT = NW * 64, KS = D / 16, DB = D / 32, CH = D / 8, ROWB = D * 2;
   constexpr int ITEMS = BN * CH, PT = ITEMS / NT, TILEB = BN * ROWB, PD = NBUF - 1;
   constexpr int VM_STEP = 2 * PT + 1;             // vector-memory operations a wave issues per tile
+  constexpr int RIDXB = NBUF * BN * 4;            // bytes of the row-offset slots at the start of LDS
   constexpr int KRING = NBUF * TILEB;             // bytes of the ring of K tiles (the ring of V tiles follows it)
   static_assert(ITEMS % NT == 0, "tile chunks must divide evenly over the threads");
   static_assert(NBUF == 2 || NBUF == 4, "two or four stages");
@@ -459,20 +461,20 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
     lswz_k[i] = ((item % CH) ^ swz_k(lrow[i])) * 16;
     lswz_v[i] = ((item % CH) ^ swz_v(lrow[i])) * 16;
   }
-  constexpr int RIDX0 = 2 * KRING;
-  __shared__ __attribute__((aligned(16))) char lds[2 * KRING + NBUF * BN * 4];
+  __shared__ __attribute__((aligned(16))) char lds[RIDXB + 2 * KRING];
+  char* const ldk = lds + RIDXB;                  // the K ring (compute_tile's V addresses carry KRING themselves)
   const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_void_t*)lds;
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   // the 64 row offsets of tile t go to the offsets slot of stage `st`, an equal share per wave
   const uint32_t ridx_voff = (uint32_t)((wave_u * (BN / NW) + (lane % (BN / NW))) * 4);
   auto issue_ridx = [&](int st, int t) __attribute__((always_inline)) {
     if (lane < BN / NW)
-      dma_b32(lds0 + RIDX0 + st * (BN * 4) + wave_u * (BN / NW) * 4, (uint32_t)(t * (BN * 4)) + ridx_voff, krow);
+      dma_b32(lds0 + st * (BN * 4) + wave_u * (BN / NW) * 4, ridx_voff, krow + (size_t)t * BN);
   };
   auto issue_tile = [&](int st, const int32_t* off) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
-      const uint32_t dst = lds0 + st * TILEB + (wave_u * 64 + i * NT) * 16;     // wave-uniform; the lane offset is implicit
+      const uint32_t dst = lds0 + RIDXB + st * TILEB + (wave_u * 64 + i * NT) * 16;     // wave-uniform; the lane offset is implicit
       dma_b128(dst, (uint32_t)off[i] + (uint32_t)lswz_k[i], Kh);
       dma_b128(dst + KRING, (uint32_t)off[i] + (uint32_t)lswz_v[i], Vh);
     }
@@ -588,6 +590,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
       probabilities();
     }
     lrun += rsum;
+    asm volatile("" ::: "memory");          // the V operands that were not requested ahead are requested from here on
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
       bf16x8_t vb[2][2];
@@ -623,10 +626,10 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
     constexpr int U = decltype(stage)::value, G = (U + PD) % NBUF;
     int32_t off[PT];
 #pragma unroll
-    for (int i = 0; i < PT; ++i) off[i] = reinterpret_cast<const int32_t*>(lds + RIDX0 + U * (BN * 4))[lrow[i]];
+    for (int i = 0; i < PT; ++i) off[i] = reinterpret_cast<const int32_t*>(lds + U * (BN * 4))[lrow[i]];
     issue_tile(G, off);
     issue_ridx(G, t + 2 * PD);
-    if (wave_has_rows) compute_tile(lds + U * TILEB, lds + U * TILEB, BN, std::false_type{});
+    if (wave_has_rows) compute_tile(ldk + U * TILEB, ldk + U * TILEB, BN, std::false_type{});
     wait_vmcnt<(PD - 1) * VM_STEP>();
     lds_barrier();
   };
@@ -664,7 +667,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
     }
     wait_vmcnt<0>();       // nothing of this wave is still on its way to LDS when it ends
     const int u = Tlast % NBUF;
-    if (wave_has_rows) compute_tile(lds + u * TILEB, lds + u * TILEB, total - Tlast * BN, std::true_type{});
+    if (wave_has_rows) compute_tile(ldk + u * TILEB, ldk + u * TILEB, total - Tlast * BN, std::true_type{});
   }
 
   // O^T accumulator value v of block db is column  db*32 + 8*(v/4) + 4*hb + v%4  of query c
@@ -841,7 +844,7 @@ __global__ __launch_bounds__(256) void attn_merge(AttnArgs a, const int32_t* __r
 #define A64_VPRE 0
 #endif
 #ifndef A128_VPRE
-#define A128_VPRE 4
+#define A128_VPRE 2
 #endif
 
 int attn_block_rows(int dtype, int d) {
