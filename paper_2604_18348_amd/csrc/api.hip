@@ -192,7 +192,7 @@ struct WS {
 };
 
 struct Dims {
-  int H, N, d, Cq, cap, capmax, nblk, nseg, maxtiles, maxr, prow, brow, BM;
+  int H, N, d, Cq, cap, capmax, nblk, nseg, maxtiles, maxr, prow, brow, BM, BMmax;
 };
 
 Dims dims_of(const adacluster_params* p) {
@@ -201,8 +201,9 @@ Dims dims_of(const adacluster_params* p) {
   D.capmax = D.cap > D.Cq ? D.cap : D.Cq;
   D.nblk = (p->N + 1023) / 1024;
   D.nseg = (p->N + 511) / 512;
-  D.BM = attn_block_rows(p->dtype, p->d);
-  D.maxtiles = p->N / D.BM + D.Cq + 1 + attn_split_slots();
+  D.BM = attn_block_rows(p->dtype, p->d, p->N, D.Cq);
+  D.BMmax = attn_block_rows_max(p->dtype);
+  D.maxtiles = p->N / attn_block_rows_min(p->dtype) + D.Cq + 1 + attn_split_slots();   // (sized for the smaller tile shape)
   D.maxr = D.cap;
   D.prow = p->N / 128 + D.capmax + 34;
   {  // rows of the block-sum table of small stages: (blocks of 256 points) x (centres), both capped
@@ -264,8 +265,8 @@ size_t layout(const adacluster_params* p, WS* w, unsigned char* base) {
   TAKE(tiles, int32_t*, H * (size_t)D.maxtiles * 6 * 4);
   TAKE(merge, int32_t*, H * (size_t)attn_split_slots() * 4 * 4);
   TAKE(nmerge, int32_t*, H * 4);
-  TAKE(part_o, float*, H * (size_t)attn_split_slots() * D.BM * d * 4);
-  TAKE(part_ml, float*, H * (size_t)attn_split_slots() * D.BM * 2 * 4);
+  TAKE(part_o, float*, H * (size_t)attn_split_slots() * D.BMmax * d * 4);
+  TAKE(part_ml, float*, H * (size_t)attn_split_slots() * D.BMmax * 2 * 4);
   TAKE(ntiles, int32_t*, H * 4);
   TAKE(krow, int32_t*, p->dtype == ADACLUSTER_BF16 ? H * (size_t)D.Cq * attn_krow_stride(D.N) * 4 : 256);
   TAKE(q_labels, int32_t*, H * N * 4);
@@ -737,7 +738,7 @@ int adacluster_dense_attn(const adacluster_params* p, const void* Q, const void*
   hipStream_t st = (hipStream_t)stream;
   const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)D.d);
   prof_begin(st);
-  RET_IF(launch_plan_dense(st, D.H, D.N, D.maxtiles, D.BM, w.rng_start, w.rng_pre, w.rng_cnt, w.tiles, w.ntiles,
+  RET_IF(launch_plan_dense(st, D.H, D.N, D.maxtiles, attn_block_rows(p->dtype, D.d, D.N, 1), w.rng_start, w.rng_pre, w.rng_cnt, w.tiles, w.ntiles,
                            D.d * (int)esize(p), p->dtype == ADACLUSTER_BF16 ? w.krow : nullptr, attn_krow_stride(D.N)));
   prof_mark(EV_PLAN, st);
   RET_IF(launch_attention(st, p->dtype, D.d, D.H, D.N, 1, D.maxtiles, 1, scale, Q, K, V, O, nullptr, w.tiles,

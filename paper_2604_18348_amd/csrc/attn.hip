@@ -847,10 +847,17 @@ __global__ __launch_bounds__(256) void attn_merge(AttnArgs a, const int32_t* __r
 #define A128_VPRE 2
 #endif
 
-int attn_block_rows(int dtype, int d) {
+// Queries per workgroup.  The bf16 kernel comes in two shapes: eight waves (256 queries, a ring of four stages),
+// and four waves (128 queries, two stages, twice the workgroups per CU) for query clusters too small to fill
+// the first without long tails (a cluster of 273 queries is 256 + 17 in one shape, 128 + 128 + 17 in the other).
+static bool attn_small_shape(int N, int Cq) { return Cq > 1 && N / Cq < 768; }
+int attn_block_rows(int dtype, int d, int N, int Cq) {
   if (dtype != ADACLUSTER_BF16) return 64;
+  if (attn_small_shape(N, Cq)) return 128;
   return d == 64 ? A64_NW * 32 : A128_NW * 32;
 }
+int attn_block_rows_min(int dtype) { return dtype == ADACLUSTER_BF16 ? 128 : 64; }
+int attn_block_rows_max(int dtype) { return dtype == ADACLUSTER_BF16 ? 256 : 64; }
 
 size_t attn_krow_stride(int N) { return (size_t)(N + 63) / 64 * 64 + KROW_PAD; }
 
@@ -882,11 +889,16 @@ int launch_attention(hipStream_t s, int dtype, int d, int H, int N, int Cq, int 
   AttnArgs a{Q, Kp, Vp, O, perm_q, tiles, ntiles, rng_start, rng_pre, rng_cnt, N, Cq, maxtiles, maxr,
              scale * 1.4426950408889634f,
              (Cq == 1 || (size_t)4 * N * d <= ((size_t)8 << 20)) ? 1 : 0,
-             part_o, part_ml, SPLIT_SLOTS, attn_block_rows(dtype, d), krow, kstride};
+             part_o, part_ml, SPLIT_SLOTS, attn_block_rows(dtype, d, N, Cq), krow, kstride};
   dim3 g((maxtiles + 7) / 8 * 8, H);
   if (dtype == ADACLUSTER_BF16) {
-    if (d == 64) attn_mfma<64, A64_NW, A64_NBUF, A64_MINB, A64_VPRE><<<g, A64_NW * 64, 0, s>>>(a);
-    else attn_mfma<128, A128_NW, A128_NBUF, A128_MINB, A128_VPRE><<<g, A128_NW * 64, 0, s>>>(a);
+    if (attn_small_shape(N, Cq)) {
+      if (d == 64) attn_mfma<64, 4, 2, 4, 0><<<g, 256, 0, s>>>(a);
+      else attn_mfma<128, 4, 2, 2, 2><<<g, 256, 0, s>>>(a);
+    } else {
+      if (d == 64) attn_mfma<64, A64_NW, A64_NBUF, A64_MINB, A64_VPRE><<<g, A64_NW * 64, 0, s>>>(a);
+      else attn_mfma<128, A128_NW, A128_NBUF, A128_MINB, A128_VPRE><<<g, A128_NW * 64, 0, s>>>(a);
+    }
     if (merge) {      // the chunks of cut key lists (none for the dense branch)
       if (d == 64) attn_merge<64><<<dim3(SPLIT_SLOTS, H), 256, 0, s>>>(a, merge, nmerge);
       else attn_merge<128><<<dim3(SPLIT_SLOTS, H), 256, 0, s>>>(a, merge, nmerge);

@@ -71,7 +71,9 @@ int launch_select(hipStream_t s, int H, int Cq, int cap, int d, int score_mode, 
                   const float* k_bmin, const float* k_bmax, const int32_t* k_sizes, const int32_t* k_count,
                   const int32_t* full_flag, int32_t* sel_idx, int32_t* sel_cnt, int kc_max);
 
-int attn_block_rows(int dtype, int d);
+int attn_block_rows(int dtype, int d, int N, int Cq);   // queries per workgroup of the attention launch
+int attn_block_rows_min(int dtype);
+int attn_block_rows_max(int dtype);
 int launch_permute_kv(hipStream_t s, int H, int N, int row_bytes, const void* K, const void* V,
                       const int32_t* perm, void* Kp, void* Vp);
 int launch_quest_scores(hipStream_t s, int dtype, int form, int clamp, int H, int Lq, int Lk, int d, const void* Q,
