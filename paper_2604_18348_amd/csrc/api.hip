@@ -179,6 +179,7 @@ struct WS {
   int32_t* perm_q; int32_t* offs_q; int32_t* perm_k; int32_t* offs_k;
   // scratch of the query clustering (its own set: it runs beside the key clustering)
   void* q_cent_lp; float* q_bias; SortScratch q_sort; int32_t* q_poff; float* q_psum; float* q_pnorm;
+  float* q_wsum; int32_t* q_wcnt;     // walk sums and counts of the one-read passes of the query clustering
   void* Kp; void* Vp;
   int32_t* rng_start; int32_t* rng_pre; int32_t* rng_cnt; int32_t* tiles; int32_t* ntiles;
   int32_t* merge; int32_t* nmerge; float* part_o; float* part_ml;   // cut key lists of the attention step
@@ -253,6 +254,11 @@ size_t layout(const adacluster_params* p, WS* w, unsigned char* base) {
   TAKE(q_poff, int32_t*, H * (size_t)(D.Cq + 1) * 4);
   TAKE(q_psum, float*, H * (size_t)(N / 128 + D.Cq + 34) * d * 4);
   TAKE(q_pnorm, float*, H * (size_t)(N / 128 + D.Cq + 34) * 4);
+  {
+    const bool one_read = p->dtype == ADACLUSTER_BF16 && D.Cq <= assign_block_sum_centres();
+    TAKE(q_wsum, float*, one_read ? H * (size_t)D.Cq * qpass_walks(D.N) * d * 4 : 256);
+    TAKE(q_wcnt, int32_t*, one_read ? H * (size_t)qpass_walks(D.N) * assign_block_sum_centres() * 4 : 256);
+  }
   TAKE(perm_q, int32_t*, H * N * 4);
   TAKE(offs_q, int32_t*, H * (size_t)(D.Cq + 1) * 4);
   TAKE(perm_k, int32_t*, H * N * 4);
@@ -311,7 +317,19 @@ int run_qcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
   const int sph = p->q_no_norm ? 0 : 1;      // by angle on q/|q| (the paper), or Euclidean on raw queries (ablation)
   RET_IF(launch_init_centroids(st, p->dtype, D.d, D.H, D.N, 0, D.Cq, D.Cq, nullptr, nullptr, sph, p->q_init_mode,
                                D.Cq, D.Cq, Q, q_centroids, w.q_cent_lp, q_assign, w.q_bias));
+  // A pass that only updates the centres reads the queries once: assignment and (normalised) sums in one
+  // kernel.  The last pass needs the labels sorted (for the attention step) and exact member statistics, and
+  // takes the sort and the segmented reduction.
+  const bool one_read = p->dtype == ADACLUSTER_BF16 && D.Cq <= assign_block_sum_centres();
   for (int it = 0; it < p->q_iters; ++it) {
+    if (one_read && it < p->q_iters - 1) {
+      const int NP = qpass_walks(D.N);
+      RET_IF(launch_qpass(st, D.d, D.H, D.N, D.Cq, D.Cq, sph, Q, w.q_cent_lp, w.q_bias, w.q_wsum, w.q_wcnt));
+      RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 0, D.Cq, D.Cq, D.Cq * NP, D.Cq, D.Cq, nullptr, sph, 1, 0, nullptr, 0,
+                             nullptr, w.q_wsum, w.q_pnorm, nullptr, nullptr, q_centroids, w.q_cent_lp, q_assign, w.q_bias,
+                             nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, w.q_wcnt, NP, NP));
+      continue;
+    }
     RET_IF(launch_assign(st, p->dtype, D.d, D.H, D.N, D.N, 0, D.Cq, D.Cq, nullptr, nullptr, Q, w.q_cent_lp, w.q_bias,
                          q_labels, nullptr));
     RET_IF(launch_sort(st, D.H, D.N, D.N, D.Cq, q_labels, nullptr, nullptr, 0, nullptr, 0, nullptr, 0, w.perm_q,

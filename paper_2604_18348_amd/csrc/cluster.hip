@@ -322,6 +322,196 @@ __global__ __launch_bounds__(256, (ACC && D == 128) ? 1 : 2) void assign_mfma(co
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// One pass of the query k-means in ONE read of the points: assignment and centroid sums together.
+// ------------------------------------------------------------------------------------------
+// A workgroup walks `subs` consecutive sub-blocks of 128 points.  Per sub-block every wave assigns its 32
+// points to the nearest of the m <= 128 centres (all of them resident in LDS; the same MFMA product and in-lane
+// arg-max as assign_mfma), then the sub-block's points, labels and weights go through LDS and every wave adds
+//   S^T[32 dims x 32 centres] += X^T[32 dims x 16 points] . E[16 points x 32 centres]
+// to the accumulator tiles it owns for the WHOLE walk (wave w: centre tile w in every dim tile).  E is the one-hot label matrix times the point's weight: 1 for Euclidean sums, and for the
+// clustering by angle the bf16 value of 1/|x|, so that the tile holds the sum of the (almost) normalised
+// members; the weight's rounding (2^-9 relative per member, of random sign) is far below the bf16 rounding the
+// centres of the next assignment get anyway.  Products are exact, the accumulation is fp32 in a fixed order,
+// so the pass is deterministic.  Walk b of head h leaves row j * NP + b of the head's part-sum table
+// psum [H][m * NP][D] and pcnt[(h * NP + b) * ACC_MAXM + j]; finalize_centroids adds the walks in order.
+// No label is written: only the last pass of a clustering needs labels, and that one takes the sorted path.
+template <int D>
+__global__ __launch_bounds__(256, 2) void qpass_mfma(const bf16raw* __restrict__ X, int N, int m, int cap, int subs,
+                                                     int weighted, const bf16raw* __restrict__ cent,
+                                                     const float* __restrict__ bias, float* __restrict__ psum,
+                                                     int32_t* __restrict__ pcnt, int NP) {
+  constexpr int KS = D / 16, DT = D / 32, ROWB = D * 2, CH = D / 8, SB = 128, MAXCT = ACC_MAXM / 32;
+  const int h = blockIdx.y, b = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = lane & 31, hb = lane >> 5;
+  const int CT = (m + 31) >> 5;
+  __shared__ __attribute__((aligned(16))) char cs[MAXCT * 32 * ROWB];     // the centres, rows permuted by chunk
+  __shared__ __attribute__((aligned(16))) float bs[MAXCT * 32];
+  __shared__ __attribute__((aligned(16))) bf16raw xs[SB * D];             // the sub-block's points, row-major
+  __shared__ __attribute__((aligned(16))) int32_t lab_s[SB];
+  __shared__ __attribute__((aligned(16))) uint32_t w_s[SB];               // weight of a point as bf16 bits
+  __shared__ int32_t cnt_s[ACC_MAXM];
+  auto swz = [](int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); };
+  {
+    const bf16raw* chh = cent + (size_t)h * cap * D;
+    for (int item = tid; item < CT * 32 * CH; item += 256) {
+      const int r = item / CH, sl = item % CH;
+      const int row = min(r, m - 1);                                      // rows past m repeat the last centre under a bias that never wins
+      *reinterpret_cast<uint4*>(cs + r * ROWB + ((sl ^ swz(r)) * 16)) =
+          *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(chh) + (size_t)row * ROWB + sl * 16);
+    }
+    if (tid < MAXCT * 32) { bs[tid] = tid < m ? bias[(size_t)h * cap + tid] : -3.0e38f; cnt_s[tid] = 0; }
+  }
+  int kaddr[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) kaddr[ks] = c * ROWB + (((ks * 2 + hb) ^ swz(c)) * 16);
+  // Wave w owns centre tile w (there are at most four) in all its dim tiles: the one-hot operand of a group
+  // of 16 points (about twenty vector instructions, more than one product costs) is built once per group
+  // and serves every dim tile.
+  f32x16_t sacc[DT];
+#pragma unroll
+  for (int k = 0; k < DT; ++k)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) sacc[k][v] = 0.f;
+  // X^T operand by transpose reads (as the V operand of the attention kernel): this lane addresses point
+  // 4*hb + (lane%16)/4 of a 16-point group, dims 16*((lane/16)%2) + 4*(lane%4) .. +3
+  const int i16 = lane & 15, blk = lane >> 4;
+  const int vrow = 4 * hb + (i16 >> 2);
+  const int gl = 2 * (blk & 1) + ((i16 & 3) >> 1);
+  // Piece q (16 bytes) of point row r sits in slot q ^ xswz(r): a bijection over 16 consecutive rows (the
+  // row-wise 16-byte writes of 16 lanes fall into 16 different bank groups) that also sends the four rows
+  // of one transpose read to four different 64-byte groups.
+  auto xswz = [](int r) { return D == 128 ? (((r & 3) << 2) | ((r >> 2) & 3)) : (((((r >> 1) & 7) & 1) << 2) | (((r >> 1) & 7) >> 1)); };
+  int xlo[DT], xhi[DT];
+#pragma unroll
+  for (int db = 0; db < DT; ++db) {
+    xlo[db] = vrow * ROWB + (((db * 4 + gl) ^ xswz(vrow)) * 16) + 8 * (i16 & 1);
+    xhi[db] = (vrow + 8) * ROWB + (((db * 4 + gl) ^ xswz(vrow + 8)) * 16) + 8 * (i16 & 1);
+  }
+  const char* xsb = reinterpret_cast<const char*>(xs);
+
+  const int p_begin = b * subs * SB;
+  const bf16raw* Xh = X + (size_t)h * N * D;
+  auto load_rows = [&](int base, bf16x8_t* xf) {
+    const int pos = base + wave * 32 + c;
+    if (pos < N) {
+      const bf16raw* row = Xh + (size_t)pos * D + hb * 8;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) { const uint4 raw = *reinterpret_cast<const uint4*>(row + ks * 16); xf[ks] = *reinterpret_cast<const bf16x8_t*>(&raw); }
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) { const uint4 z = {0, 0, 0, 0}; xf[ks] = *reinterpret_cast<const bf16x8_t*>(&z); }
+    }
+  };
+  bf16x8_t xnext[KS];
+  load_rows(p_begin, xnext);
+  __syncthreads();                       // centres, bias and counters are in LDS
+  for (int sb = 0; sb < subs; ++sb) {
+    const int base = p_begin + sb * SB;
+    if (base >= N) break;
+    bf16x8_t xf[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) xf[ks] = xnext[ks];
+    if (sb + 1 < subs) load_rows(base + SB, xnext);          // the next sub-block's rows travel under this one's arithmetic
+    const int pos = base + wave * 32 + c;
+    // squared norm of this lane's point (both half-waves hold half of the row)
+    float ss = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const uint4 raw = *reinterpret_cast<const uint4*>(&xf[ks]);
+      const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float a = __uint_as_float(w[q] << 16), bb = __uint_as_float(w[q] & 0xFFFF0000u);
+        ss = fmaf(a, a, ss); ss = fmaf(bb, bb, ss);
+      }
+    }
+    ss += __shfl_xor(ss, 32);
+    // assignment: arg-max of x.c + bias over the centre tiles, position in a tile carried in the low 4 mantissa bits
+    float best = -INFINITY; int btile = 0;
+    for (int ct = 0; ct < CT; ++ct) {
+      f32x16_t acc;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float4 b4 = *reinterpret_cast<const float4*>(&bs[ct * 32 + 8 * i + 4 * hb]);
+        acc[4 * i + 0] = b4.x; acc[4 * i + 1] = b4.y; acc[4 * i + 2] = b4.z; acc[4 * i + 3] = b4.w;
+      }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(cs + ct * 32 * ROWB + kaddr[ks]);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xf[ks], acc, 0, 0, 0);
+      }
+      float pk[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) pk[v] = __uint_as_float((__float_as_uint(acc[v]) & 0xFFFFFFF0u) | (uint32_t)(15 - v));
+      float tm = fmaxf(fmaxf(pk[0], pk[1]), pk[2]);
+#pragma unroll
+      for (int v = 3; v < 15; v += 2) tm = fmaxf(fmaxf(tm, pk[v]), pk[v + 1]);
+      tm = fmaxf(tm, pk[15]);
+      if (tm > best) { best = tm; btile = ct; }
+    }
+    {
+      const int v = 15 - (int)(__float_as_uint(best) & 15u);
+      int bidx = btile * 32 + 8 * (v >> 2) + 4 * hb + (v & 3);
+      float bv = __uint_as_float(__float_as_uint(best) & 0xFFFFFFF0u);
+      const float ob = __shfl_xor(bv, 32);
+      const int oi = __shfl_xor(bidx, 32);
+      if (ob > bv || (ob == bv && oi < bidx)) { bv = ob; bidx = oi; }
+      const int pr = wave * 32 + c;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        *reinterpret_cast<bf16x8_t*>(reinterpret_cast<char*>(xs) + pr * ROWB + (((ks * 2 + hb) ^ xswz(pr)) * 16)) = xf[ks];
+      if (hb == 0) {
+        const bool valid = pos < N;
+        lab_s[pr] = valid ? bidx : -1;
+        w_s[pr] = weighted ? (uint32_t)f32_to_bf16(1.0f / fmaxf(sqrtf(ss), 1e-12f)) : 0x3F80u;
+        if (valid) atomicAdd(&cnt_s[bidx], 1);
+      }
+    }
+    __syncthreads();
+    // sums: the owned centre tile takes the eight 16-point groups of the sub-block
+    if (wave < CT) {
+      const int cid = wave * 32 + c;
+#pragma unroll 2
+      for (int g = 0; g < SB / 16; ++g) {
+        const int4 l0 = *reinterpret_cast<const int4*>(&lab_s[g * 16 + 4 * hb]);
+        const int4 l1 = *reinterpret_cast<const int4*>(&lab_s[g * 16 + 8 + 4 * hb]);
+        const uint4 w0 = *reinterpret_cast<const uint4*>(&w_s[g * 16 + 4 * hb]);
+        const uint4 w1 = *reinterpret_cast<const uint4*>(&w_s[g * 16 + 8 + 4 * hb]);
+        uint4 e;
+        e.x = (l0.x == cid ? w0.x : 0u) | (l0.y == cid ? w0.y << 16 : 0u);
+        e.y = (l0.z == cid ? w0.z : 0u) | (l0.w == cid ? w0.w << 16 : 0u);
+        e.z = (l1.x == cid ? w1.x : 0u) | (l1.y == cid ? w1.y << 16 : 0u);
+        e.w = (l1.z == cid ? w1.z : 0u) | (l1.w == cid ? w1.w << 16 : 0u);
+        const bf16x8_t eb = *reinterpret_cast<const bf16x8_t*>(&e);
+#pragma unroll
+        for (int db = 0; db < DT; ++db) {
+          const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(xsb + g * 16 * ROWB + xlo[db]));
+          const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(xsb + g * 16 * ROWB + xhi[db]));
+          const s16x4_t both[2] = {lo, hi};
+          sacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t*>(both), eb, sacc[db], 0, 0, 0);
+        }
+      }
+    }
+    __syncthreads();                     // the sub-block's points and labels may be overwritten
+  }
+  // value v of dim tile db is dim db*32 + 8*(v/4) + 4*hb + v%4 of centre cid
+  if (wave < CT && wave * 32 + c < m) {
+    const int cid = wave * 32 + c;
+#pragma unroll
+    for (int db = 0; db < DT; ++db) {
+      float* out = psum + ((size_t)h * m * NP + (size_t)cid * NP + b) * D + db * 32 + 4 * hb;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float4 o4 = {sacc[db][4 * i], sacc[db][4 * i + 1], sacc[db][4 * i + 2], sacc[db][4 * i + 3]};
+        *reinterpret_cast<float4*>(out + 8 * i) = o4;
+      }
+    }
+  }
+  if (tid < m) pcnt[((size_t)h * NP + b) * ACC_MAXM + tid] = cnt_s[tid];
+}
+
 // fp32 I/O: one point per thread, centre chunks broadcast from LDS.
 template <int D>
 __global__ __launch_bounds__(128) void assign_f32(const float* __restrict__ X, AssignCfg cfg,
@@ -588,6 +778,7 @@ struct FinalizeCfg {
   const KState* st;
   int spherical; int update_assign; int lp_is_bf16; int want_box;
   const int32_t* bcnt; int nb_stride;     // block sums of the assignment kernel instead of cluster parts (stage mode)
+  int nb_const;                           // > 0: that many blocks (walks of the one-read query pass), whatever the state says
 };
 
 template <int D>
@@ -618,7 +809,7 @@ __global__ __launch_bounds__(64) void finalize_centroids(FinalizeCfg cfg, const 
   int nj, p_beg, p_end;
   if (cfg.bcnt) {
     // the blocks of 256 points of the assignment kernel, in block order
-    const int nb = (cfg.st[h].ucount + 255) >> 8;
+    const int nb = cfg.nb_const > 0 ? cfg.nb_const : (cfg.st[h].ucount + 255) >> 8;
     nj = 0;
     for (int b = lane; b < nb; b += 64) nj += cfg.bcnt[((size_t)h * cfg.nb_stride + b) * ACC_MAXM + j];
 #pragma unroll
@@ -634,7 +825,7 @@ __global__ __launch_bounds__(64) void finalize_centroids(FinalizeCfg cfg, const 
   for (int q = 0; q < CPL; ++q) { s[q] = 0.f; mn[q] = INFINITY; mx[q] = -INFINITY; }
   float ns = 0.f;
   int p = p_beg;
-  if (!cfg.want_box && !cfg.spherical) {
+  if (!cfg.want_box && (!cfg.spherical || cfg.update_assign)) {
     // sums only: eight parts' loads in flight, added in part order all the same
     for (; p + 8 <= p_end; p += 8) {
       float t[8][CPL];
@@ -657,7 +848,7 @@ __global__ __launch_bounds__(64) void finalize_centroids(FinalizeCfg cfg, const 
         mx[q] = fmaxf(mx[q], pmax[(pbase + p) * D + lane + 64 * q]);
       }
     }
-    if (cfg.spherical) ns += pnorm[pbase + p];
+    if (cfg.spherical && !cfg.update_assign) ns += pnorm[pbase + p];     // (member norms matter to the final outputs only)
   }
   bool ok = nj > 0;
   float val[CPL];
@@ -1484,6 +1675,17 @@ int launch_assign(hipStream_t s, int dtype, int d, int H, int N, int n_bound, in
   return chk();
 }
 
+// one-read pass of the query clustering (bf16, at most assign_block_sum_centres() centres): NP = walks per head
+int qpass_walks(int N) { const int sb = (N + 127) / 128; const int subs = (sb + 63) / 64; return (sb + subs - 1) / subs; }
+int launch_qpass(hipStream_t s, int d, int H, int N, int m, int cap, int weighted, const void* X, const void* cent_lp,
+                 const float* bias, float* psum, int32_t* pcnt) {
+  const int sb = (N + 127) / 128, subs = (sb + 63) / 64, NP = (sb + subs - 1) / subs;
+  dim3 g(NP, H);
+  if (d == 64) qpass_mfma<64><<<g, 256, 0, s>>>((const bf16raw*)X, N, m, cap, subs, weighted, (const bf16raw*)cent_lp, bias, psum, pcnt, NP);
+  else qpass_mfma<128><<<g, 256, 0, s>>>((const bf16raw*)X, N, m, cap, subs, weighted, (const bf16raw*)cent_lp, bias, psum, pcnt, NP);
+  return chk();
+}
+
 int launch_seg_reduce(hipStream_t s, int dtype, int d, int H, int N, int mode, int m_const, int m_bound, int P,
                       const KState* st, int normalize, int want_box, const void* X, const int32_t* perm,
                       const int32_t* offs, int offs_stride, int32_t* poff, float* psum, float* pnorm, float* pmin,
@@ -1506,9 +1708,10 @@ int launch_finalize(hipStream_t s, int dtype, int d, int H, int mode, int m_cons
                     const int32_t* offs, int offs_stride, const int32_t* poff, const float* psum, const float* pnorm,
                     const float* pmin, const float* pmax, float* master, void* assign_lp, float* assign_f32,
                     float* bias, float* out_cent, const float* fallback, int32_t* out_sizes,
-                    float* out_mean_norm, float* out_bmin, float* out_bmax, const int32_t* blk_cnt, int nb_stride) {
+                    float* out_mean_norm, float* out_bmin, float* out_bmax, const int32_t* blk_cnt, int nb_stride,
+                    int nb_const) {
   FinalizeCfg c{mode, m_const, P, m_bound, cap, master_stride, st, spherical, update_assign,
-                dtype == ADACLUSTER_BF16, want_box, blk_cnt, nb_stride};
+                dtype == ADACLUSTER_BF16, want_box, blk_cnt, nb_stride, nb_const};
   // in final mode every row of the output (up to cap) gets a size, so cover cap rows
   dim3 g(update_assign ? m_bound : cap, H);
   if (d == 64)

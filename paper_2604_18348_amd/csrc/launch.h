@@ -37,7 +37,13 @@ int launch_finalize(hipStream_t s, int dtype, int d, int H, int mode, int m_cons
                     const float* pmin, const float* pmax, float* master, void* assign_lp, float* assign_f32,
                     float* bias, float* out_cent, const float* fallback, int32_t* out_sizes,
                     float* out_mean_norm, float* out_bmin, float* out_bmax, const int32_t* blk_cnt = nullptr,
-                    int nb_stride = 0);
+                    int nb_stride = 0, int nb_const = 0);
+// One pass of a k-means with at most assign_block_sum_centres() centres in one read of the points (bf16):
+// assignment and (weighted) centroid sums together.  psum [H][m * NP][d], pcnt [H][NP][assign_block_sum_centres()]
+// with NP = qpass_walks(N); launch_finalize(..., blk_cnt = pcnt, nb_stride = NP, nb_const = NP) turns them into centres.
+int qpass_walks(int N);
+int launch_qpass(hipStream_t s, int d, int H, int N, int m, int cap, int weighted, const void* X, const void* cent_lp,
+                 const float* bias, float* psum, int32_t* pcnt);
 int launch_init_centroids(hipStream_t s, int dtype, int d, int H, int N, int mode, int m_const, int m_bound,
                           const KState* st, const int32_t* ulist, int spherical, int source_master, int cap,
                           int master_stride, const void* X, float* master, void* assign_lp, float* assign_f32,

@@ -62,6 +62,35 @@ def test_qcluster_chained(dtype, d, N, Cq):
             assert math.isclose(mn[h, j], qn[lab[h] == j].mean(), rel_tol=1e-5)
 
 
+@pytest.mark.parametrize("d,N,Cq", [(64, 3000, 17), (128, 2511, 65), (64, 16400, 33), (128, 20000, 128), (64, 700, 1),
+                                    (128, 130, 128)])
+def test_qcluster_update_from_one_read(d, N, Cq):
+    """bf16, at most 128 clusters: every iteration but the last assigns and sums the members in the same
+    pass over Q.  With q_iters = 2 the centres the labels refer to are the result of one such pass from
+    the strided start (Alg. 3 line 1): compared with the oracle's first update, rounded to bf16.
+    Arithmetic on the device: weights 1/|q| rounded to bf16 (relative error 2^-9 per point, averaging
+    out over the members), fp32 sums, one bf16 rounding of the result -> one bf16 step."""
+    H = 2
+    Q, _, _ = wl.make_small(17, N, d, 10, dtype="bf16", H=H)
+    p = B.Params(H=H, N=N, d=d, dtype=B.BF16, q_clusters=Cq, q_iters=2, k_m0=4, k_m_min=1, k_max_clusters=8)
+    out = B.adacluster_qcluster(p, to_dev(Q, B.BF16))
+    torch.cuda.synchronize()
+    ca = to_np(out["q_assign_centroids"])
+    rep = to_np(B.adacluster_qcluster(p, to_dev(Q, B.BF16))["q_assign_centroids"])
+    assert np.array_equal(ca, rep)                                   # no order-dependent sums
+    for h in range(H):
+        ref = orc.query_kmeans(Q[h], Cq, 2, round_fn=orc.round_to_bf16)["assign_centroids"]
+        # one bf16 step at the size of the entry; entries far below the typical size 1/sqrt(d) of a unit
+        # vector's components are sums of cancelling terms of that size, whose weight errors do not cancel
+        step = 2.0 ** -8 * np.maximum(np.abs(ref), d ** -0.5)
+        diff = np.abs(ca[h] - ref)
+        within = float((diff <= step).mean())
+        print("one-read update", d, N, Cq, "within one step", within, "max steps", float((diff / step).max()))
+        # a query within rounding of two centres may sit in the other cluster on the device: it moves two
+        # centres by about 1/n_members each, so a few entries may be one more step off
+        assert within >= 0.99 and float((diff / step).max()) <= 3.0
+
+
 @pytest.mark.parametrize("dtype,d,N,Cq", [(B.BF16, 64, 3000, 17), (B.F32, 128, 900, 9)])
 def test_qcluster_without_normalisation_chained(dtype, d, N, Cq):
     """q_no_norm = 1 (component ablation "w/o Norm"): Euclidean k-means on the raw queries.  Labels are
