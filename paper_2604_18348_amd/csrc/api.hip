@@ -710,10 +710,13 @@ int adacluster_attn(const adacluster_params* p, const void* Q, const void* K, co
   prof_begin(st);
   if (hipEventRecord(aux->fork, st) != hipSuccess || hipStreamWaitEvent(aux->s, aux->fork, 0) != hipSuccess)
     return fail(ADACLUSTER_E_INTERNAL, "stream fork failed: %s", hipGetErrorString(hipGetLastError()));
+  // From here on work may sit on the second stream.  No error leaves this function with that work still
+  // running: where the event join itself fails (or an error comes after the join of the first fork), the
+  // host waits for the second stream before it reports the error.
+  auto drained = [&](int code) { (void)hipStreamSynchronize(aux->s); return code; };
   rc = run_qcluster(p, w, aux->s, Q, q_labels, q_centroids, q_assign_centroids, q_sizes, q_mean_norm);
   prof_mark(EV_QCLUSTER, aux->s, EV_START);
-  // join before any return: the caller's stream must not run ahead of work queued on the second one
-  if (hipEventRecord(aux->join, aux->s) != hipSuccess) return fail(ADACLUSTER_E_INTERNAL, "stream join failed");
+  if (hipEventRecord(aux->join, aux->s) != hipSuccess) return drained(fail(ADACLUSTER_E_INTERNAL, "stream join failed"));
   int kc_bound = capacity(p);
   int rck = rc ? 0 : run_kcluster(p, w, st, K, k_labels, k_centroids, k_assign_centroids, k_bmin, k_bmax, k_sizes,
                                    k_count, full_flag, o.k_stage_offs, o.k_stage_of, tau_used, &kc_bound, aux->fork);
@@ -725,24 +728,27 @@ int adacluster_attn(const adacluster_params* p, const void* Q, const void* K, co
   int rcp = 0;
   if (fork2) {
     if (hipStreamWaitEvent(aux->s, aux->fork, 0) != hipSuccess)
-      return fail(ADACLUSTER_E_INTERNAL, "stream fork failed: %s", hipGetErrorString(hipGetLastError()));
+      return drained(fail(ADACLUSTER_E_INTERNAL, "stream fork failed: %s", hipGetErrorString(hipGetLastError())));
     rcp = run_permute(p, w, aux->s, K, V, EV_KSORT);
-    if (hipEventRecord(aux->join2, aux->s) != hipSuccess) return fail(ADACLUSTER_E_INTERNAL, "stream join failed");
+    if (hipEventRecord(aux->join2, aux->s) != hipSuccess) return drained(fail(ADACLUSTER_E_INTERNAL, "stream join failed"));
   }
-  if (hipStreamWaitEvent(st, aux->join, 0) != hipSuccess) return fail(ADACLUSTER_E_INTERNAL, "stream join failed");
+  if (hipStreamWaitEvent(st, aux->join, 0) != hipSuccess) return drained(fail(ADACLUSTER_E_INTERNAL, "stream join failed"));
   if (rc || rck || rcp) {
     // whatever was queued on the second stream is joined before the error is reported
-    if (fork2 && hipStreamWaitEvent(st, aux->join2, 0) != hipSuccess) return fail(ADACLUSTER_E_INTERNAL, "stream join failed");
+    if (fork2 && hipStreamWaitEvent(st, aux->join2, 0) != hipSuccess) return drained(fail(ADACLUSTER_E_INTERNAL, "stream join failed"));
     return rc ? rc : (rck ? rck : rcp);
   }
   prof_mark(EV_JOIN, st);
   const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->d);
-  RET_IF(launch_select(st, p->H, p->q_clusters, capacity(p), p->d, p->score_mode, p->select_mode, p->topk, p->top_p,
-                       scale, q_centroids, q_mean_norm, k_centroids, k_bmin, k_bmax, k_sizes, k_count, full_flag,
-                       sel_idx, sel_cnt, kc_bound));
+  rc = launch_select(st, p->H, p->q_clusters, capacity(p), p->d, p->score_mode, p->select_mode, p->topk, p->top_p,
+                     scale, q_centroids, q_mean_norm, k_centroids, k_bmin, k_bmax, k_sizes, k_count, full_flag,
+                     sel_idx, sel_cnt, kc_bound);
+  if (rc) return drained(rc == ADACLUSTER_E_INTERNAL ? fail(rc, "HIP launch failed: %s", hipGetErrorString(hipGetLastError())) : rc);
   prof_mark(EV_SELECT, st, EV_JOIN);
-  // both label sorts were left in the workspace by the clustering steps
-  return run_plan_attention(p, w, st, Q, O, k_count, sel_idx, sel_cnt, EV_SELECT, aux->join2);
+  // both label sorts were left in the workspace by the clustering steps; the attention step joins the
+  // permutation of K and V (second stream) before its first kernel that reads it
+  rc = run_plan_attention(p, w, st, Q, O, k_count, sel_idx, sel_cnt, EV_SELECT, aux->join2);
+  return rc ? drained(rc) : 0;
 }
 
 int adacluster_dense_attn(const adacluster_params* p, const void* Q, const void* K, const void* V, void* O,
