@@ -14,7 +14,7 @@ import torch
 from oracle import adacluster_oracle as orc
 from paper_2604_18348_amd import binding as B
 from paper_2604_18348_amd import workloads as wl
-from tests.helpers import cosine_label_mismatches, euclid_label_mismatches, to_dev, to_np
+from tests.helpers import REL_TIE, cosine_label_mismatches, euclid_label_mismatches, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -308,7 +308,7 @@ def test_kcluster_bf16_stage_centres_follow_the_oracle_trajectory(d, N, tau):
 
 
 @pytest.mark.parametrize("d,N,tau,iters", [(64, 7000, 2.2, 3), (128, 5000, 3.3, 3), (64, 7000, 2.2, 1),
-                                          (128, 5000, 3.3, 2)])
+                                          (128, 5000, 3.3, 2), (64, 7000, 2.2, 2)])
 def test_kcluster_many_late_stages_in_one_launch(d, N, tau, iters):
     """A tight threshold leaves thousands of points unassigned stage after stage: from the second stage
     on, one workgroup per head runs all the remaining stages in a single launch.  One more or one less
@@ -349,16 +349,39 @@ def check_stages_against_oracle(Kh, out, h, n_stages, iters, tau):
     stage_of = out["k_stage_of"].cpu().numpy()[h]
     C = to_np(out["k_assign_centroids"])[h]
     worst_equal, worst_diff, worst_removed = 1.0, 0.0, 1.0
+    excluded = 0
     for t in range(n_stages):
         U = np.flatnonzero((stage_of >= t) | (stage_of == -1))
         m_t = offs[t + 1] - offs[t]
         labels, Ct, d2 = orc.euclid_kmeans(Kh[U].astype(np.float64), m_t, iters, round_fn=orc.round_to_bf16)
         got = C[offs[t]:offs[t + 1]]
+        if iters == 2:
+            # Two passes: the stage centres are the bf16-rounded member means over the labels of pass 1, and
+            # those labels are arg-mins to rows of K (the strided sample), the same on both sides except for
+            # points within rounding of two of those rows.  Every entry is then within one bf16 step
+            # (fp32 against fp64 sums on different sides of a rounding boundary); centres that a near-tied
+            # point may have joined or left are left to the looser bound below.
+            X = Kh[U].astype(np.float64)
+            C0 = X[orc.strided_indices(U.size, m_t)]
+            G = (C0 * C0).sum(1)[None] - 2.0 * X @ C0.T
+            order = np.argsort(G, axis=1)[:, :2]
+            g0, g1 = G[np.arange(U.size), order[:, 0]], G[np.arange(U.size), order[:, 1]]
+            tied = (g1 - g0) <= REL_TIE * ((X * X).sum(1) + (C0 * C0).sum(1)[order[:, 0]])
+            strict = np.ones(m_t, dtype=bool)
+            strict[order[tied].ravel()] = False
+            excluded += int((~strict).sum())
+            step = 2.0 ** -7 * np.maximum(np.abs(Ct), np.abs(got))
+            assert np.all(np.abs(got - Ct)[strict] <= step[strict]), (t, float((np.abs(got - Ct) / np.maximum(step, 1e-30))[strict].max()))
         worst_equal = min(worst_equal, float((got == Ct).mean()))
         worst_diff = max(worst_diff, float(np.abs(got - Ct).max()))
         worst_removed = min(worst_removed, float(((d2 < tau * tau) == (stage_of[U] == t)).mean()))
     print("head", h, "stage_offs", offs[:n_stages + 1], "entries equal", worst_equal, "max diff", worst_diff,
-          "removal agreement", worst_removed)
+          "removal agreement", worst_removed, "centres left to the loose bound", excluded)
+    assert excluded <= (offs[n_stages] - offs[0]) // 4      # the strict check covers most centres
+    if iters == 1:
+        assert worst_equal == 1.0                      # the strided sample itself
+    if iters == 2:
+        assert worst_equal > 0.97 and worst_removed > 0.999
     # Both sides round the centres to bf16.  A mean that the fp32 and the fp64 sums put on different sides
     # of a rounding boundary differs by one bf16 step; in diffuse data that step flips a few points
     # on the centre's boundary in the next pass, which moves the means of both neighbours a little
@@ -366,14 +389,15 @@ def check_stages_against_oracle(Kh, out, h, n_stages, iters, tau):
     assert worst_diff < 0.1 and worst_equal > 0.8 and worst_removed > 0.995
 
 
+@pytest.mark.parametrize("iters", [3, 2])
 @pytest.mark.parametrize("d", [64, 128])
-def test_kcluster_block_sums_with_four_centre_tiles(d):
+def test_kcluster_block_sums_with_four_centre_tiles(d, iters):
     """Stages of 97 to 128 centres over few blocks of points: the assignment kernel leaves the block sums,
     and with four centre tiles a wave takes whole centre tiles.  Two such stages (the centre count is held
     at 100 by the lower limit), each checked against the oracle's k-means on the same U."""
     H, N, tau = 2, 5000, 2.4 if d == 64 else 3.4
     _, K, _ = wl.make_small(57, N, d, 40, dtype="bf16", H=H)
-    p = B.Params(H=H, N=N, d=d, dtype=B.BF16, q_clusters=4, k_iters=3, k_m0=112, k_m_min=100, k_max_clusters=400,
+    p = B.Params(H=H, N=N, d=d, dtype=B.BF16, q_clusters=4, k_iters=iters, k_m0=112, k_m_min=100, k_max_clusters=400,
                  k_max_stages=2, tau_abs=tau)
     out = B.adacluster_kcluster(p, to_dev(K, B.BF16))
     torch.cuda.synchronize()
@@ -382,7 +406,7 @@ def test_kcluster_block_sums_with_four_centre_tiles(d):
     for h in range(H):
         print("stage offsets", offs[h][:3])
         assert offs[h, 1] == 112 and offs[h, 2] == 212
-        check_stages_against_oracle(K[h], out, h, 2, 3, tau)
+        check_stages_against_oracle(K[h], out, h, 2, iters, tau)
 
 
 @pytest.mark.parametrize("dtype,d", [(B.BF16, 64), (B.BF16, 128), (B.F32, 64)])

@@ -1,8 +1,9 @@
 """Full-size chained parity on the benchmark configurations, in the launch configuration the
-benchmark times (same H, N, d, parameters), checked on sampled outputs the oracle computes one by
-one: sampled tokens' labels are the arg-min / arg-max to the reported centres, sampled query
-clusters' selections are bit-exact given the GPU's centroids, and sampled output rows equal the
-fp64 softmax over the keys of the selected clusters (1e-2 relative L2 / 2e-2 max-abs for bf16)."""
+benchmark times (same H, N, d, parameters), checked on outputs the oracle computes one by one, on
+every head: labels are the arg-min / arg-max to the reported centres (all tokens of three heads,
+1024 sampled tokens of the others), the selections of all query clusters are bit-exact given the
+GPU's centroids, and 64 sampled output rows per head equal the fp64 softmax over the keys of the
+selected clusters (1e-2 relative L2 / 2e-2 max-abs for bf16)."""
 from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
@@ -24,8 +25,6 @@ def gen(name):
     Q = torch.empty((H, N, d), dtype=dt, device="cuda")
     K = torch.empty_like(Q)
     V = torch.empty_like(Q)
-    keep = {}
-    sample_heads = sorted(set([0, H // 2, H - 1]))
 
     def one(h):
         return h, wl.make_head(cfg, h)
@@ -35,14 +34,31 @@ def gen(name):
             Q[h].copy_(torch.from_numpy(q).to(dt))
             K[h].copy_(torch.from_numpy(k).to(dt))
             V[h].copy_(torch.from_numpy(v).to(dt))
-            if h in sample_heads:
-                keep[h] = (q, k, v)
-    return cfg, Q, K, V, keep
+    return cfg, Q, K, V
+
+
+def check_labels(q64, k64, qa, ka, ql, kl, toks, chunk=8192):
+    """labels of the tokens `toks`: arg-max cosine / arg-min distance to the reported centres, or within
+    rounding of it.  Returns the number of tokens that sit on such a near-tie."""
+    ties = 0
+    kan = (ka * ka).sum(1)
+    for a in range(0, toks.size, chunk):
+        t = toks[a:a + chunk]
+        S = orc.normalize_rows(q64[t]) @ qa.T
+        bad = np.flatnonzero(S.argmax(1) != ql[t])
+        assert np.all(S[bad].max(1) - S[bad, ql[t][bad]] <= REL_TIE), "query label off a near-tie"
+        ties += bad.size
+        G = kan[None] - 2 * k64[t] @ ka.T
+        bad = np.flatnonzero(G.argmin(1) != kl[t])
+        sc_ = (k64[t][bad] ** 2).sum(1) + kan[kl[t][bad]]
+        assert np.all(G[bad, kl[t][bad]] - G[bad].min(1) <= REL_TIE * sc_), "key label off a near-tie"
+        ties += bad.size
+    return ties
 
 
 @pytest.mark.parametrize("name", ["c2", "c3", "c4", "c5"])
 def test_fullsize_sampled_parity(name):
-    cfg, Q, K, V, keep = gen(name)
+    cfg, Q, K, V = gen(name)
     H, N, d = Q.shape
     p = B.Params(H=H, N=N, d=d, dtype=B.BF16, **cfg["params"])
     outs = B.alloc_outputs(p, "cuda")
@@ -51,12 +67,16 @@ def test_fullsize_sampled_parity(name):
     kc = outs["k_count"].cpu().numpy()
     full = outs["full_flag"].cpu().numpy()
     print(name, "k_count min/mean/max", kc.min(), kc.mean(), kc.max(), "full heads", int(full.sum()),
-          "tau", float(outs["tau_used"][0]))
+          "tau", float(outs["tau_used"][0]), flush=True)
     assert np.all(kc >= 1) and np.all(kc <= p.cap)
     rng = np.random.default_rng(7)
     scale = float(np.float32(1.0 / np.sqrt(np.float32(d))))
-    for h, (q, k, v) in keep.items():
-        q64, k64, v64 = q.astype(np.float64), k.astype(np.float64), v.astype(np.float64)
+    all_token_heads = sorted(set([0, H // 2, H - 1]))
+    worst_rel, worst_max, ties = 0.0, 0.0, 0
+    for h in range(H):
+        q64 = Q[h].float().cpu().numpy().astype(np.float64)
+        k64 = K[h].float().cpu().numpy().astype(np.float64)
+        v64 = V[h].float().cpu().numpy().astype(np.float64)
         ql = outs["q_labels"][h].cpu().numpy()
         kl = outs["k_labels"][h].cpu().numpy()
         qa = to_np(outs["q_assign_centroids"][h])
@@ -64,22 +84,15 @@ def test_fullsize_sampled_parity(name):
         sizes = outs["k_sizes"][h].cpu().numpy()[:kc[h]]
         assert np.array_equal(sizes, np.bincount(kl, minlength=kc[h]))
         assert np.array_equal(outs["q_sizes"][h].cpu().numpy(), np.bincount(ql, minlength=p.q_clusters))
-        # labels of sampled tokens
-        toks = rng.choice(N, size=256, replace=False)
-        Xn = orc.normalize_rows(q64[toks])
-        S = Xn @ qa.T
-        bad = np.flatnonzero(S.argmax(1) != ql[toks])
-        assert np.all(S[bad].max(1) - S[bad, ql[toks][bad]] <= REL_TIE), "query label off a near-tie"
-        G = (ka * ka).sum(1)[None] - 2 * k64[toks] @ ka.T
-        bad = np.flatnonzero(G.argmin(1) != kl[toks])
-        sc_ = (k64[toks][bad] ** 2).sum(1) + (ka[kl[toks][bad]] ** 2).sum(1)
-        assert np.all(G[bad, kl[toks][bad]] - G[bad].min(1) <= REL_TIE * sc_), "key label off a near-tie"
+        # labels: every token of three heads, 1024 sampled tokens of the others
+        toks = np.arange(N) if h in all_token_heads else rng.choice(N, size=min(N, 1024), replace=False)
+        ties += check_labels(q64, k64, qa, ka, ql, kl, toks)
         # centroids of a few clusters are the member means of the GPU labels
         kcen = to_np(outs["k_centroids"][h])
         for j in rng.choice(kc[h], size=4, replace=False):
             if sizes[j]:
                 assert np.allclose(kcen[j], k64[kl == j].mean(0), atol=2e-5, rtol=1e-5)
-        # selection of sampled query clusters from the GPU's centroids: bit-exact
+        # selection of every query cluster from the GPU's centroids: bit-exact
         sel = sel_from_dev(outs["sel_idx"][h:h + 1], outs["sel_cnt"][h:h + 1])[0]
         Ssc = orc.cluster_scores(p.score_mode, to_np(outs["q_centroids"][h]), kcen[:kc[h]], None, None, sizes)
         if full[h]:
@@ -90,8 +103,8 @@ def test_fullsize_sampled_parity(name):
             ref_sel = orc.select_topp(Ssc, sizes, to_np(outs["q_mean_norm"][h]) * scale, p.top_p)
         for i in range(p.q_clusters):
             assert np.array_equal(sel[i], ref_sel[i]), (h, i)
-        # sampled output rows
-        rows = rng.choice(N, size=24, replace=False)
+        # 64 sampled output rows
+        rows = rng.choice(N, size=64, replace=False)
         got = O[h][torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
         order = np.argsort(kl, kind="stable")
         bounds = np.searchsorted(kl[order], np.arange(kc[h] + 1))
@@ -103,5 +116,8 @@ def test_fullsize_sampled_parity(name):
                 ref[n_] = orc.dense_attention(q64[r:r + 1], k64[kidx], v64[kidx], scale)[0]
         rel = float(np.linalg.norm(got - ref) / np.linalg.norm(ref))
         mx = float(np.abs(got - ref).max())
-        print(name, "head", h, "k_count", kc[h], "full", full[h], "rows rel", rel, "max", mx)
+        worst_rel, worst_max = max(worst_rel, rel), max(worst_max, mx)
+        print(name, "head", h, "k_count", kc[h], "full", full[h], "labels checked", toks.size, "rows rel", rel,
+              "max", mx, flush=True)
         assert rel < 1e-2 and mx < 2e-2
+    print(name, "worst rows rel", worst_rel, "max", worst_max, "labels on a near-tie", ties)

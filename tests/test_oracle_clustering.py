@@ -172,7 +172,11 @@ def test_stage_cluster_count_rule():
     assert orc.stage_cluster_count(251, 1000, 100, 8) == 26        # ceil
     assert orc.stage_cluster_count(10, 1000, 100, 8) == 8          # floor m_min
     assert orc.stage_cluster_count(5, 1000, 100, 8) == 5           # never more centres than points
-    assert orc.min_unassigned_count(0.03, 1000) == 29 or orc.min_unassigned_count(0.03, 1000) == 30
+    # The fraction is a float32 parameter of the call: float32(0.03) = 0.0299999993..., so 3 % of 1000
+    # tokens is floor(29.9999993) = 29, not 30; float32(0.1) = 0.100000001... gives 100; 0.25 is exact.
+    assert orc.min_unassigned_count(0.03, 1000) == 29
+    assert orc.min_unassigned_count(0.1, 1000) == 100
+    assert orc.min_unassigned_count(0.25, 1000) == 250
     assert orc.min_unassigned_count(0.0, 1000) == 0
 
 
