@@ -24,7 +24,7 @@ sys.path.insert(0, ROOT)
 # reads for a plain copy of known size) + WRITE_SIZE of the two rocprofv3 --pmc passes summarised in
 # profiles/attn_pipeline_<config>.txt.  A counter cannot be read from inside this script, so the
 # figures are stored; a config without a profile reports null.
-PROFILED_ATTN_TRAFFIC_BYTES = {"c2": 707.7e6, "c3": 289.0e6, "c4": 2670.6e6, "c5": 4324.2e6}
+PROFILED_ATTN_TRAFFIC_BYTES = {"c2": 918.4e6, "c3": 291.7e6, "c4": 3149.0e6, "c5": 4448.9e6}
 
 
 def cpu_baseline(name, wl, target_s=15.0):

@@ -56,11 +56,19 @@ def check_labels(q64, k64, qa, ka, ql, kl, toks, chunk=8192):
     return ties
 
 
-@pytest.mark.parametrize("name", ["c2", "c3", "c4", "c5"])
+# "c2/tau6.5": configuration 2 under an absolute threshold between the first-stage distances of its
+# clustered heads (about 4.7) and of its six diffuse heads (about 7.5).  Under the shared threshold of the
+# configuration itself (1.5 x the mean over ALL heads, which the diffuse heads inflate) every head clears at
+# the first stage and no head reaches N_max; here the diffuse heads do, take the flag F and attend densely.
+@pytest.mark.parametrize("name", ["c2", "c2/tau6.5", "c3", "c4", "c5"])
 def test_fullsize_sampled_parity(name):
+    name, _, variant = name.partition("/")
     cfg, Q, K, V = gen(name)
     H, N, d = Q.shape
-    p = B.Params(H=H, N=N, d=d, dtype=B.BF16, **cfg["params"])
+    params = dict(cfg["params"])
+    if variant:
+        params.update(tau_abs=float(variant[3:]), tau_factor=0.0)
+    p = B.Params(H=H, N=N, d=d, dtype=B.BF16, **params)
     outs = B.alloc_outputs(p, "cuda")
     O = B.adacluster_attn(p, Q, K, V, outs=outs)
     torch.cuda.synchronize()
@@ -69,6 +77,10 @@ def test_fullsize_sampled_parity(name):
     print(name, "k_count min/mean/max", kc.min(), kc.mean(), kc.max(), "full heads", int(full.sum()),
           "tau", float(outs["tau_used"][0]), flush=True)
     assert np.all(kc >= 1) and np.all(kc <= p.cap)
+    if variant:
+        diffuse = np.zeros(H, dtype=bool)
+        diffuse[list(cfg["diffuse_heads"])] = True
+        assert np.array_equal(full.astype(bool), diffuse) and np.all(kc[diffuse] >= p.k_max_clusters)
     rng = np.random.default_rng(7)
     scale = float(np.float32(1.0 / np.sqrt(np.float32(d))))
     all_token_heads = sorted(set([0, H // 2, H - 1]))
