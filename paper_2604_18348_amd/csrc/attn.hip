@@ -86,27 +86,62 @@ __global__ __launch_bounds__(256) void plan_sparse(int Cq, int cap, int maxr, in
   int32_t* rs = rng_start + ((size_t)h * Cq + i) * maxr;
   int32_t* rp = rng_pre + ((size_t)h * Cq + i) * (maxr + 1);
   __shared__ int32_t s_nr, s_total;
-  if (tid == 0) {
+  __shared__ int32_t s_we[4], s_wh[4], s_wlen[4], s_wst[4];
+  {
+    // The selected clusters in list order; a cluster whose rows follow the previous non-empty one's directly
+    // extends its range.  256 entries per round: "end of the last non-empty entry before me" by a scan that
+    // keeps the right operand when it is non-empty, then run starts and lengths by prefix sums; the state
+    // after a round (last end, keys so far, ranges so far) is carried into the next.
     const int32_t* sel = sel_idx + ((size_t)h * Cq + i) * cap;
     const int cnt = sel_cnt[(size_t)h * Cq + i];
     const int32_t* ko = k_offs + (size_t)h * k_offs_stride;
     const int kc = k_count[h];
-    int nr = 0, total = 0, cur_s = 0, cur_e = -1;
-    for (int t = 0; t < cnt; ++t) {
-      const int j = sel[t];
-      if (j < 0 || j >= kc) continue;
-      const int s = ko[j], e = ko[j + 1];
-      if (e <= s) continue;
-      if (s == cur_e) { cur_e = e; continue; }
-      if (cur_e > cur_s) { rs[nr] = cur_s; rp[nr] = total; total += cur_e - cur_s; ++nr; }
-      cur_s = s; cur_e = e;
+    const int lane = tid & 63, wave = tid >> 6;
+    int carry_e = -1, carry_total = 0, carry_nr = 0;          // identical in every thread
+    for (int base = 0; base < cnt; base += 256) {
+      const int t = base + tid;
+      int sk = 0, ek = 0;
+      bool valid = false;
+      if (t < cnt) {
+        const int j = sel[t];
+        if (j >= 0 && j < kc) { sk = ko[j]; ek = ko[j + 1]; valid = ek > sk; }
+      }
+      const int len = valid ? ek - sk : 0;
+      // inclusive scans inside the wave
+      int ie = valid ? ek : -1, ih = valid ? 1 : 0, il = len;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const int oe = __shfl_up(ie, off), oh = __shfl_up(ih, off), ol = __shfl_up(il, off);
+        if (lane >= off) { if (!ih) { ie = oe; ih = oh; } il += ol; }
+      }
+      if (lane == 63) { s_we[wave] = ie; s_wh[wave] = ih; s_wlen[wave] = il; }
+      __syncthreads();
+      // what precedes this thread: the carry, the earlier waves, the earlier lanes
+      int pe = carry_e, ph = carry_e >= 0 ? 1 : 0, plen = carry_total;
+      for (int w = 0; w < wave; ++w) { if (s_wh[w]) { pe = s_we[w]; ph = 1; } plen += s_wlen[w]; }
+      const int le = __shfl_up(ie, 1), lh = __shfl_up(ih, 1);
+      if (lane > 0 && lh) { pe = le; ph = 1; }
+      plen += il - len;
+      const bool start = valid && !(ph && pe == sk);
+      int is = start ? 1 : 0;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) { const int o = __shfl_up(is, off); if (lane >= off) is += o; }
+      if (lane == 63) s_wst[wave] = is;
+      __syncthreads();
+      int pst = carry_nr;
+      for (int w = 0; w < wave; ++w) pst += s_wst[w];
+      if (start) { const int r = pst + is - 1; rs[r] = sk; rp[r] = plen; }
+      // the carry of the next round, the same in every thread
+      for (int w = 0; w < 4; ++w) { if (s_wh[w]) carry_e = s_we[w]; carry_total += s_wlen[w]; carry_nr += s_wst[w]; }
+      __syncthreads();                         // the wave totals are free again
     }
-    if (cur_e > cur_s) { rs[nr] = cur_s; rp[nr] = total; total += cur_e - cur_s; ++nr; }
-    rp[nr] = total;
-    rng_cnt[(size_t)h * Cq + i] = nr;
-    s_nr = nr; s_total = total;
+    if (tid == 0) {
+      rp[carry_nr] = carry_total;
+      rng_cnt[(size_t)h * Cq + i] = carry_nr;
+      s_nr = carry_nr; s_total = carry_total;
+    }
   }
-  __syncthreads();        // the ranges thread 0 wrote are visible to the workgroup
+  __syncthreads();        // the ranges are visible to the whole workgroup
   // Byte offset of every key row of the concatenation, in order: what a key tile of the attention kernel
   // loads its 64 rows by.  Entries past the end (up to the padding the kernel may read ahead) repeat the
   // first row: they are loaded and never used.
@@ -115,15 +150,27 @@ __global__ __launch_bounds__(256) void plan_sparse(int Cq, int cap, int maxr, in
   int32_t* kr = krow + ((size_t)h * Cq + i) * kstride;
   const int first = nr > 0 ? rs[0] * row_bytes : 0;
   const int padded = (total + 63) / 64 * 64 + KROW_PAD;
-  for (int p = tid; p < padded; p += 256) {
-    int off = first;
-    if (p < total) {
-      int lo = 0, hi = nr - 1;                 // last range whose first position is <= p
-      while (lo < hi) { const int mid = (lo + hi + 1) >> 1; if (rp[mid] <= p) lo = mid; else hi = mid - 1; }
-      off = (rs[lo] + (p - rp[lo])) * row_bytes;
-    }
-    kr[p] = off;
+  // the search runs on a copy of the range table in LDS when it fits: its steps depend on one another, and
+  // from global memory each of them is a trip to the L2
+  constexpr int LR = 512;
+  __shared__ int32_t l_rs[LR], l_rp[LR];
+  const bool in_lds = nr <= LR;
+  if (in_lds) {
+    for (int r = tid; r < nr; r += 256) { l_rs[r] = rs[r]; l_rp[r] = rp[r]; }
+    __syncthreads();
   }
+  auto fill = [&](const int32_t* srs, const int32_t* srp) __attribute__((always_inline)) {
+    for (int p = tid; p < padded; p += 256) {
+      int off = first;
+      if (p < total) {
+        int lo = 0, hi = nr - 1;                 // last range whose first position is <= p
+        while (lo < hi) { const int mid = (lo + hi + 1) >> 1; if (srp[mid] <= p) lo = mid; else hi = mid - 1; }
+        off = (srs[lo] + (p - srp[lo])) * row_bytes;
+      }
+      kr[p] = off;
+    }
+  };
+  if (in_lds) fill(l_rs, l_rp); else fill(rs, rp);
 }
 
 // Query tiles of a head, cluster by cluster.  A query cluster whose key list is much longer than
