@@ -752,16 +752,25 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
-// fp32 kernel: one query per thread, key tiles broadcast from LDS (accuracy path, small inputs)
+// fp32 kernel (the accuracy path of fp32 inputs): the same S^T = K Q^T / O^T += V^T P^T walk on the
+// matrix cores with v_mfma_f32_32x32x2_f32 (fp32 products, fp32 accumulation)
 // ------------------------------------------------------------------------------------------
+// A workgroup is two waves of 32 queries; key tiles of 32 rows go through LDS.  In the 32x32 accumulator a
+// lane (c = lane % 32, hb = lane / 32) owns query c and the keys 8*(v/4) + 4*hb + v%4 of the tile, v = 0..15.
+// The two values a lane pair supplies per product step may be any pair of the contraction index as long as
+// both operands agree: for S the pair is (dim ks, dim D/2 + ks), so a lane keeps one contiguous half of its
+// query row; for P.V step j contracts exactly the keys of accumulator value j, so the probabilities are the
+// B operand as they stand and no value crosses the half-waves.  K rows are padded to D + 1 floats and V rows
+// to D + 8, which spreads the operand reads of a step over the banks.
 template <int D>
-__global__ __launch_bounds__(64) void attn_f32(AttnArgs a) {
-  constexpr int BN = 32;
+__global__ __launch_bounds__(128) void attn_f32(AttnArgs a) {
+  constexpr int BN = 32, HD = D / 2, KP = D + 1, VP = D + 8, DB = D / 32, NT = 128;
   const int h = blockIdx.y, tile = blockIdx.x;
   if (tile >= a.ntiles[h]) return;
   const int32_t* tl = a.tiles + ((size_t)h * a.maxtiles + tile) * TILE_REC;   // (key lists are never cut for fp32)
   const int qc = tl[0], row0 = tl[1], nrows = tl[2];
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = lane & 31, hb = lane >> 5;
   const int nr = a.rng_cnt[(size_t)h * a.Cq + qc];
   const int32_t* rs = a.rng_start + ((size_t)h * a.Cq + qc) * a.maxr;
   const int32_t* rp = a.rng_pre + ((size_t)h * a.Cq + qc) * (a.maxr + 1);
@@ -770,22 +779,32 @@ __global__ __launch_bounds__(64) void attn_f32(AttnArgs a) {
   const float* Kh = (const float*)a.Kp + (size_t)h * a.N * D;
   const float* Vh = (const float*)a.Vp + (size_t)h * a.N * D;
   float* Oh = (float*)a.O + (size_t)h * a.N * D;
-  __shared__ __attribute__((aligned(16))) float Ks[BN * D];
-  __shared__ __attribute__((aligned(16))) float Vs[BN * D];
+  __shared__ float Ks[BN * KP];
+  __shared__ __attribute__((aligned(16))) float Vs[BN * VP];
   __shared__ int32_t ridx[BN];
+  const int qrow = wave * 32 + c;
   int tok = -1;
-  if (tid < nrows) tok = a.perm_q ? a.perm_q[(size_t)h * a.N + row0 + tid] : row0 + tid;
-  float q[D], o[D];
+  if (qrow < nrows) tok = a.perm_q ? a.perm_q[(size_t)h * a.N + row0 + qrow] : row0 + qrow;
+  float q[HD];
 #pragma unroll
-  for (int j = 0; j < D; ++j) { q[j] = tok >= 0 ? Qh[(size_t)tok * D + j] : 0.f; o[j] = 0.f; }
+  for (int j = 0; j < HD; j += 4) {
+    float4 v = {0.f, 0.f, 0.f, 0.f};
+    if (tok >= 0) v = *reinterpret_cast<const float4*>(Qh + (size_t)tok * D + hb * HD + j);
+    q[j] = v.x; q[j + 1] = v.y; q[j + 2] = v.z; q[j + 3] = v.w;
+  }
+  f32x16_t o[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
   float m = -INFINITY, l = 0.f;
   RangeCursor cur;
   if (tid < BN) cur.init(rs, rp, nr);
   for (int k0 = 0; k0 < total; k0 += BN) {
-    __syncthreads();
+    __syncthreads();                                   // the previous tile has been consumed
     if (tid < BN) ridx[tid] = cur.row(k0 + tid);
     __syncthreads();
-    for (int i = tid; i < BN * D / 4; i += 64) {
+    for (int i = tid; i < BN * D / 4; i += NT) {
       const int r = i / (D / 4), qd = i % (D / 4);
       const int row = ridx[r];
       float4 kv = {0.f, 0.f, 0.f, 0.f}, vv = {0.f, 0.f, 0.f, 0.f};
@@ -793,37 +812,55 @@ __global__ __launch_bounds__(64) void attn_f32(AttnArgs a) {
         kv = reinterpret_cast<const float4*>(Kh + (size_t)row * D)[qd];
         vv = reinterpret_cast<const float4*>(Vh + (size_t)row * D)[qd];
       }
-      reinterpret_cast<float4*>(Ks)[i] = kv;
-      reinterpret_cast<float4*>(Vs)[i] = vv;
+      float* kd = &Ks[r * KP + 4 * qd];
+      kd[0] = kv.x; kd[1] = kv.y; kd[2] = kv.z; kd[3] = kv.w;
+      *reinterpret_cast<float4*>(&Vs[r * VP + 4 * qd]) = vv;
     }
     __syncthreads();
-    const int kn = min(BN, total - k0);
-    for (int r = 0; r < kn; ++r) {
-      float s = 0.f;
+    f32x16_t sacc;
 #pragma unroll
-      for (int j = 0; j < D; j += 4) {
-        const float4 kv = *reinterpret_cast<const float4*>(&Ks[r * D + j]);
-        s = fmaf(q[j], kv.x, s); s = fmaf(q[j + 1], kv.y, s);
-        s = fmaf(q[j + 2], kv.z, s); s = fmaf(q[j + 3], kv.w, s);
-      }
-      s *= a.scale_log2e;
-      const float mnew = fmaxf(m, s);
-      const float alpha = exp2f(m - mnew);
-      const float p = exp2f(s - mnew);
-      l = l * alpha + p;
+    for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
 #pragma unroll
-      for (int j = 0; j < D; j += 4) {
-        const float4 vv = *reinterpret_cast<const float4*>(&Vs[r * D + j]);
-        o[j] = fmaf(o[j], alpha, p * vv.x); o[j + 1] = fmaf(o[j + 1], alpha, p * vv.y);
-        o[j + 2] = fmaf(o[j + 2], alpha, p * vv.z); o[j + 3] = fmaf(o[j + 3], alpha, p * vv.w);
+    for (int ks = 0; ks < HD; ++ks)
+      sacc = __builtin_amdgcn_mfma_f32_32x32x2f32(Ks[c * KP + hb * HD + ks], q[ks], sacc, 0, 0, 0);
+    const int kn = total - k0;                          // keys of this tile that exist (>= 1)
+    float tmax = -INFINITY;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int key = 8 * (v >> 2) + 4 * hb + (v & 3);
+      sacc[v] = key < kn ? sacc[v] * a.scale_log2e : -INFINITY;
+      tmax = fmaxf(tmax, sacc[v]);
+    }
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+    const float mnew = fmaxf(m, tmax);                  // finite: the tile holds at least one key
+    const float alpha = exp2f(m - mnew);
+    float lsum = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { sacc[v] = exp2f(sacc[v] - mnew); lsum += sacc[v]; }
+    lsum += __shfl_xor(lsum, 32);
+    l = l * alpha + lsum;
+    m = mnew;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int key = 8 * (j >> 2) + 4 * hb + (j & 3);
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x2f32(Vs[key * VP + db * 32 + c], sacc[j], o[db], 0, 0, 0);
       }
-      m = mnew;
     }
   }
+  // value v of dim block db is dim db*32 + 8*(v/4) + 4*hb + v%4 of query c
   if (tok >= 0) {
     const float inv = l > 0.f ? 1.0f / l : 0.f;
 #pragma unroll
-    for (int j = 0; j < D; ++j) Oh[(size_t)tok * D + j] = o[j] * inv;
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const float4 o4 = {o[db][4 * g] * inv, o[db][4 * g + 1] * inv, o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv};
+        *reinterpret_cast<float4*>(Oh + (size_t)tok * D + db * 32 + 8 * g + 4 * hb) = o4;
+      }
   }
 }
 
@@ -951,8 +988,8 @@ int launch_attention(hipStream_t s, int dtype, int d, int H, int N, int Cq, int 
       else attn_merge<128><<<dim3(SPLIT_SLOTS, H), 256, 0, s>>>(a, merge, nmerge);
     }
   } else {
-    if (d == 64) attn_f32<64><<<g, 64, 0, s>>>(a);
-    else attn_f32<128><<<g, 64, 0, s>>>(a);
+    if (d == 64) attn_f32<64><<<g, 128, 0, s>>>(a);
+    else attn_f32<128><<<g, 128, 0, s>>>(a);
   }
   return hipGetLastError() == hipSuccess ? 0 : ADACLUSTER_E_INTERNAL;
 }
