@@ -174,7 +174,7 @@ struct WS {
   KState* kstate; int32_t* summary; float* tau; int32_t* u_prev;
   void* cent_lp; float* bias; float* master;
   int32_t* labels_tmp; float* dist2; int32_t* ulist[2]; int32_t* blockcnt; double* tau_part;
-  SortScratch sort; int32_t* perm_tmp; int32_t* offs_tmp; int32_t* poff;
+  SortScratch sort; int32_t* perm_tmp; int32_t* offs_tmp; int32_t* poff; int32_t* pcl;
   float* psum; float* pnorm; float* pmin; float* pmax; int32_t* bcnt; float* bsum;
   int32_t* perm_q; int32_t* offs_q; int32_t* perm_k; int32_t* offs_k;
   // scratch of the query clustering (its own set: it runs beside the key clustering)
@@ -239,6 +239,7 @@ size_t layout(const adacluster_params* p, WS* w, unsigned char* base) {
   TAKE(perm_tmp, int32_t*, H * N * 4);
   TAKE(offs_tmp, int32_t*, H * (size_t)(D.capmax + 1) * 4);
   TAKE(poff, int32_t*, H * (size_t)(D.capmax + 1) * 4);
+  TAKE(pcl, int32_t*, H * (size_t)D.prow * 4);
   TAKE(psum, float*, H * (size_t)D.prow * d * 4);
   TAKE(bcnt, int32_t*, H * (size_t)STAGE_SUM_BLOCKS * assign_block_sum_centres() * 4);
   TAKE(bsum, float*, H * (size_t)D.brow * d * 4);
@@ -335,7 +336,7 @@ int run_qcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
     RET_IF(launch_sort(st, D.H, D.N, D.N, D.Cq, q_labels, nullptr, nullptr, 0, nullptr, 0, nullptr, 0, w.perm_q,
                        w.offs_q, D.Cq + 1, w.q_sort, w.q_poff, reduce_part_rows(), &poff_done));
     RET_IF(launch_seg_reduce(st, p->dtype, D.d, D.H, D.N, 0, D.Cq, D.Cq, P, nullptr, sph, 0, Q, w.perm_q, w.offs_q,
-                             D.Cq + 1, w.q_poff, w.q_psum, w.q_pnorm, nullptr, nullptr, poff_done));
+                             D.Cq + 1, w.q_poff, nullptr, w.q_psum, w.q_pnorm, nullptr, nullptr, poff_done));
     const bool last = it == p->q_iters - 1;
     if (!last) {
       RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 0, D.Cq, D.Cq, P, D.Cq, D.Cq, nullptr, sph, 1, 0, w.offs_q,
@@ -373,7 +374,7 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
         RET_IF(launch_sort(st, D.H, D.N, D.N, D.cap, k_labels, nullptr, nullptr, 0, &w.kstate->m_t, sizeof(KState) / 4,
                            nullptr, 0, w.perm_tmp, w.offs_tmp, D.capmax + 1, w.sort, w.poff, reduce_part_rows(), &poff_done));
         RET_IF(launch_seg_reduce(st, p->dtype, D.d, D.H, D.N, 1, 0, D.cap, Pw, w.kstate, 0, 0, K, w.perm_tmp,
-                                 w.offs_tmp, D.capmax + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax, poff_done));
+                                 w.offs_tmp, D.capmax + 1, w.poff, w.pcl, w.psum, w.pnorm, w.pmin, w.pmax, poff_done));
         RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 1, 0, D.cap, Pw, D.cap, D.cap, w.kstate, 0, 1, 0, w.offs_tmp,
                                D.capmax + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax, k_centroids, w.cent_lp,
                                k_assign, w.bias, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr));
@@ -462,7 +463,7 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
                            sizeof(KState) / 4, &w.kstate->m_t, sizeof(KState) / 4, &w.kstate->active,
                            sizeof(KState) / 4, w.perm_tmp, w.offs_tmp, D.capmax + 1, w.sort, w.poff, reduce_part_rows(), &poff_done));
         RET_IF(launch_seg_reduce(st, p->dtype, D.d, D.H, D.N, 1, 0, m_bound, P, w.kstate, 0, 0, K, w.perm_tmp,
-                                 w.offs_tmp, D.capmax + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax, poff_done));
+                                 w.offs_tmp, D.capmax + 1, w.poff, w.pcl, w.psum, w.pnorm, w.pmin, w.pmax, poff_done));
         RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 1, 0, m_bound, P, D.cap, p->k_m0, w.kstate, 0, 1, 0,
                                w.offs_tmp, D.capmax + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax, w.master, w.cent_lp,
                                k_assign, w.bias, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr));
@@ -487,7 +488,7 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
   const int want_box = (k_bmin && k_bmax) ? 1 : 0;
   const int P = parts_for(D.N, D.cap);
   RET_IF(launch_seg_reduce(st, p->dtype, D.d, D.H, D.N, 2, 0, D.cap, P, w.kstate, 0, want_box, K, w.perm_k, w.offs_k,
-                           D.cap + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax, poff_done));
+                           D.cap + 1, w.poff, w.pcl, w.psum, w.pnorm, w.pmin, w.pmax, poff_done));
   prof_mark(EV_KREDUCE, st, EV_KSORT);
   RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 2, 0, D.cap, P, D.cap, D.cap, w.kstate, 0, 0, want_box, w.offs_k,
                          D.cap + 1, w.poff, w.psum, w.pnorm, w.pmin, w.pmax, nullptr, nullptr, nullptr, nullptr, k_centroids,

@@ -602,8 +602,10 @@ static constexpr int REDUCE_ROWS = 128;   // rows summed by one wave
 
 // poff[j] = number of parts of the clusters before j (a cluster of n rows has ceil(n/REDUCE_ROWS)
 // parts), j = 0..m.  One block per head.
+// pcl[b] = cluster of part b (written when there are more than 128 clusters: seg_reduce then reads its
+// cluster instead of searching poff, ten dependent round trips at 1024 clusters).
 __global__ __launch_bounds__(1024) void part_scan(ReduceCfg cfg, const int32_t* __restrict__ offs, int offs_stride,
-                                                  int32_t* __restrict__ poff) {
+                                                  int32_t* __restrict__ poff, int32_t* __restrict__ pcl) {
   const int h = blockIdx.x, tid = threadIdx.x;
   int m;
   if (!reduce_setup(cfg, h, m)) return;
@@ -623,15 +625,20 @@ __global__ __launch_bounds__(1024) void part_scan(ReduceCfg cfg, const int32_t* 
     __syncthreads();
   }
   int base = sc[tid] - run;
-  for (int j = j0; j < j1; ++j) { po[j] = base; base += (of[j + 1] - of[j] + REDUCE_ROWS - 1) / REDUCE_ROWS; }
+  int32_t* pc = (pcl && m > 128) ? pcl + (size_t)h * cfg.P : nullptr;
+  for (int j = j0; j < j1; ++j) {
+    po[j] = base;
+    const int np = (of[j + 1] - of[j] + REDUCE_ROWS - 1) / REDUCE_ROWS;
+    if (pc) for (int q = 0; q < np && base + q < cfg.P; ++q) pc[base + q] = j;
+    base += np;
+  }
   if (tid == 1023) po[m] = sc[1023];
 }
 
 template <typename T> struct Vec16;
 template <> struct Vec16<bf16raw> {
   static constexpr int N = 8;
-  static __device__ __forceinline__ void load(const bf16raw* p, float* x) {
-    const uint4 r = *reinterpret_cast<const uint4*>(p);
+  static __device__ __forceinline__ void decode(const uint4 r, float* x) {
     const uint32_t w[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) { x[2 * i] = __uint_as_float(w[i] << 16); x[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u); }
@@ -639,9 +646,8 @@ template <> struct Vec16<bf16raw> {
 };
 template <> struct Vec16<float> {
   static constexpr int N = 4;
-  static __device__ __forceinline__ void load(const float* p, float* x) {
-    const float4 r = *reinterpret_cast<const float4*>(p);
-    x[0] = r.x; x[1] = r.y; x[2] = r.z; x[3] = r.w;
+  static __device__ __forceinline__ void decode(const uint4 r, float* x) {
+    x[0] = __uint_as_float(r.x); x[1] = __uint_as_float(r.y); x[2] = __uint_as_float(r.z); x[3] = __uint_as_float(r.w);
   }
 };
 
@@ -649,7 +655,7 @@ template <typename T, int D>
 __global__ __launch_bounds__(64) void seg_reduce(const T* __restrict__ X, ReduceCfg cfg,
                                                  const int32_t* __restrict__ perm,
                                                  const int32_t* __restrict__ offs, int offs_stride,
-                                                 const int32_t* __restrict__ poff,
+                                                 const int32_t* __restrict__ poff, const int32_t* __restrict__ pcl,
                                                  float* __restrict__ psum, float* __restrict__ pnorm,
                                                  float* __restrict__ pmin, float* __restrict__ pmax) {
   constexpr int EV = Vec16<T>::N;     // elements per 16-byte load
@@ -682,9 +688,14 @@ __global__ __launch_bounds__(64) void seg_reduce(const T* __restrict__ X, Reduce
     end = jn == m ? o2 : (jn < 64 ? __shfl(o0, jn) : __shfl(o1, jn - 64));
   } else {
     if (b >= po[m]) return;
-    int lo = 0, hi = m - 1;
-    while (lo < hi) { const int mid = (lo + hi + 1) >> 1; if (po[mid] <= b) lo = mid; else hi = mid - 1; }
-    j = lo; part = b - po[j];
+    if (pcl) {
+      j = pcl[(size_t)h * cfg.P + b];
+    } else {
+      int lo = 0, hi = m - 1;
+      while (lo < hi) { const int mid = (lo + hi + 1) >> 1; if (po[mid] <= b) lo = mid; else hi = mid - 1; }
+      j = lo;
+    }
+    part = b - po[j];
     beg = of[j]; end = of[j + 1];
   }
   const int mb = beg + part * REDUCE_ROWS;
@@ -724,26 +735,31 @@ __global__ __launch_bounds__(64) void seg_reduce(const T* __restrict__ X, Reduce
   // the number of dependent memory round trips, not by bytes.  Every lane runs the same number of
   // steps (the shuffles in add_row need all lanes of a row present); rows past the end contribute
   // nothing.  The order in which a lane adds its rows is ascending, whatever UNR is.
-  constexpr int UNR = 8;
+  // The rows wait in registers as loaded (16 bytes, four registers each) and are decoded one by one when
+  // they are added, so that sixteen gathers per lane fit where eight decoded rows did.
+  constexpr int UNR = (64 / RPI) < 16 ? (64 / RPI) : 16;
   int idx_next = (mb + lane < me) ? pm[mb + lane] : 0;
   for (int r0 = mb; r0 < me; r0 += 64) {
     const int idx = idx_next;
     if (r0 + 64 < me) idx_next = (r0 + 64 + lane < me) ? pm[r0 + 64 + lane] : 0;
     const int nhere = min(64, me - r0);
     for (int k0 = 0; k0 < nhere; k0 += UNR * RPI) {
-      float x[UNR][EV];
+      uint4 raw[UNR];
       bool valid[UNR];
 #pragma unroll
       for (int u = 0; u < UNR; ++u) {
         const int k = k0 + u * RPI + slot;            // < 64 + RPI*UNR, but only k < nhere is used
         valid[u] = k < nhere;
         const int tok = __shfl(idx, k & 63);
-#pragma unroll
-        for (int e = 0; e < EV; ++e) x[u][e] = 0.f;
-        if (valid[u]) Vec16<T>::load(Xh + (size_t)tok * D, x[u]);
+        raw[u] = uint4{0u, 0u, 0u, 0u};
+        if (valid[u]) raw[u] = *reinterpret_cast<const uint4*>(Xh + (size_t)tok * D);
       }
 #pragma unroll
-      for (int u = 0; u < UNR; ++u) add_row(x[u], valid[u]);
+      for (int u = 0; u < UNR; ++u) {
+        float x[EV];
+        Vec16<T>::decode(raw[u], x);
+        add_row(x, valid[u]);
+      }
     }
   }
   // merge the row slots: slot s+o into slot s, o = RPI/2 ... 1
@@ -1614,7 +1630,7 @@ __global__ __launch_bounds__(256) void mse_partial(const T* __restrict__ X, cons
     if (r < end) {
       const int j = labels[(size_t)h * N + r];
       float x[EV];
-      Vec16<T>::load(X + ((size_t)h * N + r) * D + cl * EV, x);
+      Vec16<T>::decode(*reinterpret_cast<const uint4*>(X + ((size_t)h * N + r) * D + cl * EV), x);
       const float* c = cent + ((size_t)h * cap + j) * D + cl * EV;
 #pragma unroll
       for (int e = 0; e < EV; ++e) { const float df = x[e] - c[e]; ss = fmaf(df, df, ss); }
@@ -1688,17 +1704,18 @@ int launch_qpass(hipStream_t s, int d, int H, int N, int m, int cap, int weighte
 
 int launch_seg_reduce(hipStream_t s, int dtype, int d, int H, int N, int mode, int m_const, int m_bound, int P,
                       const KState* st, int normalize, int want_box, const void* X, const int32_t* perm,
-                      const int32_t* offs, int offs_stride, int32_t* poff, float* psum, float* pnorm, float* pmin,
-                      float* pmax, int poff_ready) {
+                      const int32_t* offs, int offs_stride, int32_t* poff, int32_t* pcl, float* psum, float* pnorm,
+                      float* pmin, float* pmax, int poff_ready) {
   ReduceCfg c{mode, m_const, N, P, m_bound, st, normalize, want_box};
-  if (!poff_ready) part_scan<<<H, 1024, 0, s>>>(c, offs, offs_stride, poff);
+  if (!poff_ready) part_scan<<<H, 1024, 0, s>>>(c, offs, offs_stride, poff, pcl);
+  else pcl = nullptr;                  // (the one-launch sort of small heads cuts the parts itself and leaves no table)
   dim3 g(P, H);
   if (dtype == ADACLUSTER_BF16) {
-    if (d == 64) seg_reduce<bf16raw, 64><<<g, 64, 0, s>>>((const bf16raw*)X, c, perm, offs, offs_stride, poff, psum, pnorm, pmin, pmax);
-    else seg_reduce<bf16raw, 128><<<g, 64, 0, s>>>((const bf16raw*)X, c, perm, offs, offs_stride, poff, psum, pnorm, pmin, pmax);
+    if (d == 64) seg_reduce<bf16raw, 64><<<g, 64, 0, s>>>((const bf16raw*)X, c, perm, offs, offs_stride, poff, pcl, psum, pnorm, pmin, pmax);
+    else seg_reduce<bf16raw, 128><<<g, 64, 0, s>>>((const bf16raw*)X, c, perm, offs, offs_stride, poff, pcl, psum, pnorm, pmin, pmax);
   } else {
-    if (d == 64) seg_reduce<float, 64><<<g, 64, 0, s>>>((const float*)X, c, perm, offs, offs_stride, poff, psum, pnorm, pmin, pmax);
-    else seg_reduce<float, 128><<<g, 64, 0, s>>>((const float*)X, c, perm, offs, offs_stride, poff, psum, pnorm, pmin, pmax);
+    if (d == 64) seg_reduce<float, 64><<<g, 64, 0, s>>>((const float*)X, c, perm, offs, offs_stride, poff, pcl, psum, pnorm, pmin, pmax);
+    else seg_reduce<float, 128><<<g, 64, 0, s>>>((const float*)X, c, perm, offs, offs_stride, poff, pcl, psum, pnorm, pmin, pmax);
   }
   return chk();
 }

@@ -28,8 +28,8 @@ int launch_assign(hipStream_t s, int dtype, int d, int H, int N, int n_bound, in
 int assign_block_sum_centres();   // most centres the assignment kernel keeps block sums for
 int launch_seg_reduce(hipStream_t s, int dtype, int d, int H, int N, int mode, int m_const, int m_bound, int P,
                       const KState* st, int normalize, int want_box, const void* X, const int32_t* perm,
-                      const int32_t* offs, int offs_stride, int32_t* poff, float* psum, float* pnorm, float* pmin, float* pmax,
-                      int poff_ready = 0);
+                      const int32_t* offs, int offs_stride, int32_t* poff, int32_t* pcl, float* psum, float* pnorm, float* pmin,
+                      float* pmax, int poff_ready = 0);
 int reduce_part_rows();
 int launch_finalize(hipStream_t s, int dtype, int d, int H, int mode, int m_const, int m_bound, int P, int cap,
                     int master_stride, const KState* st, int spherical, int update_assign, int want_box,
