@@ -174,7 +174,7 @@ struct WS {
   KState* kstate; int32_t* summary; float* tau; int32_t* u_prev;
   void* cent_lp; float* bias; float* master;
   int32_t* labels_tmp; float* dist2; int32_t* ulist[2]; int32_t* blockcnt; double* tau_part;
-  SortScratch sort; int32_t* perm_tmp; int32_t* offs_tmp; int32_t* poff; int32_t* pcl;
+  SortScratch sort; int32_t* perm_tmp; int32_t* offs_tmp; int32_t* poff; int32_t* pcl; int32_t* lab0; float* score0;
   float* psum; float* pnorm; float* pmin; float* pmax; int32_t* bcnt; float* bsum;
   int32_t* perm_q; int32_t* offs_q; int32_t* perm_k; int32_t* offs_k;
   // scratch of the query clustering (its own set: it runs beside the key clustering)
@@ -240,6 +240,8 @@ size_t layout(const adacluster_params* p, WS* w, unsigned char* base) {
   TAKE(offs_tmp, int32_t*, H * (size_t)(D.capmax + 1) * 4);
   TAKE(poff, int32_t*, H * (size_t)(D.capmax + 1) * 4);
   TAKE(pcl, int32_t*, H * (size_t)D.prow * 4);
+  TAKE(lab0, int32_t*, p->dtype == ADACLUSTER_BF16 ? H * N * 4 : 256);
+  TAKE(score0, float*, p->dtype == ADACLUSTER_BF16 ? H * N * 4 : 256);
   TAKE(psum, float*, H * (size_t)D.prow * d * 4);
   TAKE(bcnt, int32_t*, H * (size_t)STAGE_SUM_BLOCKS * assign_block_sum_centres() * 4);
   TAKE(bsum, float*, H * (size_t)D.brow * d * 4);
@@ -385,6 +387,7 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
     RET_IF(launch_kstate_export(st, w.kstate, D.H, k_count, full_flag, k_stage_offs));
   } else {
   const int u_min = (int)floor((double)p->min_unassigned_frac * (double)p->N);
+  const bool seeded = p->dtype == ADACLUSTER_BF16;
   RET_IF(launch_kstate_init(st, w.kstate, D.H, D.N));
   if (k_stage_of) RET_IF(launch_fill_i32(st, k_stage_of, (size_t)D.H * D.N, -1));
   if (p->tau_abs > 0.f) RET_IF(launch_tau(st, D.H, D.N, nullptr, nullptr, 0.f, p->tau_abs, w.tau));
@@ -456,8 +459,11 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
                                k_assign, w.bias, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, w.bcnt, nblk));
         continue;
       }
+      // (the last pass of stage 0 runs over all points against the first-stage centres as they will stay:
+      // it keeps a copy of its labels and best scores, which the final pass starts from)
+      const bool keep = seeded && t == 0 && !update;
       RET_IF(launch_assign(st, p->dtype, D.d, D.H, D.N, n_bound, 1, 0, D.cap, w.kstate, ul, K, w.cent_lp, w.bias,
-                           w.labels_tmp, w.dist2));
+                           w.labels_tmp, w.dist2, nullptr, nullptr, 0, keep ? w.lab0 : nullptr, keep ? w.score0 : nullptr));
       if (update) {
         RET_IF(launch_sort(st, D.H, D.N, n_bound, m_bound, w.labels_tmp, ul, &w.kstate->ucount,
                            sizeof(KState) / 4, &w.kstate->m_t, sizeof(KState) / 4, &w.kstate->active,
@@ -476,9 +482,14 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
   }
   if (kc_bound_out) *kc_bound_out = kc_bound < D.cap ? kc_bound : D.cap;
   RET_IF(launch_kstate_export(st, w.kstate, D.H, k_count, full_flag, k_stage_offs, w.tau, tau_used));
-  // last step of Algorithm 1: nearest centre among all stage centres, then member statistics
-  RET_IF(launch_assign(st, p->dtype, D.d, D.H, D.N, D.N, 2, 0, D.cap, w.kstate, nullptr, K, w.cent_lp, w.bias,
-                       k_labels, nullptr));
+  // last step of Algorithm 1: nearest centre among all stage centres, then member statistics.  bf16: the
+  // nearest first-stage centre of every point is known from stage 0, so only the later stages' centres are visited.
+  if (seeded)
+    RET_IF(launch_assign(st, p->dtype, D.d, D.H, D.N, D.N, 3, 0, D.cap, w.kstate, nullptr, K, w.cent_lp, w.bias,
+                         k_labels, nullptr, nullptr, nullptr, 0, nullptr, nullptr, w.lab0, w.score0))
+  else
+    RET_IF(launch_assign(st, p->dtype, D.d, D.H, D.N, D.N, 2, 0, D.cap, w.kstate, nullptr, K, w.cent_lp, w.bias,
+                         k_labels, nullptr));
   }
   RET_IF(launch_sort(st, D.H, D.N, D.N, D.cap, k_labels, nullptr, nullptr, 0, &w.kstate->ccount, sizeof(KState) / 4,
                      nullptr, 0, w.perm_k, w.offs_k, D.cap + 1, w.sort, w.poff, reduce_part_rows(), &poff_done));

@@ -16,15 +16,23 @@ namespace adac {
 // modes: 0 = fixed (row_off 0, m = m_const, n = N, every head)
 //        1 = stage (row_off = ccount, m = m_t, n = ucount, only active heads)
 //        2 = final (row_off 0, m = ccount, n = N, every head)
+//        3 = final, seeded (bf16): only the centres of the stages after the first are visited (row_off =
+//            stage_offs[1], m = ccount - row_off); every point starts from its best first-stage centre, whose
+//            label and score the last pass of stage 0 left in seed_lab / seed_score (that pass ran over all
+//            points against exactly those centres).  Labels are indices into all centres, as in mode 2.
+// keep_lab / keep_score (stage 0, last pass): a second copy of the labels and the best score, for mode 3.
 struct AssignCfg {
   int mode; int m_const; int N; int cap;
   const KState* st; const int32_t* ulist;
+  int32_t* keep_lab; float* keep_score;
+  const int32_t* seed_lab; const float* seed_score;
 };
 
 __device__ __forceinline__ bool assign_setup(const AssignCfg& c, int h, int& n, int& m, int& row_off) {
   if (c.mode == 0) { n = c.N; m = c.m_const; row_off = 0; return true; }
   const KState& s = c.st[h];
   if (c.mode == 1) { n = s.ucount; m = s.m_t; row_off = s.ccount; return s.active != 0; }
+  if (c.mode == 3) { n = c.N; row_off = s.stage_offs[1]; m = s.ccount - row_off; return true; }
   n = c.N; m = s.ccount; row_off = 0; return true;
 }
 
@@ -115,6 +123,33 @@ __global__ __launch_bounds__(256, (ACC && D == 128) ? 1 : 2) void assign_mfma(co
   float best[PB]; int btile[PB];
 #pragma unroll
   for (int pb = 0; pb < PB; ++pb) { best[pb] = -INFINITY; btile[pb] = 0; }
+  // Seeded final pass: the half-wave that owns the seed centre's accumulator position starts from the seed,
+  // in the packed form a visit of that centre would have left (score with the position code in the low bits);
+  // a negative tile marks "still the seed".
+  int slab[PB];
+  const int label_base = cfg.mode == 3 ? row_off : 0;
+  if (!ACC && cfg.seed_lab) {
+#pragma unroll
+    for (int pb = 0; pb < PB; ++pb) {
+      slab[pb] = 0;
+      if (pos[pb] < n) {
+        const int j0 = cfg.seed_lab[(size_t)h * cfg.N + pos[pb]];
+        const float s0 = cfg.seed_score[(size_t)h * cfg.N + pos[pb]];
+        const int r = j0 & 31, v0 = ((r >> 3) << 2) | (r & 3);
+        slab[pb] = j0;
+        if (hb == ((r >> 2) & 1)) {
+          best[pb] = __uint_as_float((__float_as_uint(s0) & 0xFFFFFFF0u) | (uint32_t)(15 - v0));
+          btile[pb] = -1;
+        }
+      }
+    }
+    if (m <= 0) {                      // no later stage: the first-stage labels are final
+#pragma unroll
+      for (int pb = 0; pb < PB; ++pb)
+        if (hb == 0 && pos[pb] < n) labels[(size_t)h * cfg.N + pos[pb]] = slab[pb];
+      return;
+    }
+  }
 
   const bf16raw* ch = cent + ((size_t)h * cfg.cap + row_off) * D;
   const float* bh = bias + (size_t)h * cfg.cap + row_off;
@@ -197,7 +232,8 @@ __global__ __launch_bounds__(256, (ACC && D == 128) ? 1 : 2) void assign_mfma(co
   for (int pb = 0; pb < PB; ++pb) {
     // accumulator value v of a tile is centre  32*tile + 8*(v/4) + 4*hb + v%4
     const int v = 15 - (int)(__float_as_uint(best[pb]) & 15u);   // 15-v was packed: equal scores >= 0 go to the lowest centre
-    int bidx = btile[pb] * 32 + 8 * (v >> 2) + 4 * hb + (v & 3);
+    int bidx = label_base + btile[pb] * 32 + 8 * (v >> 2) + 4 * hb + (v & 3);
+    if (!ACC && cfg.seed_lab && btile[pb] < 0) bidx = slab[pb];
     float bv = __uint_as_float(__float_as_uint(best[pb]) & 0xFFFFFFF0u);
     const float ob = __shfl_xor(bv, 32);
     const int oi = __shfl_xor(bidx, 32);
@@ -205,6 +241,7 @@ __global__ __launch_bounds__(256, (ACC && D == 128) ? 1 : 2) void assign_mfma(co
     if (hb == 0 && pos[pb] < n) {
       labels[(size_t)h * cfg.N + pos[pb]] = bidx;
       if (dist2) dist2[(size_t)h * cfg.N + pos[pb]] = fmaxf(xn2[pb] - 2.f * bv, 0.f);
+      if (!ACC && cfg.keep_lab) { cfg.keep_lab[(size_t)h * cfg.N + pos[pb]] = bidx; cfg.keep_score[(size_t)h * cfg.N + pos[pb]] = bv; }
     }
     if (ACC) blab[pb] = pos[pb] < n ? bidx : -1;
   }
@@ -1670,8 +1707,10 @@ int assign_block_sum_centres() { return ACC_MAXM; }
 
 int launch_assign(hipStream_t s, int dtype, int d, int H, int N, int n_bound, int mode, int m_const, int cap,
                   const KState* st, const int32_t* ulist, const void* X, const void* cent_lp, const float* bias,
-                  int32_t* labels, float* dist2, float* blk_sum, int32_t* blk_cnt, int P) {
-  AssignCfg c{mode, m_const, N, cap, st, ulist};
+                  int32_t* labels, float* dist2, float* blk_sum, int32_t* blk_cnt, int P, int32_t* keep_lab,
+                  float* keep_score, const int32_t* seed_lab, const float* seed_score) {
+  if ((mode == 3 || keep_lab || seed_lab) && (dtype != ADACLUSTER_BF16 || blk_sum)) return ADACLUSTER_E_INTERNAL;
+  AssignCfg c{mode, m_const, N, cap, st, ulist, keep_lab, keep_score, seed_lab, seed_score};
   if (dtype == ADACLUSTER_BF16) {
     dim3 g((n_bound + 255) / 256, H);
     const AccumOut ao{blk_sum, blk_cnt, P, (int)g.x};

@@ -24,7 +24,9 @@ int launch_sort(hipStream_t st, int H, int N, int n_bound, int m_bound, const in
 
 int launch_assign(hipStream_t s, int dtype, int d, int H, int N, int n_bound, int mode, int m_const, int cap,
                   const KState* st, const int32_t* ulist, const void* X, const void* cent_lp, const float* bias,
-                  int32_t* labels, float* dist2, float* blk_sum = nullptr, int32_t* blk_cnt = nullptr, int P = 0);
+                  int32_t* labels, float* dist2, float* blk_sum = nullptr, int32_t* blk_cnt = nullptr, int P = 0,
+                  int32_t* keep_lab = nullptr, float* keep_score = nullptr, const int32_t* seed_lab = nullptr,
+                  const float* seed_score = nullptr);
 int assign_block_sum_centres();   // most centres the assignment kernel keeps block sums for
 int launch_seg_reduce(hipStream_t s, int dtype, int d, int H, int N, int mode, int m_const, int m_bound, int P,
                       const KState* st, int normalize, int want_box, const void* X, const int32_t* perm,
