@@ -17,7 +17,7 @@
  *     are undefined after a call.  Output buffers are fully overwritten.
  *   - All work is ordered by `stream` (a hipStream_t passed as void*; NULL is
  *     the default stream): it is enqueued there, except that adacluster_attn puts
- *     the query clustering and the K/V permutation on a second, library-owned stream
+ *     the query clustering (and, for fp32 inputs, the K/V permutation) on a second, library-owned stream
  *     (one per calling thread and device, created on first use, default priority),
  *     forked from `stream` and joined back to it before the step that needs the
  *     result, so work queued on `stream` after the call still waits for all of it.
@@ -279,7 +279,8 @@ int adacluster_quest_scores(int32_t H, int32_t Lq, int32_t Lk, int32_t d, int32_
  * stream at their stage boundaries (adacluster_qcluster and adacluster_kcluster record their own).
  * adacluster_profile_read waits for the last recorded call
  * and writes, to the HOST array ms[7], the milliseconds of: query clustering, Algorithm 1,
- * selection (stand-alone sparse_attn: the two label sorts), K/V permutation, planning, the
+ * selection (stand-alone sparse_attn: the two label sorts), K/V permutation (fp32 inputs only: bf16
+ * rows are read where they are, through the key permutation), planning, the
  * attention kernel, and the segmented reduction over all N keys that ends Algorithm 1 (one launch,
  * also counted inside Algorithm 1); -1 for a stage the call did not run.  In adacluster_attn the two clusterings
  * run side by side and each is timed from the start of the call, so their sum exceeds the time

@@ -214,6 +214,12 @@ Dims dims_of(const adacluster_params* p) {
   return D;
 }
 
+// bf16: the attention kernel takes every key row by its byte offset, so K and V stay where they are and the
+// row-offset table of a query cluster is written through the key permutation (no permuted copies; measured
+// against gathering K and V into cluster order first: the same attention time, and the gather with its 4 bytes
+// of HBM traffic per input byte gone).  fp32: the kernel walks row ranges of the permuted copies.
+static bool rows_in_place(const adacluster_params* p) { return p->dtype == ADACLUSTER_BF16; }
+
 size_t layout(const adacluster_params* p, WS* w, unsigned char* base) {
   const Dims D = dims_of(p);
   const size_t H = D.H, N = D.N, d = D.d, es = esize(p);
@@ -266,8 +272,8 @@ size_t layout(const adacluster_params* p, WS* w, unsigned char* base) {
   TAKE(offs_q, int32_t*, H * (size_t)(D.Cq + 1) * 4);
   TAKE(perm_k, int32_t*, H * N * 4);
   TAKE(offs_k, int32_t*, H * (size_t)(D.cap + 1) * 4);
-  TAKE(Kp, void*, H * N * d * es);
-  TAKE(Vp, void*, H * N * d * es);
+  TAKE(Kp, void*, rows_in_place(p) ? 256 : H * N * d * es);      // permuted copies: fp32 only
+  TAKE(Vp, void*, rows_in_place(p) ? 256 : H * N * d * es);
   TAKE(rng_start, int32_t*, H * (size_t)D.Cq * D.maxr * 4);
   TAKE(rng_pre, int32_t*, H * (size_t)D.Cq * (D.maxr + 1) * 4);
   TAKE(rng_cnt, int32_t*, H * (size_t)D.Cq * 4);
@@ -523,18 +529,19 @@ int run_permute(const adacluster_params* p, const WS& w, hipStream_t st, const v
 // range lists and query tiles from the selection, then the attention kernel over the permuted rows
 int run_plan_attention(const adacluster_params* p, const WS& w, hipStream_t st, const void* Q, void* O,
                        const int32_t* k_count, const int32_t* sel_idx, const int32_t* sel_cnt, int prof_from,
-                       hipEvent_t permute_done) {
+                       hipEvent_t permute_done, const void* K = nullptr, const void* V = nullptr) {
   const Dims D = dims_of(p);
+  const bool inplace = K && V && rows_in_place(p);
   const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)D.d);
   RET_IF(launch_plan_sparse(st, p->dtype, D.H, D.Cq, D.cap, D.maxr, D.maxtiles, D.BM, w.offs_q, D.Cq + 1, w.offs_k,
                             D.cap + 1, k_count, sel_idx, sel_cnt, w.rng_start, w.rng_pre, w.rng_cnt, w.tiles, w.ntiles,
                             w.merge, w.nmerge, D.d * (int)esize(p), p->dtype == ADACLUSTER_BF16 ? w.krow : nullptr,
-                            attn_krow_stride(D.N)));
+                            attn_krow_stride(D.N), inplace ? w.perm_k : nullptr, D.N));
   prof_mark(EV_PLAN, st, prof_from);
   if (permute_done && hipStreamWaitEvent(st, permute_done, 0) != hipSuccess)
     return fail(ADACLUSTER_E_INTERNAL, "stream join failed");
   if (permute_done) prof_mark(EV_JOIN2, st);
-  RET_IF(launch_attention(st, p->dtype, D.d, D.H, D.N, D.Cq, D.maxtiles, D.maxr, scale, Q, w.Kp, w.Vp, O, w.perm_q,
+  RET_IF(launch_attention(st, p->dtype, D.d, D.H, D.N, D.Cq, D.maxtiles, D.maxr, scale, Q, inplace ? K : w.Kp, inplace ? V : w.Vp, O, w.perm_q,
                           w.tiles, w.ntiles, w.rng_start, w.rng_pre, w.rng_cnt, w.part_o, w.part_ml, w.merge, w.nmerge,
                           w.krow, attn_krow_stride(D.N)));
   prof_mark(EV_ATTN, st, permute_done ? EV_JOIN2 : -1);
@@ -683,8 +690,8 @@ int adacluster_sparse_attn(const adacluster_params* p, const void* Q, const void
   RET_IF(launch_sort(st, D.H, D.N, D.N, D.cap, k_labels, nullptr, nullptr, 0, k_count, 1, nullptr, 0, w.perm_k, w.offs_k,
                      D.cap + 1, w.sort));
   prof_mark(EV_SELECT, st);   // (time of the two label sorts when called stand-alone)
-  if ((rc = run_permute(p, w, st, K, V, -1))) return rc;
-  return run_plan_attention(p, w, st, Q, O, k_count, sel_idx, sel_cnt, -1, nullptr);
+  if (!rows_in_place(p) && (rc = run_permute(p, w, st, K, V, -1))) return rc;
+  return run_plan_attention(p, w, st, Q, O, k_count, sel_idx, sel_cnt, -1, nullptr, K, V);
 }
 
 int adacluster_attn(const adacluster_params* p, const void* Q, const void* K, const void* V, void* O,
@@ -737,7 +744,7 @@ int adacluster_attn(const adacluster_params* p, const void* Q, const void* K, co
   // The K/V permutation needs only the key label sort, which is final before the last centroid
   // update of the key clustering: it goes to the second stream too (behind the query clustering
   // there) and runs beside that update, the selection and the planning.
-  const bool fork2 = !rc && !rck;
+  const bool fork2 = !rc && !rck && !rows_in_place(p);     // (bf16 has no permutation step)
   int rcp = 0;
   if (fork2) {
     if (hipStreamWaitEvent(aux->s, aux->fork, 0) != hipSuccess)
@@ -760,7 +767,7 @@ int adacluster_attn(const adacluster_params* p, const void* Q, const void* K, co
   prof_mark(EV_SELECT, st, EV_JOIN);
   // both label sorts were left in the workspace by the clustering steps; the attention step joins the
   // permutation of K and V (second stream) before its first kernel that reads it
-  rc = run_plan_attention(p, w, st, Q, O, k_count, sel_idx, sel_cnt, EV_SELECT, aux->join2);
+  rc = run_plan_attention(p, w, st, Q, O, k_count, sel_idx, sel_cnt, EV_SELECT, fork2 ? aux->join2 : nullptr, K, V);
   return rc ? drained(rc) : 0;
 }
 

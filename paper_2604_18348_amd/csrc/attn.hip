@@ -81,7 +81,8 @@ __global__ __launch_bounds__(256) void plan_sparse(int Cq, int cap, int maxr, in
                             const int32_t* __restrict__ k_count,
                             const int32_t* __restrict__ sel_idx, const int32_t* __restrict__ sel_cnt,
                             int32_t* __restrict__ rng_start, int32_t* __restrict__ rng_pre,
-                            int32_t* __restrict__ rng_cnt, int32_t* __restrict__ krow, size_t kstride) {
+                            int32_t* __restrict__ rng_cnt, int32_t* __restrict__ krow, size_t kstride,
+                            const int32_t* __restrict__ perm_k, int N) {
   const int h = blockIdx.y, i = blockIdx.x, tid = threadIdx.x;
   int32_t* rs = rng_start + ((size_t)h * Cq + i) * maxr;
   int32_t* rp = rng_pre + ((size_t)h * Cq + i) * (maxr + 1);
@@ -148,7 +149,8 @@ __global__ __launch_bounds__(256) void plan_sparse(int Cq, int cap, int maxr, in
   if (!krow) return;       // (the fp32 kernel walks the ranges itself)
   const int nr = s_nr, total = s_total;
   int32_t* kr = krow + ((size_t)h * Cq + i) * kstride;
-  const int first = nr > 0 ? rs[0] * row_bytes : 0;
+  const int32_t* pk = perm_k ? perm_k + (size_t)h * N : nullptr;      // sorted position -> token (rows stay where they are)
+  const int first = nr > 0 ? (pk ? pk[rs[0]] : rs[0]) * row_bytes : 0;
   const int padded = (total + 63) / 64 * 64 + KROW_PAD;
   // the search runs on a copy of the range table in LDS when it fits: its steps depend on one another, and
   // from global memory each of them is a trip to the L2
@@ -165,7 +167,8 @@ __global__ __launch_bounds__(256) void plan_sparse(int Cq, int cap, int maxr, in
       if (p < total) {
         int lo = 0, hi = nr - 1;                 // last range whose first position is <= p
         while (lo < hi) { const int mid = (lo + hi + 1) >> 1; if (srp[mid] <= p) lo = mid; else hi = mid - 1; }
-        off = (srs[lo] + (p - srp[lo])) * row_bytes;
+        const int row = srs[lo] + (p - srp[lo]);
+        off = (pk ? pk[row] : row) * row_bytes;
       }
       kr[p] = off;
     }
@@ -951,9 +954,10 @@ int launch_plan_sparse(hipStream_t s, int dtype, int H, int Cq, int cap, int max
                        const int32_t* q_offs, int q_offs_stride, const int32_t* k_offs, int k_offs_stride,
                        const int32_t* k_count, const int32_t* sel_idx, const int32_t* sel_cnt,
                        int32_t* rng_start, int32_t* rng_pre, int32_t* rng_cnt, int32_t* tiles, int32_t* ntiles,
-                       int32_t* merge, int32_t* nmerge, int row_bytes, int32_t* krow, size_t kstride) {
+                       int32_t* merge, int32_t* nmerge, int row_bytes, int32_t* krow, size_t kstride,
+                       const int32_t* perm_k, int N) {
   plan_sparse<<<dim3(Cq, H), 256, 0, s>>>(Cq, cap, maxr, row_bytes, k_offs, k_offs_stride, k_count, sel_idx, sel_cnt,
-                                         rng_start, rng_pre, rng_cnt, krow, kstride);
+                                         rng_start, rng_pre, rng_cnt, krow, kstride, perm_k, N);
   plan_tiles<<<H, 256, 0, s>>>(Cq, maxr, maxtiles, BM, SPLIT_SLOTS, dtype == ADACLUSTER_BF16 ? 1 : 0, q_offs,
                               q_offs_stride, rng_pre, rng_cnt, tiles, ntiles, merge, nmerge);
   return hipGetLastError() == hipSuccess ? 0 : ADACLUSTER_E_INTERNAL;

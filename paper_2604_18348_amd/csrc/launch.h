@@ -93,7 +93,7 @@ int launch_plan_sparse(hipStream_t s, int dtype, int H, int Cq, int cap, int max
                        const int32_t* q_offs, int q_offs_stride, const int32_t* k_offs, int k_offs_stride,
                        const int32_t* k_count, const int32_t* sel_idx, const int32_t* sel_cnt,
                        int32_t* rng_start, int32_t* rng_pre, int32_t* rng_cnt, int32_t* tiles, int32_t* ntiles,
-                       int32_t* merge, int32_t* nmerge, int row_bytes, int32_t* krow, size_t kstride);
+                       int32_t* merge, int32_t* nmerge, int row_bytes, int32_t* krow, size_t kstride, const int32_t* perm_k = nullptr, int N = 0);
 int launch_plan_dense(hipStream_t s, int H, int N, int maxtiles, int BM, int32_t* rng_start, int32_t* rng_pre,
                       int32_t* rng_cnt, int32_t* tiles, int32_t* ntiles, int row_bytes, int32_t* krow, size_t kstride);
 // entries per (head, query cluster) of the table of key-row byte offsets the bf16 attention kernel loads by

@@ -87,7 +87,8 @@ def mfma_microbench_tflops(B, iters=20000):
 def measure(name, steps, warmup, spinup_ms=500.0, dense_steps=3, profile_reps=None, want_hbm=True):
     """One configuration, end to end: the fused call cold and warm-started, its stage times, the dense call
     on the same kernel, the attention kernel against the bf16 MFMA peak, and the HBM-bound passes (label
-    sorts, K/V row gather, segmented reduction) against the HBM peak.  Returns a dict of plain numbers."""
+    sorts, segmented reduction, and for fp32 inputs the K/V row gather) against the HBM peak.  Returns a
+    dict of plain numbers."""
     import torch
     from . import binding as B
     from . import workloads as wl
