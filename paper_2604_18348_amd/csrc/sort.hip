@@ -52,8 +52,18 @@ __global__ __launch_bounds__(8 * RBINS) void radix_scan(int nseg, int32_t* __res
   int32_t* hh = hist + (size_t)h * nseg * RBINS;
   const int per = (nseg + 7) / 8;
   const int s0 = g * per, s1 = min(nseg, s0 + per);
+  // The counts are read in batches of eight independent loads (a load per step behind the store of the step
+  // before would make every segment a round trip of its own): first for the group's total, then again, once
+  // the base is known, to write the running positions.
+  constexpr int BATCH = 8;
   int run = 0;
-  for (int s = s0; s < s1; ++s) { const int c = hh[s * RBINS + b]; hh[s * RBINS + b] = run; run += c; }
+  for (int sb = s0; sb < s1; sb += BATCH) {
+    int c[BATCH];
+#pragma unroll
+    for (int k = 0; k < BATCH; ++k) c[k] = sb + k < s1 ? hh[(sb + k) * RBINS + b] : 0;
+#pragma unroll
+    for (int k = 0; k < BATCH; ++k) run += c[k];
+  }
   __shared__ int32_t gsum[8][RBINS];
   __shared__ int32_t tot[RBINS];
   gsum[g][b] = run;
@@ -62,9 +72,18 @@ __global__ __launch_bounds__(8 * RBINS) void radix_scan(int nseg, int32_t* __res
   for (int i = 0; i < 8; ++i) { const int v = gsum[i][b]; if (i < g) before += v; all += v; }
   if (g == 0) tot[b] = all;
   __syncthreads();
-  int base = before;
-  for (int i = 0; i < b; ++i) base += tot[i];
-  for (int s = s0; s < s1; ++s) hh[s * RBINS + b] += base;
+  int pos = before;
+  for (int i = 0; i < b; ++i) pos += tot[i];
+  for (int sb = s0; sb < s1; sb += BATCH) {
+    int c[BATCH];
+#pragma unroll
+    for (int k = 0; k < BATCH; ++k) c[k] = sb + k < s1 ? hh[(sb + k) * RBINS + b] : 0;
+#pragma unroll
+    for (int k = 0; k < BATCH; ++k) {
+      if (sb + k < s1) hh[(sb + k) * RBINS + b] = pos;
+      pos += c[k];
+    }
+  }
 }
 
 // scatter one pass: (label, value) pairs move to their stable sorted position
