@@ -376,10 +376,10 @@ __device__ __forceinline__ s16x4_t lds_read_tr16(const char* p) {
 // before a workgroup barrier; hiding the loads from the compiler leaves that protocol in charge.  Each lane
 // loads `bytes` at sbase + voff; the wave's data land at lds_addr + lane * bytes (M0 carries the LDS address).
 __device__ __forceinline__ void dma_b128(uint32_t lds_addr, uint32_t voff, const void* sbase) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(sbase) : "memory");
 }
 __device__ __forceinline__ void dma_b32(uint32_t lds_addr, uint32_t voff, const void* sbase) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(sbase) : "memory");
 }
 
 // s_waitcnt with only the vector-memory counter set (gfx9 encoding: vmcnt[3:0] and [15:14])
