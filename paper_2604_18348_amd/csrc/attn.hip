@@ -557,7 +557,9 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
     // All K operands of the tile are requested before the first product, and (below) the V operands before
     // the soft-max arithmetic: an LDS read takes a hundred cycles or more to come back, and the compiler, left
     // alone, requests an operand only one product ahead of its use.  The empty asm statements are fences for
-    // memory operations only: reads do not sink below them, the register-only MFMAs and VALU work move freely.
+    // memory operations (reads do not sink below them); the scheduling barrier behind each keeps the products
+    // from rising above the reads that follow their own operands' (a product placed between two reads makes the
+    // wave wait for its operand before the next read is even requested: measured, 5 % of the kernel at d=64).
     f32x16_t sacc[2];
     bf16x8_t ka[2][KS];
 #pragma unroll
@@ -566,6 +568,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
       for (int ks = 0; ks < KS; ++ks)
         ka[kb][ks] = *reinterpret_cast<const bf16x8_t*>(ks_ + kb * 32 * ROWB + kaddr[ks]);
     asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -584,6 +587,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
           va[db][kb][s2] = *reinterpret_cast<const bf16x8_t*>(both);
         }
     asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
     // accumulator value v of block kb is key  kb*32 + 8*(v/4) + 4*hb + v%4
     if (MASK) {
 #pragma unroll
@@ -640,26 +644,29 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
       probabilities();
     }
     lrun += rsum;
-    asm volatile("" ::: "memory");          // the V operands that were not requested ahead are requested from here on
+    asm volatile("" ::: "memory");          // the V operands that were not requested ahead are requested from here on,
+    bf16x8_t vb[DB - VPRE > 0 ? DB - VPRE : 1][2][2];      // ALL of them before the first product (second fence): left
+#pragma unroll                                            // alone, the compiler requests an operand one product ahead
+    for (int db = VPRE; db < DB; ++db)                     // of its use and every product then waits out an LDS read
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          const char* vp = vs_ + (kb * 32 + 16 * s2) * ROWB + vaddr[db];
+          const s16x4_t lo = lds_read_tr16(vp), hi = lds_read_tr16(vp + 8 * ROWB);
+          const s16x4_t both[2] = {lo, hi};
+          vb[db - VPRE][kb][s2] = *reinterpret_cast<const bf16x8_t*>(both);
+        }
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
-      bf16x8_t vb[2][2];
-      if (db >= VPRE) {
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int s2 = 0; s2 < 2; ++s2) {
-            const char* vp = vs_ + (kb * 32 + 16 * s2) * ROWB + vaddr[db];
-            const s16x4_t lo = lds_read_tr16(vp), hi = lds_read_tr16(vp + 8 * ROWB);
-            const s16x4_t both[2] = {lo, hi};
-            vb[kb][s2] = *reinterpret_cast<const bf16x8_t*>(both);
-          }
-      }
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2)
-          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(db < VPRE ? va[db < VPRE ? db : 0][kb][s2] : vb[kb][s2], pf[kb][s2], oacc[db], 0, 0, 0);
+          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(db < VPRE ? va[db < VPRE ? db : 0][kb][s2] : vb[db >= VPRE ? db - VPRE : 0][kb][s2],
+                                                             pf[kb][s2], oacc[db], 0, 0, 0);
     }
   };
 
