@@ -376,10 +376,10 @@ __device__ __forceinline__ s16x4_t lds_read_tr16(const char* p) {
 // before a workgroup barrier; hiding the loads from the compiler leaves that protocol in charge.  Each lane
 // loads `bytes` at sbase + voff; the wave's data land at lds_addr + lane * bytes (M0 carries the LDS address).
 __device__ __forceinline__ void dma_b128(uint32_t lds_addr, uint32_t voff, const void* sbase) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(sbase) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(sbase) : "memory", "m0");
 }
 __device__ __forceinline__ void dma_b32(uint32_t lds_addr, uint32_t voff, const void* sbase) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(sbase) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(sbase) : "memory", "m0");
 }
 
 // s_waitcnt with only the vector-memory counter set (gfx9 encoding: vmcnt[3:0] and [15:14])
@@ -412,6 +412,8 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
   constexpr int BN = 64, NT = NW * 64, KS = D / 16, DB = D / 32, CH = D / 8, ROWB = D * 2;
   constexpr int ITEMS = BN * CH, PT = ITEMS / NT, TILEB = BN * ROWB, PD = NBUF - 1;
   constexpr int VM_STEP = 2 * PT + 1;             // vector-memory operations a wave issues per tile
+  constexpr int ISSUE_J0 = D == 128 ? 2 : 3, ISSUE_STRIDE = (2 * KS - ISSUE_J0) / VM_STEP;     // the requests spread over the S products
+  static_assert(ISSUE_STRIDE >= 1, "more requests than S products to put them behind");
   constexpr int RIDXB = NBUF * BN * 4;            // bytes of the row-offset slots at the start of LDS
   constexpr int KRING = NBUF * TILEB;             // bytes of the ring of K tiles (the ring of V tiles follows it)
   static_assert(ITEMS % NT == 0, "tile chunks must divide evenly over the threads");
@@ -521,6 +523,12 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
     if (lane < BN / NW)
       dma_b32(lds0 + st * (BN * 4) + wave_u * (BN / NW) * 4, ridx_voff, krow + (size_t)t * BN);
   };
+  auto issue_tile_op = [&](int st, const int32_t* off, int n) __attribute__((always_inline)) {     // operation n of issue_tile
+    const int i = n >> 1;
+    const uint32_t dst = lds0 + RIDXB + st * TILEB + (wave_u * 64 + i * NT) * 16;
+    if ((n & 1) == 0) dma_b128(dst, (uint32_t)off[i] + (uint32_t)lswz_k[i], Kh);
+    else dma_b128(dst + KRING, (uint32_t)off[i] + (uint32_t)lswz_v[i], Vh);
+  };
   auto issue_tile = [&](int st, const int32_t* off) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
@@ -551,9 +559,13 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
   const float sc = a.scale_log2e;
   constexpr float P_LIMIT = 65536.f;      // a tile whose probabilities sum past this moves the reference
 
+  // `prep` and `issue(n)`, n < ND: the requests of the tiles further ahead (row offsets out of LDS, then ND
+  // direct-to-LDS loads), placed by compute_tile where they cost nothing: the offsets are read behind the K
+  // operands, the loads are issued one by one between the S products, in the shadow of the matrix pipe.
   auto compute_tile = [&](const char* ks_, const char* vs_, int nvalid /* < BN only on a masked tail tile */,
-                          auto masked) __attribute__((always_inline)) {
+                          auto masked, auto&& prep, auto&& issue, auto nd_) __attribute__((always_inline)) {
     constexpr bool MASK = decltype(masked)::value;
+    constexpr int ND = decltype(nd_)::value;
     // All K operands of the tile are requested before the first product, and (below) the V operands before
     // the soft-max arithmetic: an LDS read takes a hundred cycles or more to come back, and the compiler, left
     // alone, requests an operand only one product ahead of its use.  The empty asm statements are fences for
@@ -568,12 +580,22 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
       for (int ks = 0; ks < KS; ++ks)
         ka[kb][ks] = *reinterpret_cast<const bf16x8_t*>(ks_ + kb * 32 * ROWB + kaddr[ks]);
     asm volatile("" ::: "memory");
+    prep();
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
+      for (int ks = 0; ks < KS; ++ks) {
         sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kb][ks], qf[ks], ks == 0 ? zero16 : sacc[kb], 0, 0, 0);
+        // request n goes behind product ISSUE_J0 + n * ISSUE_STRIDE
+        const int j = kb * KS + ks;
+        if (ND > 0 && j >= ISSUE_J0 && (j - ISSUE_J0) % ISSUE_STRIDE == 0 && (j - ISSUE_J0) / ISSUE_STRIDE < ND) {
+          __builtin_amdgcn_sched_barrier(0);
+          issue((j - ISSUE_J0) / ISSUE_STRIDE);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    static_assert(ND == 0 || ISSUE_J0 + (ND - 1) * ISSUE_STRIDE < 2 * KS, "every request finds a product to go behind");
     bf16x8_t va[VPRE > 0 ? VPRE : 1][2][2];
 #pragma unroll
     for (int db = 0; db < VPRE; ++db)
@@ -682,11 +704,20 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
   auto step = [&](auto stage, int t) __attribute__((always_inline)) {
     constexpr int U = decltype(stage)::value, G = (U + PD) % NBUF;
     int32_t off[PT];
+    auto prep = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < PT; ++i) off[i] = reinterpret_cast<const int32_t*>(lds + U * (BN * 4))[lrow[i]];
-    issue_tile(G, off);
-    issue_ridx(G, t + 2 * PD);
-    if (wave_has_rows) compute_tile(ldk + U * TILEB, ldk + U * TILEB, BN, std::false_type{});
+      for (int i = 0; i < PT; ++i) off[i] = reinterpret_cast<const int32_t*>(lds + U * (BN * 4))[lrow[i]];
+    };
+    auto issue = [&](int n) __attribute__((always_inline)) {
+      if (n < 2 * PT) issue_tile_op(G, off, n); else issue_ridx(G, t + 2 * PD);
+    };
+    if (wave_has_rows) {
+      compute_tile(ldk + U * TILEB, ldk + U * TILEB, BN, std::false_type{}, prep, issue, std::integral_constant<int, VM_STEP>{});
+    } else {               // a wave without query rows still loads its share of the tiles
+      prep();
+#pragma unroll
+      for (int n = 0; n < VM_STEP; ++n) issue(n);
+    }
     wait_vmcnt<(PD - 1) * VM_STEP>();
     lds_barrier();
   };
@@ -724,7 +755,8 @@ __global__ __launch_bounds__(NW * 64, MINB) void attn_mfma(AttnArgs a) {
     }
     wait_vmcnt<0>();       // nothing of this wave is still on its way to LDS when it ends
     const int u = Tlast % NBUF;
-    if (wave_has_rows) compute_tile(ldk + u * TILEB, ldk + u * TILEB, total - Tlast * BN, std::true_type{});
+    if (wave_has_rows) compute_tile(ldk + u * TILEB, ldk + u * TILEB, total - Tlast * BN, std::true_type{}, [] {}, [](int) {},
+                                    std::integral_constant<int, 0>{});
   }
 
   // O^T accumulator value v of block db is column  db*32 + 8*(v/4) + 4*hb + v%4  of query c
