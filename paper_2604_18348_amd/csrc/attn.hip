@@ -914,26 +914,40 @@ __global__ __launch_bounds__(128) void attn_f32(AttnArgs a) {
 template <int D>
 __global__ __launch_bounds__(256) void attn_merge(AttnArgs a, const int32_t* __restrict__ merge,
                                                   const int32_t* __restrict__ nmerge) {
+  // blockIdx.z takes every gridDim.z-th group of rows; the (at most 16) chunks of a row are loaded together,
+  // not one after the other: the kernel is a handful of dependent round trips either way, so what counts is
+  // how many of its loads are in flight at once.
+  constexpr int MAXP = 16;                       // most chunks a list is cut into (plan_tiles)
   const int h = blockIdx.y, e = blockIdx.x;
   if (e >= nmerge[h]) return;
   const int32_t* ml = merge + ((size_t)h * a.slots + e) * 4;
-  const int row0 = ml[0], nrows = ml[1], slot0 = ml[2], pieces = ml[3];
+  const int row0 = ml[0], nrows = ml[1], slot0 = ml[2], pieces = min(ml[3], MAXP);
   const int32_t* pq = a.perm_q ? a.perm_q + (size_t)h * a.N : nullptr;
   bf16raw* Oh = (bf16raw*)a.O + (size_t)h * a.N * D;
   constexpr int LPR = D / 4;                     // lanes per row, four columns each
-  for (int r = threadIdx.x / LPR; r < nrows; r += 256 / LPR) {
-    const int col = (threadIdx.x % LPR) * 4;
+  const int col = (threadIdx.x % LPR) * 4;
+  for (int r = blockIdx.z * (256 / LPR) + threadIdx.x / LPR; r < nrows; r += gridDim.z * (256 / LPR)) {
+    float ms[MAXP], ls[MAXP];
+    float4 os[MAXP];
+#pragma unroll
+    for (int s = 0; s < MAXP; ++s) {
+      const size_t so = ((size_t)h * a.slots + slot0 + min(s, pieces - 1)) * a.BM + r;
+      ms[s] = a.part_ml[so * 2];
+      ls[s] = a.part_ml[so * 2 + 1];
+      os[s] = *reinterpret_cast<const float4*>(a.part_o + so * D + col);
+    }
     float m = -INFINITY;
-    for (int s = 0; s < pieces; ++s)
-      m = fmaxf(m, a.part_ml[(((size_t)h * a.slots + slot0 + s) * a.BM + r) * 2]);
+#pragma unroll
+    for (int s = 0; s < MAXP; ++s) if (s < pieces) m = fmaxf(m, ms[s]);
     float l = 0.f;
     float4 o = {0.f, 0.f, 0.f, 0.f};
-    for (int s = 0; s < pieces; ++s) {
-      const size_t so = ((size_t)h * a.slots + slot0 + s) * a.BM + r;
-      const float w = __builtin_amdgcn_exp2f((a.part_ml[so * 2] - m) * a.scale_log2e);
-      l = fmaf(w, a.part_ml[so * 2 + 1], l);
-      const float4 v = *reinterpret_cast<const float4*>(a.part_o + so * D + col);
-      o.x = fmaf(w, v.x, o.x); o.y = fmaf(w, v.y, o.y); o.z = fmaf(w, v.z, o.z); o.w = fmaf(w, v.w, o.w);
+#pragma unroll
+    for (int s = 0; s < MAXP; ++s) {
+      if (s < pieces) {                          // in chunk order, as before: the sums are the same to the bit
+        const float w = __builtin_amdgcn_exp2f((ms[s] - m) * a.scale_log2e);
+        l = fmaf(w, ls[s], l);
+        o.x = fmaf(w, os[s].x, o.x); o.y = fmaf(w, os[s].y, o.y); o.z = fmaf(w, os[s].z, o.z); o.w = fmaf(w, os[s].w, o.w);
+      }
     }
     const float inv = l > 0.f ? 1.0f / l : 0.f;
     const int tok = pq ? pq[row0 + r] : row0 + r;
@@ -1027,8 +1041,8 @@ int launch_attention(hipStream_t s, int dtype, int d, int H, int N, int Cq, int 
       else attn_mfma<128, A128_NW, A128_NBUF, A128_MINB, A128_VPRE><<<g, A128_NW * 64, 0, s>>>(a);
     }
     if (merge) {      // the chunks of cut key lists (none for the dense branch)
-      if (d == 64) attn_merge<64><<<dim3(SPLIT_SLOTS, H), 256, 0, s>>>(a, merge, nmerge);
-      else attn_merge<128><<<dim3(SPLIT_SLOTS, H), 256, 0, s>>>(a, merge, nmerge);
+      if (d == 64) attn_merge<64><<<dim3(SPLIT_SLOTS, H, 4), 256, 0, s>>>(a, merge, nmerge);
+      else attn_merge<128><<<dim3(SPLIT_SLOTS, H, 4), 256, 0, s>>>(a, merge, nmerge);
     }
   } else {
     if (d == 64) attn_f32<64><<<g, 128, 0, s>>>(a);
