@@ -20,11 +20,11 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-# HBM-side traffic of one attention-kernel launch, bytes: FETCH_SIZE (divided by the 0.504 the counter
+# HBM-side traffic of one attention-kernel launch, bytes: FETCH_SIZE (divided by the 0.50 the counter
 # reads for a plain copy of known size) + WRITE_SIZE of the two rocprofv3 --pmc passes summarised in
 # profiles/attn_pipeline_<config>.txt.  A counter cannot be read from inside this script, so the
 # figures are stored; a config without a profile reports null.
-PROFILED_ATTN_TRAFFIC_BYTES = {"c2": 918.4e6, "c3": 291.7e6, "c4": 3149.0e6, "c5": 4448.9e6}
+PROFILED_ATTN_TRAFFIC_BYTES = {"c2": 957.1e6, "c3": 293.8e6, "c4": 3104.2e6, "c5": 4492.0e6}
 
 
 def cpu_baseline(name, wl, target_s=15.0):

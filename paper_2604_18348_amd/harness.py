@@ -45,7 +45,8 @@ def executed_pairs(outs, p):
     tot = 0
     cols = np.arange(si.shape[2])[None, :]
     for h in range(p.H):
-        keys = np.where(cols < sc[h][:, None], ks[h][si[h]], 0).sum(axis=1)
+        live = cols < sc[h][:, None]                       # entries past a list's count are not written
+        keys = np.where(live, ks[h][np.where(live, si[h], 0)], 0).sum(axis=1)
         tot += int((qs[h] * keys).sum())
     return tot
 
