@@ -59,36 +59,59 @@ def cpu_baseline(name, wl, target_s=15.0):
                     sample="fp64 numpy oracle, full call on %d of %d heads (%.1f s measured), scaled by H"
                            % (len(heads), H, dt))
 
-    Q, K, V = wl.make_qkv(name, heads=[0])
-    Q, K, V = Q[0].astype(np.float64), K[0].astype(np.float64), V[0].astype(np.float64)
-    t = [time.perf_counter()]
-    tau = float(np.float32(P["tau_abs"])) if P["tau_abs"] > 0 else orc.tau_from_factor(K[None], P["tau_factor"], P["k_m0"], P["k_iters"], rf)
-    t.append(time.perf_counter())
-    qc = orc.query_kmeans(Q, P["q_clusters"], P["q_iters"], round_fn=rf)
-    t.append(time.perf_counter())
-    kc = orc.multistage_kmeans(K, tau, P["k_max_clusters"], P["k_m0"], P["k_m_min"], P["k_iters"], P["k_max_stages"],
-                               P["min_unassigned_frac"], rf)
-    t.append(time.perf_counter())
-    S = orc.cluster_scores(P["score_mode"], qc["centroids"], kc["centroids"], kc["box_min"], kc["box_max"], kc["sizes"])
     scale = 1.0 / math.sqrt(d)
-    sel = orc.select_topk(S, P["topk"]) if P["select_mode"] == 0 else orc.select_topp(S, kc["sizes"], qc["mean_norm"] * scale, P["top_p"])
-    t.append(time.perf_counter())
-    # the attention sample: a probe on every 512th query row sizes the stride so that the sample itself
-    # takes about two thirds of the time asked for
-    orc.sparse_attention_gather(Q, K, V, qc["labels"], kc["labels"], sel, scale, rows=np.arange(0, N, 512))
-    probe_s = time.perf_counter() - t[-1]
-    stride = int(min(512, max(1, math.ceil(probe_s * 512 / (target_s * 0.67)))))
-    t_attn0 = time.perf_counter()
-    rows = np.arange(0, N, stride)
-    orc.sparse_attention_gather(Q, K, V, qc["labels"], kc["labels"], sel, scale, rows=rows)
-    t_attn1 = time.perf_counter()
-    dt = [b - a for a, b in zip(t[:-1], t[1:])] + [t_attn1 - t_attn0]
-    head_s = dt[0] + dt[1] + dt[2] + dt[3] + dt[4] * (N / len(rows))
+
+    def one_head(head, stride):
+        """every step of the call on one head; stride None: sized by a probe.  -> (step seconds, stride, head seconds)"""
+        Q, K, V = wl.make_qkv(name, heads=[head])
+        Q, K, V = Q[0].astype(np.float64), K[0].astype(np.float64), V[0].astype(np.float64)
+        t = [time.perf_counter()]
+        tau = float(np.float32(P["tau_abs"])) if P["tau_abs"] > 0 else orc.tau_from_factor(K[None], P["tau_factor"], P["k_m0"], P["k_iters"], rf)
+        t.append(time.perf_counter())
+        qc = orc.query_kmeans(Q, P["q_clusters"], P["q_iters"], round_fn=rf)
+        t.append(time.perf_counter())
+        kc = orc.multistage_kmeans(K, tau, P["k_max_clusters"], P["k_m0"], P["k_m_min"], P["k_iters"], P["k_max_stages"],
+                                   P["min_unassigned_frac"], rf)
+        t.append(time.perf_counter())
+        S = orc.cluster_scores(P["score_mode"], qc["centroids"], kc["centroids"], kc["box_min"], kc["box_max"], kc["sizes"])
+        sel = orc.select_topk(S, P["topk"]) if P["select_mode"] == 0 else orc.select_topp(S, kc["sizes"], qc["mean_norm"] * scale, P["top_p"])
+        t.append(time.perf_counter())
+
+        def attention(st):
+            t0 = time.perf_counter()
+            rows = np.arange(0, N, st)
+            orc.sparse_attention_gather(Q, K, V, qc["labels"], kc["labels"], sel, scale, rows=rows)
+            return time.perf_counter() - t0, len(rows)
+
+        if stride is None:
+            # a probe on every 512th query row sizes the stride so that the sample takes about two thirds of
+            # the time asked for; the probe's time is partly per-cluster overhead, so one refinement follows
+            probe_s, _ = attention(512)
+            stride = int(min(512, max(1, math.ceil(probe_s * 512 / (target_s * 0.67)))))
+            ta, nrows = attention(stride)
+            if stride > 1 and ta < 0.3 * target_s:
+                stride = int(max(1, math.floor(stride * ta / (target_s * 0.67))))
+                ta, nrows = attention(stride)
+        else:
+            ta, nrows = attention(stride)
+        dt = [b - a for a, b in zip(t[:-1], t[1:])] + [ta]
+        return dt, stride, dt[0] + dt[1] + dt[2] + dt[3] + dt[4] * (N / nrows)
+
+    # head 0, then further heads (spread over the head range) while less than about 10 s have been measured
+    dts, stride, hs = one_head(0, None)
+    measured, heads, head_secs = sum(dts), [0], [hs]
+    for head in (H // 2, H - 1, H // 4):
+        if measured >= 10.0 or head in heads:
+            break
+        d2, _, h2 = one_head(head, stride)
+        measured += sum(d2); heads.append(head); head_secs.append(h2)
+    head_s = float(np.mean(head_secs))
     return dict(value=head_s * 1e3 * H, unit="ms/call", cores=int(cores), kind="oracle",
-                sample="fp64 numpy oracle on head 0 of %d, step by step: threshold pass %.1f s, query clustering %.1f s, "
-                       "Algorithm 1 %.1f s, selection %.1f s (all in full), attention on every %dth query row %.1f s "
-                       "(scaled by %d); %.1f s measured, the head's %.1f s scaled by H"
-                       % (H, dt[0], dt[1], dt[2], dt[3], stride, dt[4], stride, sum(dt), head_s))
+                sample="fp64 numpy oracle on head%s %s of %d, step by step; head 0: threshold pass %.1f s, query clustering "
+                       "%.1f s, Algorithm 1 %.1f s, selection %.1f s (all in full), attention on every %dth query row "
+                       "%.1f s (scaled by %d); %.1f s measured in all, a head's mean %.1f s scaled by H"
+                       % ("s" if len(heads) > 1 else "", ", ".join(map(str, heads)), H, dts[0], dts[1], dts[2], dts[3], stride,
+                          dts[4], stride, measured, head_s))
 
 
 def main():
