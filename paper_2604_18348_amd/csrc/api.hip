@@ -526,7 +526,7 @@ int run_permute(const adacluster_params* p, const WS& w, hipStream_t st, const v
   return 0;
 }
 
-// range lists and query tiles from the selection, then the attention kernel over the permuted rows
+// range lists, row offsets and query tiles from the selection, then the attention kernel
 int run_plan_attention(const adacluster_params* p, const WS& w, hipStream_t st, const void* Q, void* O,
                        const int32_t* k_count, const int32_t* sel_idx, const int32_t* sel_cnt, int prof_from,
                        hipEvent_t permute_done, const void* K = nullptr, const void* V = nullptr) {

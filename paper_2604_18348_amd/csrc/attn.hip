@@ -1,7 +1,9 @@
 // Attention over the selected key clusters (Alg. 3 lines 9-10) and the dense branch.
 //
-// Keys and values are first permuted cluster-contiguous (row gathers, HBM bound).  For every
-// query cluster the selected key clusters then form a short list of row ranges in that order; a
+// The label sort puts the keys in cluster order (a permutation, no copy for bf16: the planning step writes,
+// per query cluster, the byte offset of every selected key row in K and V as they are, and the kernel loads
+// its tiles through that table; fp32 gathers K and V into cluster order first and walks row ranges).  For
+// every query cluster the selected key clusters form a short list of row ranges in that order; a
 // query tile walks the concatenation of its ranges in full 64-key tiles, so cluster raggedness
 // costs nothing but one masked tail tile.  The flash-style kernel keeps the S^T = K Q^T
 // orientation: in the 32x32 MFMA accumulator a lane then owns one query and 16 keys, soft-max
@@ -20,7 +22,7 @@ static constexpr int SPLIT_SLOTS = 128;  // partial slots per head for the chunk
 static constexpr int KROW_PAD = 8 * 64;  // entries of the row-offset table a key list is padded by: the kernel reads up to 7 tiles ahead
 
 // ------------------------------------------------------------------------------------------
-// permutation of K and V rows
+// permutation of K and V rows (fp32 inputs)
 // ------------------------------------------------------------------------------------------
 // dst[h][i][:] = src[h][perm[h][i]][:], 16-byte pieces, one row per group of ROWB/16 lanes; a thread
 // moves its piece of RPT rows of both tensors, all loads issued before the first store.
@@ -71,7 +73,7 @@ int launch_permute_kv(hipStream_t s, int H, int N, int row_bytes, const void* K,
 // ------------------------------------------------------------------------------------------
 // plan: per query cluster the merged key ranges; per head the list of query tiles
 // ------------------------------------------------------------------------------------------
-// rng_start [H][Cq][maxr]   first permuted key row of range r
+// rng_start [H][Cq][maxr]   first key row (in cluster order) of range r
 // rng_pre   [H][Cq][maxr+1] keys before range r in the concatenation (last = total)
 // rng_cnt   [H][Cq]
 // tiles     [H][maxtiles] x {cluster, first sorted query position, rows, first key tile, end key
