@@ -8,6 +8,8 @@
 #include "common.h"
 #include "launch.h"
 
+#include <atomic>
+
 #pragma clang fp contract(off)
 
 namespace adac {
@@ -347,8 +349,17 @@ int launch_select(hipStream_t s, int H, int Cq, int cap, int d, int score_mode, 
   SelectCfg c{Cq, cap, d, lds_cap, score_mode, select_mode, topk, (double)top_p, (double)scale};
   const size_t shm = (size_t)lds_cap * 20;
   if (shm > 150 * 1024) return ADACLUSTER_E_BADSHAPE;
-  hipError_t e = hipFuncSetAttribute((const void*)select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
-  if (e != hipSuccess) return ADACLUSTER_E_INTERNAL;
+  // The kernel's dynamic-LDS limit is raised only when a launch needs more than any launch before it on this
+  // device (a call that repeats an earlier shape then consists of launches only, which is what a caller that
+  // captures it into a HIP graph needs).
+  static std::atomic<int> granted[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return ADACLUSTER_E_INTERNAL;
+  if ((int)shm > granted[dev].load()) {
+    if (hipFuncSetAttribute((const void*)select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm) != hipSuccess)
+      return ADACLUSTER_E_INTERNAL;
+    granted[dev].store((int)shm);
+  }
   select_kernel<<<dim3(Cq, H), 256, shm, s>>>(c, q_cent, q_mean_norm, k_cent, k_bmin, k_bmax, k_sizes, k_count,
                                               full_flag, sel_idx, sel_cnt);
   return hipGetLastError() == hipSuccess ? 0 : ADACLUSTER_E_INTERNAL;

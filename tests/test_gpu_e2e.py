@@ -267,3 +267,46 @@ def test_many_heads():
         ref = orc.sparse_attention_gather(Q[h], K[h], V[h], ql[h], kl[h], sel_gpu[h])
         rel, mx = attn_errors(O[h], ref)
         assert rel < 1e-2 and mx < 2e-2, (h, rel, mx)
+
+
+def test_warm_start_call_replays_from_a_hip_graph():
+    """The warm-start call (Sec. 3.2.2) has no host read-back and allocates nothing: captured into a HIP graph on
+    the caller's stream (its second stream joins the capture through the fork and join events), every replay
+    must give what the same sequence of eager calls gives, bit for bit.  The centres of a call are the start of
+    the next, so replay r is compared with the r-th eager call from the same state; eager work and
+    synchronisations sit between the replays."""
+    import dataclasses
+    H, N, d = 2, 3000, 64
+    Q, K, V = wl.make_small(5, N, d, 12, dtype="bf16", H=H)
+    Qd, Kd, Vd = to_dev(Q, B.BF16), to_dev(K, B.BF16), to_dev(V, B.BF16)
+    p = B.Params(H=H, N=N, d=d, dtype=B.BF16, q_clusters=9, q_iters=3, k_iters=3, k_m0=20, k_m_min=4,
+                 k_max_clusters=80, min_unassigned_frac=0.03, topk=5)
+    ws = B.workspace(p)
+    outs = B.alloc_outputs(p, "cuda")
+    O = torch.empty_like(Qd)
+    B.adacluster_attn(p, Qd, Kd, Vd, outs=outs, out=O, ws=ws)                  # the cold call of step 0
+    torch.cuda.synchronize()
+    pw = dataclasses.replace(p, q_init_mode=1, k_init_mode=1, q_iters=2, k_iters=2)
+    state0 = {k: v.clone() for k, v in outs.items() if v is not None}
+
+    def restore():
+        for k, v in state0.items():
+            outs[k].copy_(v)
+
+    eager = []
+    for _ in range(3):
+        B.adacluster_attn(pw, Qd, Kd, Vd, outs=outs, out=O, ws=ws)
+        torch.cuda.synchronize()
+        eager.append(O.clone())
+    restore()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.adacluster_attn(pw, Qd, Kd, Vd, outs=outs, out=O, ws=ws)
+    restore()
+    torch.cuda.synchronize()
+    for r in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        assert float(torch.rand(4096, device="cuda").sum()) > 0                 # eager work between the replays
+        assert torch.equal(O, eager[r]), r
