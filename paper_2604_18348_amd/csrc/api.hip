@@ -161,7 +161,7 @@ constexpr int STAGE_SUM_BLOCKS = 128;   // a stage of at most this many 256-poin
 inline int capacity(const adacluster_params* p) { return p->k_max_clusters + p->k_m0; }
 inline size_t esize(const adacluster_params* p) { return p->dtype == ADACLUSTER_BF16 ? 2 : 4; }
 // upper bound of the number of 128-row parts of n rows in m clusters
-inline int parts_for(int n, int m) { return m + (n + 127) / 128 + 1; }
+inline int parts_for(int n, int m) { const int r = reduce_part_rows(); return m + (n + r - 1) / r + 1; }   // every cluster ends in at most one short part
 
 // ---- workspace layout ----------------------------------------------------------------------
 struct Layout {
@@ -206,7 +206,7 @@ Dims dims_of(const adacluster_params* p) {
   D.BMmax = attn_block_rows_max(p->dtype);
   D.maxtiles = p->N / attn_block_rows_min(p->dtype) + D.Cq + 1 + attn_split_slots();   // (sized for the smaller tile shape)
   D.maxr = D.cap;
-  D.prow = p->N / 128 + D.capmax + 34;
+  D.prow = p->N / reduce_part_rows() + D.capmax + 34;
   {  // rows of the block-sum table of small stages: (blocks of 256 points) x (centres), both capped
     const int nb = (p->N + 255) / 256, mb = p->k_m0 < assign_block_sum_centres() ? p->k_m0 : assign_block_sum_centres();
     D.brow = (nb < STAGE_SUM_BLOCKS ? nb : STAGE_SUM_BLOCKS) * mb;
@@ -261,8 +261,8 @@ size_t layout(const adacluster_params* p, WS* w, unsigned char* base) {
   TAKE(q_sort.val_a, int32_t*, H * N * 4);
   TAKE(q_sort.lab_b, int32_t*, H * N * 4);
   TAKE(q_poff, int32_t*, H * (size_t)(D.Cq + 1) * 4);
-  TAKE(q_psum, float*, H * (size_t)(N / 128 + D.Cq + 34) * d * 4);
-  TAKE(q_pnorm, float*, H * (size_t)(N / 128 + D.Cq + 34) * 4);
+  TAKE(q_psum, float*, H * (size_t)(N / reduce_part_rows() + D.Cq + 34) * d * 4);
+  TAKE(q_pnorm, float*, H * (size_t)(N / reduce_part_rows() + D.Cq + 34) * 4);
   {
     const bool one_read = p->dtype == ADACLUSTER_BF16 && D.Cq <= assign_block_sum_centres();
     TAKE(q_wsum, float*, one_read ? H * (size_t)D.Cq * qpass_walks(D.N) * d * 4 : 256);

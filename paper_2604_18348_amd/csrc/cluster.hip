@@ -635,7 +635,7 @@ __device__ __forceinline__ bool reduce_setup(const ReduceCfg& c, int h, int& m) 
 // wave takes RPI = 64/LPR rows per step (two steps in flight), and the RPI row slots are merged
 // at the end in a fixed order, so the result does not depend on scheduling.
 // psum [H][m_bound][P][D]; pnorm [H][m_bound][P]; pmin/pmax like psum.
-static constexpr int REDUCE_ROWS = 128;   // rows summed by one wave
+static constexpr int REDUCE_ROWS = 128;   // rows summed by one wave (64, 96 and 192 measured the same)
 
 // poff[j] = number of parts of the clusters before j (a cluster of n rows has ceil(n/REDUCE_ROWS)
 // parts), j = 0..m.  One block per head.
