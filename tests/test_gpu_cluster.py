@@ -442,9 +442,17 @@ def test_kcluster_warm_start_chained(dtype, d):
         assert np.array_equal(warm["k_sizes"].cpu().numpy()[h, :kc[h]], sref)
         assert np.allclose(to_np(warm["k_centroids"])[h, :kc[h]], cref, atol=2e-5, rtol=1e-5)
         assert np.array_equal(to_np(warm["k_box_min"])[h, :kc[h]], mnref)
-        ref = orc.warm_key_clustering(Kh, to_np(cold["k_centroids"])[h, :kc[h]], 2, round_fn=rf)
-        agree = float((ref["labels"] == lab).mean())
-        close = float(np.isclose(ref["assign_centroids"], C, atol=2e-2 if dtype == B.BF16 else 1e-4).mean())
+        start = to_np(cold["k_centroids"])[h, :kc[h]].astype(np.float64)
+        ref = orc.warm_key_clustering(Kh, start, 2, round_fn=rf)
+        # Two start centres that coincide up to rounding split their tokens by rounding alone, on either side:
+        # such centres and their tokens are not compared.  (Algorithm 1 produces them: a cluster whose members all
+        # stay outside tau comes back with the same members, hence the same mean, in the next stage; the cold
+        # call's final pass then leaves one of the two empty, at the other's position up to the last bit.)
+        gap = np.sqrt(((start[:, None, :] - start[None]) ** 2).sum(-1)) + np.eye(kc[h]) * 1e30
+        twin = gap.min(1) < 1e-4
+        keep = ~twin[ref["labels"]] & ~twin[lab]
+        agree = float((ref["labels"] == lab)[keep].mean())
+        close = float(np.isclose(ref["assign_centroids"], C, atol=2e-2 if dtype == B.BF16 else 1e-4)[~twin].mean())
         print("warm", dt_name(dtype), d, "head", h, "label agreement", agree, "centres close", close)
         # free-running comparison: bf16 centre rounding can flip near-tied tokens between
         # neighbouring centres, so only broad agreement is required here (the chained checks above are exact)
