@@ -378,7 +378,10 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
     for (int it = 0; it < p->k_iters; ++it) {
       RET_IF(launch_assign(st, p->dtype, D.d, D.H, D.N, D.N, 1, 0, D.cap, w.kstate, nullptr, K, w.cent_lp, w.bias,
                            k_labels, nullptr));
-      if (it < p->k_iters - 1) {
+      if (it < p->k_iters - 1 && direct_update_fits(p->dtype, D.N, D.cap)) {
+        RET_IF(launch_update_direct(st, D.d, D.H, D.N, D.cap, D.cap, D.cap, w.kstate, k_labels, nullptr, K, k_centroids,
+                                    w.cent_lp, k_assign, w.bias));
+      } else if (it < p->k_iters - 1) {
         RET_IF(launch_sort(st, D.H, D.N, D.N, D.cap, k_labels, nullptr, nullptr, 0, &w.kstate->m_t, sizeof(KState) / 4,
                            nullptr, 0, w.perm_tmp, w.offs_tmp, D.capmax + 1, w.sort, w.poff, reduce_part_rows(), &poff_done));
         RET_IF(launch_seg_reduce(st, p->dtype, D.d, D.H, D.N, 1, 0, D.cap, Pw, w.kstate, 0, 0, K, w.perm_tmp,
@@ -470,7 +473,11 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
       const bool keep = seeded && t == 0 && !update;
       RET_IF(launch_assign(st, p->dtype, D.d, D.H, D.N, n_bound, 1, 0, D.cap, w.kstate, ul, K, w.cent_lp, w.bias,
                            w.labels_tmp, w.dist2, nullptr, nullptr, 0, keep ? w.lab0 : nullptr, keep ? w.score0 : nullptr));
-      if (update) {
+      if (update && direct_update_fits(p->dtype, n_bound, m_bound)) {
+        // few points (fp32): every centre gathers its members from the label list itself, one launch
+        RET_IF(launch_update_direct(st, D.d, D.H, D.N, m_bound, D.cap, p->k_m0, w.kstate, w.labels_tmp, ul, K, w.master,
+                                    w.cent_lp, k_assign, w.bias));
+      } else if (update) {
         RET_IF(launch_sort(st, D.H, D.N, n_bound, m_bound, w.labels_tmp, ul, &w.kstate->ucount,
                            sizeof(KState) / 4, &w.kstate->m_t, sizeof(KState) / 4, &w.kstate->active,
                            sizeof(KState) / 4, w.perm_tmp, w.offs_tmp, D.capmax + 1, w.sort, w.poff, reduce_part_rows(), &poff_done));

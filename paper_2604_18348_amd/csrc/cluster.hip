@@ -965,6 +965,109 @@ __global__ __launch_bounds__(64) void finalize_centroids(FinalizeCfg cfg, const 
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Centroid update of a stage with few points in ONE launch (fp32 inputs): the workgroup of a centre finds
+// its members in the label list itself (an ordered compaction, so the member order is the list order),
+// sums their rows in a fixed order and writes the new centre, its copies for the assignment kernel and
+// the arg-max bias.  It stands for the label sort, the segmented reduction and the combining kernel,
+// three launches that are each bound by latency at a few thousand points.
+// ------------------------------------------------------------------------------------------
+constexpr int DIRECT_ROUND = 4096;          // list positions scanned per round: 1024 per wave, 16 per lane
+#ifndef ADAC_DIRECT_MAX_VISITS
+#define ADAC_DIRECT_MAX_VISITS (1 << 21)
+#endif
+constexpr long long DIRECT_MAX_VISITS = ADAC_DIRECT_MAX_VISITS;   // centres x points up to which every centre scans the whole list
+
+template <int D>
+__global__ __launch_bounds__(256) void update_direct_f32(const float* __restrict__ X, int N, int cap, int master_stride,
+                                                         const KState* __restrict__ st,
+                                                         const int32_t* __restrict__ labels,
+                                                         const int32_t* __restrict__ ulist,
+                                                         float* __restrict__ master, float* __restrict__ assign_lp,
+                                                         float* __restrict__ assign_f32, float* __restrict__ bias) {
+  constexpr int LPR = D / 4, G = 256 / LPR;   // lanes per row (16 bytes each), rows in flight per step
+  const int h = blockIdx.y, j = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const KState& s = st[h];
+  if (!s.active) return;
+  const int n = s.ucount, m = s.m_t, row_off = s.ccount;
+  if (j >= m) return;
+  __shared__ int32_t list[DIRECT_ROUND];
+  __shared__ int32_t wcnt[4];
+  __shared__ float4 red[256];
+  const int32_t* lab = labels + (size_t)h * N;
+  const int32_t* ul = ulist ? ulist + (size_t)h * N : nullptr;
+  const float* Xh = X + (size_t)h * N * D;
+  const int g = tid / LPR, cl = tid % LPR;
+  const uint64_t below = (1ull << lane) - 1ull;
+  float4 acc = {0.f, 0.f, 0.f, 0.f};
+  int total = 0;
+  for (int r0 = 0; r0 < n; r0 += DIRECT_ROUND) {
+    // wave w scans positions r0 + 1024 w ... in 16 steps of 64; members keep their list order
+    int tok[16];
+    uint32_t hit = 0;
+    int mine = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int pos = r0 + wave * 1024 + i * 64 + lane;
+      const bool in = pos < n;
+      const int l = in ? lab[pos] : -1;
+      tok[i] = in ? (ul ? ul[pos] : pos) : 0;
+      if (l == j) hit |= 1u << i;
+    }
+    int woff[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const uint64_t b = __ballot((hit >> i) & 1u);
+      woff[i] = mine + __popcll(b & below);
+      mine += __popcll(b);
+    }
+    __syncthreads();                 // the list of the round before has been summed
+    if (lane == 0) wcnt[wave] = mine;
+    __syncthreads();
+    int base = 0, cnt = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) { const int c = wcnt[w]; if (w < wave) base += c; cnt += c; }
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      if ((hit >> i) & 1u) list[base + woff[i]] = tok[i];
+    __syncthreads();
+    // row i of the round goes to row group i % G; a group adds its rows in ascending order
+    for (int i0 = g; i0 < cnt; i0 += 4 * G) {
+      float4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int i = i0 + u * G;
+        v[u] = float4{0.f, 0.f, 0.f, 0.f};
+        if (i < cnt) v[u] = *reinterpret_cast<const float4*>(Xh + (size_t)list[i] * D + cl * 4);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
+    }
+    total += cnt;
+  }
+  if (total == 0) return;            // an empty cluster keeps its centre
+  red[tid] = acc;
+  __syncthreads();
+  if (tid >= LPR) return;
+  float4 sum = red[cl];
+#pragma unroll
+  for (int q = 1; q < G; ++q) {
+    const float4 t = red[q * LPR + cl];
+    sum.x += t.x; sum.y += t.y; sum.z += t.z; sum.w += t.w;
+  }
+  const float cntf = (float)total;
+  const float4 val = {sum.x / cntf, sum.y / cntf, sum.z / cntf, sum.w / cntf};
+  *reinterpret_cast<float4*>(master + ((size_t)h * master_stride + j) * D + cl * 4) = val;
+  const size_t ao = ((size_t)h * cap + row_off + j) * D + cl * 4;
+  *reinterpret_cast<float4*>(assign_lp + ao) = val;
+  *reinterpret_cast<float4*>(assign_f32 + ao) = val;
+  float bsum = fmaf(val.x, val.x, 0.f);
+  bsum = fmaf(val.y, val.y, bsum); bsum = fmaf(val.z, val.z, bsum); bsum = fmaf(val.w, val.w, bsum);
+#pragma unroll
+  for (int o = 1; o < LPR; o <<= 1) bsum += __shfl_xor(bsum, o);
+  if (cl == 0) bias[(size_t)h * cap + row_off + j] = -0.5f * bsum;
+}
+
 // Initial centres: strided sample of the current point list (or the rows of `master` as given).
 //   source_master = 1: master already holds the centres (warm start)
 template <typename T, int D>
@@ -1778,6 +1881,18 @@ int launch_finalize(hipStream_t s, int dtype, int d, int H, int mode, int m_cons
     finalize_centroids<128><<<g, 64, 0, s>>>(c, offs, offs_stride, poff, psum, pnorm, pmin, pmax, master, assign_lp,
                                              assign_f32, bias, out_cent, fallback, out_sizes, out_mean_norm,
                                              out_bmin, out_bmax);
+  return chk();
+}
+
+bool direct_update_fits(int dtype, int n_bound, int m_bound) {
+  return dtype == ADACLUSTER_F32 && (long long)n_bound * m_bound <= DIRECT_MAX_VISITS;
+}
+int launch_update_direct(hipStream_t s, int d, int H, int N, int m_bound, int cap, int master_stride, const KState* st,
+                         const int32_t* labels, const int32_t* ulist, const void* X, float* master, void* assign_lp,
+                         float* assign_f32, float* bias) {
+  dim3 g(m_bound, H);
+  if (d == 64) update_direct_f32<64><<<g, 256, 0, s>>>((const float*)X, N, cap, master_stride, st, labels, ulist, master, (float*)assign_lp, assign_f32, bias);
+  else update_direct_f32<128><<<g, 256, 0, s>>>((const float*)X, N, cap, master_stride, st, labels, ulist, master, (float*)assign_lp, assign_f32, bias);
   return chk();
 }
 

@@ -40,6 +40,13 @@ int launch_finalize(hipStream_t s, int dtype, int d, int H, int mode, int m_cons
                     float* bias, float* out_cent, const float* fallback, int32_t* out_sizes,
                     float* out_mean_norm, float* out_bmin, float* out_bmax, const int32_t* blk_cnt = nullptr,
                     int nb_stride = 0, int nb_const = 0);
+// Centroid update of a running stage (state mode 1) in one launch, fp32 inputs: every centre's workgroup scans the
+// stage's label list (`ulist` NULL: positions are tokens), so it is for few points and centres only:
+// direct_update_fits() says when.  Writes what launch_finalize(update_assign = 1) writes.
+bool direct_update_fits(int dtype, int n_bound, int m_bound);
+int launch_update_direct(hipStream_t s, int d, int H, int N, int m_bound, int cap, int master_stride, const KState* st,
+                         const int32_t* labels, const int32_t* ulist, const void* X, float* master, void* assign_lp,
+                         float* assign_f32, float* bias);
 // One pass of a k-means with at most assign_block_sum_centres() centres in one read of the points (bf16):
 // assignment and (weighted) centroid sums together.  psum [H][m * NP][d], pcnt [H][NP][assign_block_sum_centres()]
 // with NP = qpass_walks(N); launch_finalize(..., blk_cnt = pcnt, nb_stride = NP, nb_const = NP) turns them into centres.

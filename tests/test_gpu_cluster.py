@@ -227,6 +227,22 @@ def test_kcluster_chained(dtype, d, N, M):
     assert math.isclose(tau, tau_ref, rel_tol=2e-3)
 
 
+def test_kcluster_fp32_sorted_and_direct_updates():
+    """fp32 inputs update the centres of a stage either from the sorted labels (segmented reduction) or, when
+    centres x points is small, by one workgroup per centre that gathers its members itself.  Stage 0 here
+    (240 centres, 9000 points) is above the switch, the later stages are below it."""
+    H, N, d = 2, 9000, 64
+    _, K, _ = wl.make_small(29, N, d, 40, dtype="f32", H=H)
+    K[1] = np.random.default_rng(9).standard_normal((N, d)).astype(np.float32)      # a diffuse head: more stages
+    p = B.Params(H=H, N=N, d=d, dtype=B.F32, q_clusters=8, k_iters=3, k_m0=240, k_m_min=8, k_max_clusters=720,
+                 tau_factor=1.2, min_unassigned_frac=0.02)
+    out = B.adacluster_kcluster(p, to_dev(K, B.F32))
+    torch.cuda.synchronize()
+    check_kcluster(K, p, out, B.F32)
+    so = out["k_stage_offs"].cpu().numpy()
+    assert (np.diff(so[1]) > 0).sum() >= 2, so          # the diffuse head ran at least two stages
+
+
 def test_kcluster_more_than_128_stage_centres():
     """Stage centre counts above 128 need two radix passes of the label sort, here inside the
     one-workgroup-per-head kernels (small heads)."""
