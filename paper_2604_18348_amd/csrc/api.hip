@@ -181,6 +181,7 @@ struct WS {
   void* q_cent_lp; float* q_bias; SortScratch q_sort; int32_t* q_poff; float* q_psum; float* q_pnorm;
   float* q_wsum; int32_t* q_wcnt;     // walk sums and counts of the one-read passes of the query clustering
   void* Kp; void* Vp;
+  double* scores;       // [H][Cq][cap] centroid scores between the kernels of the selection step
   int32_t* rng_start; int32_t* rng_pre; int32_t* rng_cnt; int32_t* tiles; int32_t* ntiles;
   int32_t* merge; int32_t* nmerge; float* part_o; float* part_ml;   // cut key lists of the attention step
   int32_t* krow;        // [H][Cq][kstride] byte offset of every key row of a query cluster's list
@@ -274,6 +275,7 @@ size_t layout(const adacluster_params* p, WS* w, unsigned char* base) {
   TAKE(offs_k, int32_t*, H * (size_t)(D.cap + 1) * 4);
   TAKE(Kp, void*, rows_in_place(p) ? 256 : H * N * d * es);      // permuted copies: fp32 only
   TAKE(Vp, void*, rows_in_place(p) ? 256 : H * N * d * es);
+  TAKE(scores, double*, H * (size_t)D.Cq * D.cap * 8);
   TAKE(rng_start, int32_t*, H * (size_t)D.Cq * D.maxr * 4);
   TAKE(rng_pre, int32_t*, H * (size_t)D.Cq * (D.maxr + 1) * 4);
   TAKE(rng_cnt, int32_t*, H * (size_t)D.Cq * 4);
@@ -675,7 +677,7 @@ int adacluster_select(const adacluster_params* p, const float* q_centroids, cons
   const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->d);
   RET_IF(launch_select((hipStream_t)stream, p->H, p->q_clusters, capacity(p), p->d, p->score_mode, p->select_mode,
                        p->topk, p->top_p, scale, q_centroids, q_mean_norm, k_centroids, k_box_min, k_box_max, k_sizes,
-                       k_count, full_flag, sel_idx, sel_cnt, capacity(p)));
+                       k_count, full_flag, sel_idx, sel_cnt, capacity(p), w.scores));
   return 0;
 }
 
@@ -769,7 +771,7 @@ int adacluster_attn(const adacluster_params* p, const void* Q, const void* K, co
   const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->d);
   rc = launch_select(st, p->H, p->q_clusters, capacity(p), p->d, p->score_mode, p->select_mode, p->topk, p->top_p,
                      scale, q_centroids, q_mean_norm, k_centroids, k_bmin, k_bmax, k_sizes, k_count, full_flag,
-                     sel_idx, sel_cnt, kc_bound);
+                     sel_idx, sel_cnt, kc_bound, w.scores);
   if (rc) return drained(rc == ADACLUSTER_E_INTERNAL ? fail(rc, "HIP launch failed: %s", hipGetErrorString(hipGetLastError())) : rc);
   prof_mark(EV_SELECT, st, EV_JOIN);
   // both label sorts were left in the workspace by the clustering steps; the attention step joins the

@@ -973,10 +973,7 @@ __global__ __launch_bounds__(64) void finalize_centroids(FinalizeCfg cfg, const 
 // three launches that are each bound by latency at a few thousand points.
 // ------------------------------------------------------------------------------------------
 constexpr int DIRECT_ROUND = 4096;          // list positions scanned per round: 1024 per wave, 16 per lane
-#ifndef ADAC_DIRECT_MAX_VISITS
-#define ADAC_DIRECT_MAX_VISITS (1 << 21)
-#endif
-constexpr long long DIRECT_MAX_VISITS = ADAC_DIRECT_MAX_VISITS;   // centres x points up to which every centre scans the whole list
+constexpr long long DIRECT_MAX_VISITS = 1 << 21;   // centres x points up to which every centre scans the whole list
 
 template <int D>
 __global__ __launch_bounds__(256) void update_direct_f32(const float* __restrict__ X, int N, int cap, int master_stride,

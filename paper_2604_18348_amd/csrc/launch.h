@@ -84,7 +84,7 @@ int launch_kstate_export(hipStream_t s, const KState* st, int H, int32_t* k_coun
 int launch_select(hipStream_t s, int H, int Cq, int cap, int d, int score_mode, int select_mode, int topk,
                   float top_p, float scale, const float* q_cent, const float* q_mean_norm, const float* k_cent,
                   const float* k_bmin, const float* k_bmax, const int32_t* k_sizes, const int32_t* k_count,
-                  const int32_t* full_flag, int32_t* sel_idx, int32_t* sel_cnt, int kc_max);
+                  const int32_t* full_flag, int32_t* sel_idx, int32_t* sel_cnt, int kc_max, double* scores);   // scores: scratch [H][Cq][cap]
 
 int attn_block_rows(int dtype, int d, int N, int Cq);   // queries per workgroup of the attention launch
 int attn_block_rows_min(int dtype);

@@ -1,10 +1,11 @@
 // Critical-cluster selection: centroid scores (Eq. 1 / Eq. 2, Algorithm 2), arg-top-k (Alg. 3
 // line 8) and the top-p budget.
 //
-// The score matrix is tiny (Cq x Ck x d per head), so it is evaluated in fp64 with one rounded
-// multiply and one rounded add per term, summed in ascending dimension order.  That makes every
-// bit of a score, and therefore every selected index set, reproducible by a CPU implementation.
-// Floating-point contraction is switched off for this file for the same reason.
+// The score matrix is tiny (Cq x Ck x d per head), so it is evaluated in fp64, term by term in ascending
+// dimension order, with the bits a rounded multiply followed by a rounded add would give (score_kernel says
+// why its fused multiply-adds do).  That makes every bit of a score, and therefore every selected index set,
+// reproducible by a CPU implementation.  Floating-point contraction by the compiler is switched off for this
+// file for the same reason.
 #include "common.h"
 #include "launch.h"
 
@@ -44,12 +45,140 @@ __device__ __forceinline__ uint64_t order_key(double v) {
   return (u >> 63) ? ~u : (u | 0x8000000000000000ull);
 }
 
+// Scores of every (query cluster, key cluster) pair: S[h][i][j], -inf for an empty key cluster, 0 for a head
+// that attends to everything.  A thread owns SCORE_ROWS key clusters and reads their rows (16 bytes at a time,
+// one step ahead) ONCE for SCORE_QG query clusters, whose centroids wait in LDS split by sign:
+//   (q, 0) where q's sign bit is clear, (0, q) where it is set.
+// Every score is the pair of chains  sp += q+ * k+,  sn += q- * k-  in ascending dimension order with
+// k+/k- = max(c,0)/min(c,0) (Algorithm 2), box max/min (Eq. 1), or c itself with q- = 0 (plain dot product).
+// The term of the sign q does not have is an exact zero, which leaves its chain as it was, so each chain sees
+// exactly the terms it owns.  q and k are float values, so a product is exact in double (48 significant bits
+// at most, exponents far inside the range) and the fused multiply-add rounds once, exactly where the add of a
+// separately rounded product would: the same bits as multiply-then-add at twice the rate.
+// (One workgroup per query cluster reading every key row itself, as the selection kernel did before, was bound
+// by L2 traffic: 65 reads of a head's centroid table.)
+// Measured at 1171 / 500 key clusters per head (24 / 30 heads, d = 128 / 64), (QG, rows): (13,1) 61 / 30 us,
+// (7,1) 76 / 29, (13,2) 66 / 36, (9,2) 84 / 30, (7,2) 83 / 41, (5,2) 89 / 44; with one row the LDS pipe is the
+// limit (a 16-byte broadcast read per two fused multiply-adds), with more rows the registers and the smaller
+// number of waves are.  The query values as scalar operands (scalar loads from a table prepared by another
+// kernel, no LDS) took 165 / 75 us: the scalar cache delivers far less than the LDS.
+constexpr int SCORE_QG = 13;       // query clusters per thread (65 = 5 groups)
+constexpr int SCORE_ROWS = 1;      // key clusters per thread
+constexpr int SCORE_THREADS = 128;
+
+__global__ __launch_bounds__(SCORE_THREADS) void score_kernel(SelectCfg cfg, const float* __restrict__ q_cent,
+                                                              const float* __restrict__ k_cent,
+                                                              const float* __restrict__ k_bmin,
+                                                              const float* __restrict__ k_bmax,
+                                                              const int32_t* __restrict__ k_sizes,
+                                                              const int32_t* __restrict__ k_count,
+                                                              const int32_t* __restrict__ full_flag,
+                                                              double* __restrict__ S) {
+  constexpr int QG = SCORE_QG, R = SCORE_ROWS;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  double2* qs = reinterpret_cast<double2*>(smem);            // [QG][d]
+  const int h = blockIdx.z, i0 = blockIdx.y * QG, tid = threadIdx.x;
+  const int d = cfg.d;
+  const int kc = min(k_count[h], cfg.lds_cap);
+  if ((int)blockIdx.x * (R * SCORE_THREADS) >= kc) return;
+  const bool dot = cfg.score_mode == ADACLUSTER_SCORE_DOT, box = cfg.score_mode == ADACLUSTER_SCORE_BOX;
+  for (int e = tid; e < QG * d; e += SCORE_THREADS) {
+    const int g = e / d, t = e - g * d;
+    const int i = min(i0 + g, cfg.Cq - 1);        // (the last group repeats the last cluster; not stored)
+    const float q = q_cent[((size_t)h * cfg.Cq + i) * d + t];
+    const bool neg = (__float_as_uint(q) >> 31) != 0u;
+    double2 v;
+    v.x = (dot || !neg) ? (double)q : 0.0;
+    v.y = (!dot && neg) ? (double)q : 0.0;
+    qs[e] = v;
+  }
+  __syncthreads();
+  // Row r of this thread is key cluster jb + r * SCORE_THREADS.  A row that needs no arithmetic (past the
+  // count, empty, or in a head that attends to everything) runs on row jb's data all the same and stores its
+  // fixed value instead.
+  const int jb = blockIdx.x * (R * SCORE_THREADS) + tid;
+  if (jb >= kc) return;
+  const bool all = full_flag[h] != 0;
+  bool live[R], any_live = false; double fixed[R];
+  const float4* rpos[R]; const float4* rneg[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int j = jb + r * SCORE_THREADS;
+    const int nj = j < kc ? k_sizes[(size_t)h * cfg.cap + j] : 0;
+    live[r] = j < kc && nj > 0 && !all;
+    any_live = any_live || live[r];
+    fixed[r] = nj == 0 ? -INFINITY : 0.0;
+    const int jl = live[r] ? j : jb;
+    rpos[r] = reinterpret_cast<const float4*>((box ? k_bmax : k_cent) + ((size_t)h * cfg.cap + jl) * d);
+    rneg[r] = reinterpret_cast<const float4*>((box ? k_bmin : k_cent) + ((size_t)h * cfg.cap + jl) * d);
+  }
+  double sp[R][QG], sn[R][QG];
+#pragma unroll
+  for (int r = 0; r < R; ++r)
+#pragma unroll
+    for (int g = 0; g < QG; ++g) { sp[r][g] = 0.0; sn[r][g] = 0.0; }
+  if (any_live) {
+    constexpr int B4 = 4 / R > 0 ? 4 / R : 1;      // 16-byte pieces of a row per step
+    float4 pb[R][B4], nb[R][B4];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+      for (int u4 = 0; u4 < B4; ++u4) { pb[r][u4] = rpos[r][u4]; nb[r][u4] = box ? rneg[r][u4] : pb[r][u4]; }
+    for (int st = 0; st < d / (4 * B4); ++st) {
+      float4 pc[R][B4], nc[R][B4];
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int u4 = 0; u4 < B4; ++u4) { pc[r][u4] = pb[r][u4]; nc[r][u4] = nb[r][u4]; }
+      if (st + 1 < d / (4 * B4)) {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+          for (int u4 = 0; u4 < B4; ++u4) {
+            pb[r][u4] = rpos[r][(st + 1) * B4 + u4];
+            nb[r][u4] = box ? rneg[r][(st + 1) * B4 + u4] : pb[r][u4];
+          }
+      }
+#pragma unroll
+      for (int u4 = 0; u4 < B4; ++u4) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int t = (st * B4 + u4) * 4 + u;
+          double kp[R], kn[R];
+#pragma unroll
+          for (int r = 0; r < R; ++r) {
+            const float pv = u == 0 ? pc[r][u4].x : u == 1 ? pc[r][u4].y : u == 2 ? pc[r][u4].z : pc[r][u4].w;
+            const float nv = u == 0 ? nc[r][u4].x : u == 1 ? nc[r][u4].y : u == 2 ? nc[r][u4].z : nc[r][u4].w;
+            kp[r] = (double)((box || dot) ? pv : fmaxf(pv, 0.f));
+            kn[r] = (double)((box || dot) ? nv : fminf(nv, 0.f));
+          }
+#pragma unroll
+          for (int g = 0; g < QG; ++g) {
+            const double2 q2 = qs[g * d + t];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+              sp[r][g] = __fma_rn(q2.x, kp[r], sp[r][g]);
+              sn[r][g] = __fma_rn(q2.y, kn[r], sn[r][g]);
+            }
+          }
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int j = jb + r * SCORE_THREADS;
+    if (j >= kc) continue;
+    double* out = S + ((size_t)h * cfg.Cq + i0) * cfg.cap + j;
+#pragma unroll
+    for (int g = 0; g < QG; ++g)
+      if (i0 + g < cfg.Cq) out[(size_t)g * cfg.cap] = live[r] ? sp[r][g] + sn[r][g] : fixed[r];
+  }
+}
+
 // One block per (query cluster, head).  Dynamic LDS: key[cap] (uint64) + flag[cap] (int).
-__global__ __launch_bounds__(256) void select_kernel(SelectCfg cfg, const float* __restrict__ q_cent,
+__global__ __launch_bounds__(256) void select_kernel(SelectCfg cfg, const double* __restrict__ S,
                                                      const float* __restrict__ q_mean_norm,
-                                                     const float* __restrict__ k_cent,
-                                                     const float* __restrict__ k_bmin,
-                                                     const float* __restrict__ k_bmax,
                                                      const int32_t* __restrict__ k_sizes,
                                                      const int32_t* __restrict__ k_count,
                                                      const int32_t* __restrict__ full_flag,
@@ -59,8 +188,6 @@ __global__ __launch_bounds__(256) void select_kernel(SelectCfg cfg, const float*
   double* sval = reinterpret_cast<double*>(smem);                        // [cap] score, then weight
   uint64_t* skey = reinterpret_cast<uint64_t*>(smem + (size_t)cfg.lds_cap * 8);   // [lds_cap]
   int32_t* sflag = reinterpret_cast<int32_t*>(smem + (size_t)cfg.lds_cap * 16);   // [lds_cap]
-  __shared__ double qrow[128];
-  __shared__ uint64_t qneg_mask[2];
   __shared__ int32_t wsum[4], wsum2[4];
   __shared__ int32_t s_take, s_digit, s_krem, s_all;
   __shared__ int32_t hist[256];
@@ -69,88 +196,15 @@ __global__ __launch_bounds__(256) void select_kernel(SelectCfg cfg, const float*
 
   const int h = blockIdx.y, i = blockIdx.x, tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int d = cfg.d;
   bool use_thr = false;          // top-k by threshold key: selected = key > thr_key, or == thr_key among the first thr_rem
   uint64_t thr_key = 0;
   int thr_rem = 0;
   const int kc = min(k_count[h], cfg.lds_cap);
   const bool all = full_flag[h] != 0;
+  // ---- scores of this query cluster (score_kernel)
   {
-    const double q = tid < d ? (double)q_cent[((size_t)h * cfg.Cq + i) * d + tid] : 0.0;
-    if (tid < d) qrow[tid] = q;
-    const uint64_t neg = __ballot(__double2hiint(q) < 0);        // sign bits of 64 dimensions
-    if (lane == 0 && wave < 2) qneg_mask[wave] = neg;
-  }
-  __syncthreads();
-  // wave-uniform sign masks of the query centroid, kept in scalar registers
-  const uint64_t nm0 = qneg_mask[0], nm1 = qneg_mask[1];
-  auto uniform64 = [](uint64_t v) {
-    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
-    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
-    return ((uint64_t)hi << 32) | (uint64_t)lo;
-  };
-  const uint64_t neg0 = uniform64(nm0), neg1 = uniform64(nm1);
-
-  // ---- scores (a thread owns a key cluster; its row is read 16 bytes at a time)
-  for (int j = tid; j < kc; j += 256) {
-    const int nj = k_sizes[(size_t)h * cfg.cap + j];
-    double s;
-    if (nj == 0) {
-      s = -INFINITY;
-    } else if (all) {
-      s = 0.0;
-    } else if (cfg.score_mode == ADACLUSTER_SCORE_DOT) {
-      const float4* cr = reinterpret_cast<const float4*>(k_cent + ((size_t)h * cfg.cap + j) * d);
-      s = 0.0;
-      for (int t4 = 0; t4 < d / 4; ++t4) {
-        const float4 c4 = cr[t4];
-        s = s + qrow[4 * t4 + 0] * (double)c4.x;
-        s = s + qrow[4 * t4 + 1] * (double)c4.y;
-        s = s + qrow[4 * t4 + 2] * (double)c4.z;
-        s = s + qrow[4 * t4 + 3] * (double)c4.w;
-      }
-    } else {
-      const bool box = cfg.score_mode == ADACLUSTER_SCORE_BOX;
-      const float4* rpos = reinterpret_cast<const float4*>((box ? k_bmax : k_cent) + ((size_t)h * cfg.cap + j) * d);
-      const float4* rneg = reinterpret_cast<const float4*>((box ? k_bmin : k_cent) + ((size_t)h * cfg.cap + j) * d);
-      double sp = 0.0, sn = 0.0;
-      // 64 dimensions per step: the sixteen 16-byte loads of a step are in flight together (the rows come
-      // from L2 or further away, and the wait for them is most of this loop), the chain of adds runs on
-      // registers (d is 64 or 128)
-      for (int t64 = 0; t64 < d / 64; ++t64) {
-        float4 pb[16], nb[16];
-#pragma unroll
-        for (int u4 = 0; u4 < 16; ++u4) pb[u4] = rpos[t64 * 16 + u4];
-        if (box) {
-#pragma unroll
-          for (int u4 = 0; u4 < 16; ++u4) nb[u4] = rneg[t64 * 16 + u4];
-        } else {
-#pragma unroll
-          for (int u4 = 0; u4 < 16; ++u4) nb[u4] = pb[u4];
-        }
-#pragma unroll
-        for (int u4 = 0; u4 < 16; ++u4) {
-          const float pv[4] = {pb[u4].x, pb[u4].y, pb[u4].z, pb[u4].w}, nv[4] = {nb[u4].x, nb[u4].y, nb[u4].z, nb[u4].w};
-#pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            // The sign of q is the same for the whole workgroup.  The term of the other sign is an exact
-            // zero, and adding a zero leaves a running sum as it is, so only one of the two is formed.
-            const int t = 64 * t64 + 4 * u4 + u;
-            const double q = qrow[t];
-            const bool qpos_ = !(((t64 == 0 ? neg0 : neg1) >> (t & 63)) & 1ull);
-            if (qpos_) {
-              const float kp = box ? pv[u] : fmaxf(pv[u], 0.f);
-              sp = sp + q * (double)kp;
-            } else {
-              const float kn = box ? nv[u] : fminf(nv[u], 0.f);
-              sn = sn + q * (double)kn;
-            }
-          }
-        }
-      }
-      s = sp + sn;
-    }
-    sval[j] = s;
+    const double* sr = S + ((size_t)h * cfg.Cq + i) * cfg.cap;
+    for (int j = tid; j < kc; j += 256) sval[j] = sr[j];
   }
   __syncthreads();
 
@@ -342,7 +396,7 @@ __global__ __launch_bounds__(256) void select_kernel(SelectCfg cfg, const float*
 int launch_select(hipStream_t s, int H, int Cq, int cap, int d, int score_mode, int select_mode, int topk,
                   float top_p, float scale, const float* q_cent, const float* q_mean_norm, const float* k_cent,
                   const float* k_bmin, const float* k_bmax, const int32_t* k_sizes, const int32_t* k_count,
-                  const int32_t* full_flag, int32_t* sel_idx, int32_t* sel_cnt, int kc_max) {
+                  const int32_t* full_flag, int32_t* sel_idx, int32_t* sel_cnt, int kc_max, double* scores) {
   // kc_max: an upper bound of k_count[h] known to the host; it sizes the LDS arrays (and with
   // them the number of workgroups a CU can hold)
   const int lds_cap = kc_max < cap ? (kc_max + 63) / 64 * 64 : cap;
@@ -360,8 +414,11 @@ int launch_select(hipStream_t s, int H, int Cq, int cap, int d, int score_mode, 
       return ADACLUSTER_E_INTERNAL;
     granted[dev].store((int)shm);
   }
-  select_kernel<<<dim3(Cq, H), 256, shm, s>>>(c, q_cent, q_mean_norm, k_cent, k_bmin, k_bmax, k_sizes, k_count,
-                                              full_flag, sel_idx, sel_cnt);
+  const int kb = kc_max < cap ? kc_max : cap;
+  score_kernel<<<dim3((kb + SCORE_ROWS * SCORE_THREADS - 1) / (SCORE_ROWS * SCORE_THREADS), (Cq + SCORE_QG - 1) / SCORE_QG, H),
+                 SCORE_THREADS, (size_t)SCORE_QG * d * sizeof(double2), s>>>(c, q_cent, k_cent, k_bmin, k_bmax, k_sizes, k_count,
+                                                                            full_flag, scores);
+  select_kernel<<<dim3(Cq, H), 256, shm, s>>>(c, scores, q_mean_norm, k_sizes, k_count, full_flag, sel_idx, sel_cnt);
   return hipGetLastError() == hipSuccess ? 0 : ADACLUSTER_E_INTERNAL;
 }
 
