@@ -973,7 +973,8 @@ __global__ __launch_bounds__(64) void finalize_centroids(FinalizeCfg cfg, const 
 // three launches that are each bound by latency at a few thousand points.
 // ------------------------------------------------------------------------------------------
 constexpr int DIRECT_ROUND = 4096;          // list positions scanned per round: 1024 per wave, 16 per lane
-constexpr long long DIRECT_MAX_VISITS = 1 << 21;   // centres x points up to which every centre scans the whole list
+constexpr long long DIRECT_MAX_VISITS = 1 << 21;
+constexpr int DIRECT_MAX_POINTS = 4 * DIRECT_ROUND;  // a workgroup scans the list alone: at most four rounds   // centres x points up to which every centre scans the whole list
 
 template <int D>
 __global__ __launch_bounds__(256) void update_direct_f32(const float* __restrict__ X, int N, int cap, int master_stride,
@@ -1882,7 +1883,7 @@ int launch_finalize(hipStream_t s, int dtype, int d, int H, int mode, int m_cons
 }
 
 bool direct_update_fits(int dtype, int n_bound, int m_bound) {
-  return dtype == ADACLUSTER_F32 && (long long)n_bound * m_bound <= DIRECT_MAX_VISITS;
+  return dtype == ADACLUSTER_F32 && n_bound <= DIRECT_MAX_POINTS && (long long)n_bound * m_bound <= DIRECT_MAX_VISITS;
 }
 int launch_update_direct(hipStream_t s, int d, int H, int N, int m_bound, int cap, int master_stride, const KState* st,
                          const int32_t* labels, const int32_t* ulist, const void* X, float* master, void* assign_lp,
