@@ -652,16 +652,18 @@ __global__ __launch_bounds__(1024) void part_scan(ReduceCfg cfg, const int32_t* 
   const int j0 = tid * per, j1 = min(m, j0 + per);
   int run = 0;
   for (int j = j0; j < j1; ++j) run += (of[j + 1] - of[j] + REDUCE_ROWS - 1) / REDUCE_ROWS;
-  __shared__ int32_t sc[1024];
-  sc[tid] = run;
+  // inclusive scan over the 1024 threads: inside a wave by shuffles, across the 16 waves through LDS
+  const int lane = tid & 63, wave = tid >> 6;
+  int incl = run;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) { const int v = __shfl_up(incl, o); if (lane >= o) incl += v; }
+  __shared__ int32_t wtot[16];
+  if (lane == 63) wtot[wave] = incl;
   __syncthreads();
-  for (int o = 1; o < 1024; o <<= 1) {
-    const int v = tid >= o ? sc[tid - o] : 0;
-    __syncthreads();
-    sc[tid] += v;
-    __syncthreads();
-  }
-  int base = sc[tid] - run;
+  int before = 0, total = 0;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) { const int v = wtot[w]; if (w < wave) before += v; total += v; }
+  int base = before + incl - run;
   int32_t* pc = (pcl && m > 128) ? pcl + (size_t)h * cfg.P : nullptr;
   for (int j = j0; j < j1; ++j) {
     po[j] = base;
@@ -669,7 +671,7 @@ __global__ __launch_bounds__(1024) void part_scan(ReduceCfg cfg, const int32_t* 
     if (pc) for (int q = 0; q < np && base + q < cfg.P; ++q) pc[base + q] = j;
     base += np;
   }
-  if (tid == 1023) po[m] = sc[1023];
+  if (tid == 1023) po[m] = total;
 }
 
 template <typename T> struct Vec16;
@@ -1255,25 +1257,31 @@ __global__ __launch_bounds__(256) void filter_count(const KState* __restrict__ s
   if (tid == 0) blockcnt[(size_t)h * nblk + b] = ws[0] + ws[1] + ws[2] + ws[3];
 }
 
-__global__ void filter_scan(KState* __restrict__ st, int nblk_used, int nblk, int32_t* __restrict__ blockcnt,
-                            int32_t* __restrict__ u_prev) {
-  const int h = blockIdx.x;
-  if (threadIdx.x != 0) return;
+__global__ __launch_bounds__(64) void filter_scan(KState* __restrict__ st, int nblk_used, int nblk,
+                                                  int32_t* __restrict__ blockcnt, int32_t* __restrict__ u_prev) {
+  // one wave per head: a lane takes a run of consecutive blocks, the runs are chained by a wave scan
+  const int h = blockIdx.x, lane = threadIdx.x;
   KState s = st[h];
   if (!s.active) return;
-  const int nb = (s.ucount + 1023) / 1024;
-  int run = 0;
-  for (int b = 0; b < nb && b < nblk_used; ++b) {
-    const int c = blockcnt[(size_t)h * nblk + b];
-    blockcnt[(size_t)h * nblk + b] = run;
-    run += c;
-  }
+  const int nb = min((s.ucount + 1023) / 1024, nblk_used);
+  const int per = (nb + 63) / 64;
+  const int b0 = min(lane * per, nb), b1 = min(b0 + per, nb);
+  int32_t* bc = blockcnt + (size_t)h * nblk;
+  int mine = 0;
+  for (int b = b0; b < b1; ++b) mine += bc[b];
+  int incl = mine;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) { const int v = __shfl_up(incl, o); if (lane >= o) incl += v; }
+  const int total = __shfl(incl, 63);
+  int run = incl - mine;
+  for (int b = b0; b < b1; ++b) { const int c = bc[b]; bc[b] = run; run += c; }
+  if (lane != 0) return;
   u_prev[h] = s.ucount;
-  s.ucount = run;
+  s.ucount = total;
   s.ccount += s.m_t;
   s.stage += 1;
   s.stage_offs[s.stage] = s.ccount;
-  s.u_hist[s.stage] = run;
+  s.u_hist[s.stage] = total;
   st[h] = s;
 }
 
