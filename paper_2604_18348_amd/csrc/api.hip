@@ -510,9 +510,13 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
                      nullptr, 0, w.perm_k, w.offs_k, D.cap + 1, w.sort, w.poff, reduce_part_rows(), &poff_done));
   // the key permutation is final here: work that needs nothing else of the clustering may start
   if (sorted_ev && hipEventRecord(sorted_ev, st) != hipSuccess) return fail(ADACLUSTER_E_INTERNAL, "stream fork failed");
-  prof_mark(EV_KSORT, st);
   const int want_box = (k_bmin && k_bmax) ? 1 : 0;
   const int P = parts_for(D.N, D.cap);
+  if (!poff_done) {       // the cut into reduction parts belongs to the sort's side of the profile mark
+    RET_IF(launch_part_scan(st, D.H, D.N, 2, 0, D.cap, P, w.kstate, w.offs_k, D.cap + 1, w.poff, w.pcl));
+    poff_done = 2;
+  }
+  prof_mark(EV_KSORT, st);
   RET_IF(launch_seg_reduce(st, p->dtype, D.d, D.H, D.N, 2, 0, D.cap, P, w.kstate, 0, want_box, K, w.perm_k, w.offs_k,
                            D.cap + 1, w.poff, w.pcl, w.psum, w.pnorm, w.pmin, w.pmax, poff_done));
   prof_mark(EV_KREDUCE, st, EV_KSORT);

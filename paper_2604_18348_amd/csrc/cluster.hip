@@ -1855,8 +1855,10 @@ int launch_seg_reduce(hipStream_t s, int dtype, int d, int H, int N, int mode, i
                       const int32_t* offs, int offs_stride, int32_t* poff, int32_t* pcl, float* psum, float* pnorm,
                       float* pmin, float* pmax, int poff_ready) {
   ReduceCfg c{mode, m_const, N, P, m_bound, st, normalize, want_box};
+  // poff_ready: 0 the parts are cut here; 1 the one-launch sort of small heads has cut them (and left no part ->
+  // cluster table); 2 launch_part_scan has
   if (!poff_ready) part_scan<<<H, 1024, 0, s>>>(c, offs, offs_stride, poff, pcl);
-  else pcl = nullptr;                  // (the one-launch sort of small heads cuts the parts itself and leaves no table)
+  else if (poff_ready == 1) pcl = nullptr;
   dim3 g(P, H);
   if (dtype == ADACLUSTER_BF16) {
     if (d == 64) seg_reduce<bf16raw, 64><<<g, 64, 0, s>>>((const bf16raw*)X, c, perm, offs, offs_stride, poff, pcl, psum, pnorm, pmin, pmax);
@@ -1865,6 +1867,13 @@ int launch_seg_reduce(hipStream_t s, int dtype, int d, int H, int N, int mode, i
     if (d == 64) seg_reduce<float, 64><<<g, 64, 0, s>>>((const float*)X, c, perm, offs, offs_stride, poff, pcl, psum, pnorm, pmin, pmax);
     else seg_reduce<float, 128><<<g, 64, 0, s>>>((const float*)X, c, perm, offs, offs_stride, poff, pcl, psum, pnorm, pmin, pmax);
   }
+  return chk();
+}
+
+int launch_part_scan(hipStream_t s, int H, int N, int mode, int m_const, int m_bound, int P, const KState* st,
+                     const int32_t* offs, int offs_stride, int32_t* poff, int32_t* pcl) {
+  ReduceCfg c{mode, m_const, N, P, m_bound, st, 0, 0};
+  part_scan<<<H, 1024, 0, s>>>(c, offs, offs_stride, poff, pcl);
   return chk();
 }
 

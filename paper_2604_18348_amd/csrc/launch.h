@@ -33,6 +33,9 @@ int launch_seg_reduce(hipStream_t s, int dtype, int d, int H, int N, int mode, i
                       const int32_t* offs, int offs_stride, int32_t* poff, int32_t* pcl, float* psum, float* pnorm, float* pmin,
                       float* pmax, int poff_ready = 0);
 int reduce_part_rows();
+// Cuts the clusters of a sorted head into reduction parts on its own (launch_seg_reduce then takes poff_ready = 2).
+int launch_part_scan(hipStream_t s, int H, int N, int mode, int m_const, int m_bound, int P, const KState* st,
+                     const int32_t* offs, int offs_stride, int32_t* poff, int32_t* pcl);
 int launch_finalize(hipStream_t s, int dtype, int d, int H, int mode, int m_const, int m_bound, int P, int cap,
                     int master_stride, const KState* st, int spherical, int update_assign, int want_box,
                     const int32_t* offs, int offs_stride, const int32_t* poff, const float* psum, const float* pnorm,
