@@ -836,8 +836,9 @@ struct FinalizeCfg {
   int nb_const;                           // > 0: that many blocks (walks of the one-read query pass), whatever the state says
 };
 
+constexpr int FIN_ROWS = 4;           // clusters per workgroup, one wave each (no step needs the workgroup)
 template <int D>
-__global__ __launch_bounds__(64) void finalize_centroids(FinalizeCfg cfg, const int32_t* __restrict__ offs,
+__global__ __launch_bounds__(64 * FIN_ROWS) void finalize_centroids(FinalizeCfg cfg, const int32_t* __restrict__ offs,
                                                          int offs_stride, const int32_t* __restrict__ poff,
                                                          const float* __restrict__ psum,
                                                          const float* __restrict__ pnorm,
@@ -849,7 +850,7 @@ __global__ __launch_bounds__(64) void finalize_centroids(FinalizeCfg cfg, const 
                                                          int32_t* __restrict__ out_sizes, float* __restrict__ out_mean_norm,
                                                          float* __restrict__ out_bmin, float* __restrict__ out_bmax) {
   constexpr int CPL = D / 64;          // columns per lane
-  const int h = blockIdx.y, j = blockIdx.x, lane = threadIdx.x;
+  const int h = blockIdx.y, j = blockIdx.x * FIN_ROWS + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   int m, row_off = 0;
   if (cfg.mode == 0) m = cfg.m_const;
   else {
@@ -1887,13 +1888,13 @@ int launch_finalize(hipStream_t s, int dtype, int d, int H, int mode, int m_cons
   FinalizeCfg c{mode, m_const, P, m_bound, cap, master_stride, st, spherical, update_assign,
                 dtype == ADACLUSTER_BF16, want_box, blk_cnt, nb_stride, nb_const};
   // in final mode every row of the output (up to cap) gets a size, so cover cap rows
-  dim3 g(update_assign ? m_bound : cap, H);
+  dim3 g(((update_assign ? m_bound : cap) + FIN_ROWS - 1) / FIN_ROWS, H);
   if (d == 64)
-    finalize_centroids<64><<<g, 64, 0, s>>>(c, offs, offs_stride, poff, psum, pnorm, pmin, pmax, master, assign_lp,
+    finalize_centroids<64><<<g, 64 * FIN_ROWS, 0, s>>>(c, offs, offs_stride, poff, psum, pnorm, pmin, pmax, master, assign_lp,
                                             assign_f32, bias, out_cent, fallback, out_sizes, out_mean_norm,
                                             out_bmin, out_bmax);
   else
-    finalize_centroids<128><<<g, 64, 0, s>>>(c, offs, offs_stride, poff, psum, pnorm, pmin, pmax, master, assign_lp,
+    finalize_centroids<128><<<g, 64 * FIN_ROWS, 0, s>>>(c, offs, offs_stride, poff, psum, pnorm, pmin, pmax, master, assign_lp,
                                              assign_f32, bias, out_cent, fallback, out_sizes, out_mean_norm,
                                              out_bmin, out_bmax);
   return chk();
