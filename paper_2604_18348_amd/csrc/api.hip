@@ -464,7 +464,7 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
       const bool update = it < p->k_iters - 1;
       if (block_sums && update) {
         RET_IF(launch_assign(st, p->dtype, D.d, D.H, D.N, n_bound, 1, 0, D.cap, w.kstate, ul, K, w.cent_lp, w.bias,
-                             w.labels_tmp, w.dist2, w.bsum, w.bcnt, Pb));
+                             w.labels_tmp, nullptr, w.bsum, w.bcnt, Pb));        // (distances: last pass only)
         RET_IF(launch_finalize(st, p->dtype, D.d, D.H, 1, 0, m_bound, Pb, D.cap, p->k_m0, w.kstate, 0, 1, 0,
                                nullptr, 0, nullptr, w.bsum, w.pnorm, w.pmin, w.pmax, w.master, w.cent_lp,
                                k_assign, w.bias, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, w.bcnt, nblk));
@@ -474,7 +474,8 @@ int run_kcluster(const adacluster_params* p, const WS& w, hipStream_t st, const 
       // it keeps a copy of its labels and best scores, which the final pass starts from)
       const bool keep = seeded && t == 0 && !update;
       RET_IF(launch_assign(st, p->dtype, D.d, D.H, D.N, n_bound, 1, 0, D.cap, w.kstate, ul, K, w.cent_lp, w.bias,
-                           w.labels_tmp, w.dist2, nullptr, nullptr, 0, keep ? w.lab0 : nullptr, keep ? w.score0 : nullptr));
+                           w.labels_tmp, update ? nullptr : w.dist2, nullptr, nullptr, 0, keep ? w.lab0 : nullptr,
+                           keep ? w.score0 : nullptr));
       if (update && direct_update_fits(p->dtype, n_bound, m_bound)) {
         // few points (fp32): every centre gathers its members from the label list itself, one launch
         RET_IF(launch_update_direct(st, D.d, D.H, D.N, m_bound, D.cap, p->k_m0, w.kstate, w.labels_tmp, ul, K, w.master,

@@ -103,11 +103,17 @@ __global__ __launch_bounds__(256, (ACC && D == 128) ? 1 : 2) void assign_mfma(co
       for (int ks = 0; ks < KS; ++ks) {
         const uint4 raw = *reinterpret_cast<const uint4*>(row + ks * 16);
         xf[pb][ks] = *reinterpret_cast<const bf16x8_t*>(&raw);
-        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+      }
+      if (dist2) {                       // ||x||^2 is only needed for the distances
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const float a = __uint_as_float(w[q] << 16), b = __uint_as_float(w[q] & 0xFFFF0000u);
-          ss = fmaf(a, a, ss); ss = fmaf(b, b, ss);
+        for (int ks = 0; ks < KS; ++ks) {
+          const uint4 raw = *reinterpret_cast<const uint4*>(&xf[pb][ks]);
+          const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const float a = __uint_as_float(w[q] << 16), b = __uint_as_float(w[q] & 0xFFFF0000u);
+            ss = fmaf(a, a, ss); ss = fmaf(b, b, ss);
+          }
         }
       }
     } else {
