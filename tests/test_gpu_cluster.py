@@ -243,6 +243,34 @@ def test_kcluster_fp32_sorted_and_direct_updates():
     assert (np.diff(so[1]) > 0).sum() >= 2, so          # the diffuse head ran at least two stages
 
 
+def test_kcluster_fp32_direct_update_scans_in_rounds():
+    """A first stage of 9 500 fp32 points goes through the one-launch update in three scan rounds.  With two
+    passes the stage centres are the member means over the labels of pass 1, which are arg-mins to the strided
+    sample: recomputed here in fp64, centres that a near-tied point may have joined or left aside."""
+    from tests.helpers import REL_TIE
+    H, N, d, m0 = 1, 9500, 64, 12
+    _, K, _ = wl.make_small(33, N, d, 10, dtype="f32", H=H)
+    p = B.Params(H=H, N=N, d=d, dtype=B.F32, q_clusters=4, k_iters=2, k_m0=m0, k_m_min=4, k_max_clusters=48,
+                 tau_factor=1.0, min_unassigned_frac=0.02)
+    out = B.adacluster_kcluster(p, to_dev(K, B.F32))
+    torch.cuda.synchronize()
+    check_kcluster(K, p, out, B.F32)
+    X = K[0].astype(np.float64)
+    C0 = X[orc.strided_indices(N, m0)]
+    G = (C0 * C0).sum(1)[None] - 2.0 * X @ C0.T
+    order = np.argsort(G, axis=1)[:, :2]
+    rows = np.arange(N)
+    tied = (G[rows, order[:, 1]] - G[rows, order[:, 0]]) <= REL_TIE * ((X * X).sum(1) + (C0 * C0).sum(1)[order[:, 0]])
+    strict = np.ones(m0, dtype=bool)
+    strict[order[tied].ravel()] = False
+    lab = order[:, 0]
+    assert np.bincount(lab, minlength=m0).min() > 0
+    means = np.stack([X[lab == j].mean(0) for j in range(m0)])
+    got = to_np(out["k_assign_centroids"])[0, :m0]
+    assert strict.sum() >= m0 // 2, strict            # the check covers most centres
+    assert np.allclose(got[strict], means[strict], atol=2e-5, rtol=1e-5), float(np.abs(got - means)[strict].max())
+
+
 def test_kcluster_more_than_128_stage_centres():
     """Stage centre counts above 128 need two radix passes of the label sort, here inside the
     one-workgroup-per-head kernels (small heads)."""
