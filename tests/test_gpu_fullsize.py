@@ -3,7 +3,8 @@ benchmark times (same H, N, d, parameters), checked on outputs the oracle comput
 every head: labels are the arg-min / arg-max to the reported centres (all tokens of three heads,
 1024 sampled tokens of the others), the selections of all query clusters are bit-exact given the
 GPU's centroids, and 64 sampled output rows per head equal the fp64 softmax over the keys of the
-selected clusters (1e-2 relative L2 / 2e-2 max-abs for bf16)."""
+selected clusters (1e-2 relative L2 / 2e-2 max-abs for bf16).  The warm-started call is checked the same
+way at the 75.6K-token configuration."""
 from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
@@ -72,6 +73,34 @@ def test_fullsize_sampled_parity(name):
     outs = B.alloc_outputs(p, "cuda")
     O = B.adacluster_attn(p, Q, K, V, outs=outs)
     torch.cuda.synchronize()
+    verify(name, variant, cfg, p, Q, K, V, outs, O)
+
+
+def test_fullsize_warm_start_parity():
+    """The warm-started call at the 75.6K-token configuration, as the benchmark times it (previous centres and
+    counts as the start, two passes each, on inputs that have drifted a little): same checks as the cold call.
+    The selection step here sizes its LDS for N_max + m0 clusters, and the assignment runs against every centre
+    of the previous call."""
+    import dataclasses
+    cfg, Q, K, V = gen("c4")
+    H, N, d = Q.shape
+    p = B.Params(H=H, N=N, d=d, dtype=B.BF16, **cfg["params"])
+    outs = B.alloc_outputs(p, "cuda")
+    B.adacluster_attn(p, Q, K, V, outs=outs)
+    torch.cuda.synchronize()
+    kc_cold = outs["k_count"].cpu().numpy().copy()
+    g = torch.Generator(device="cuda"); g.manual_seed(11)
+    Q2 = (Q.float() + 0.05 * torch.randn(Q.shape, device="cuda", generator=g)).to(Q.dtype)
+    K2 = (K.float() + 0.05 * torch.randn(K.shape, device="cuda", generator=g)).to(K.dtype)
+    pw = dataclasses.replace(p, q_init_mode=1, k_init_mode=1, q_iters=2, k_iters=2)
+    O = B.adacluster_attn(pw, Q2, K2, V, outs=outs)
+    torch.cuda.synchronize()
+    assert np.array_equal(outs["k_count"].cpu().numpy(), kc_cold)         # the count is carried over
+    verify("c4 warm", "", cfg, pw, Q2, K2, V, outs, O)
+
+
+def verify(name, variant, cfg, p, Q, K, V, outs, O):
+    H, N, d = Q.shape
     kc = outs["k_count"].cpu().numpy()
     full = outs["full_flag"].cpu().numpy()
     print(name, "k_count min/mean/max", kc.min(), kc.mean(), kc.max(), "full heads", int(full.sum()),
