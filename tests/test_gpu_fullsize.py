@@ -19,6 +19,10 @@ from tests.helpers import REL_TIE, sel_from_dev, to_np
 pytestmark = pytest.mark.gpu
 
 
+import functools
+
+
+@functools.lru_cache(maxsize=None)
 def gen(name):
     cfg = wl.CONFIGS[name]
     H, N, d = cfg["H"], wl.n_tokens(cfg), cfg["d"]
@@ -97,6 +101,31 @@ def test_fullsize_warm_start_parity():
     torch.cuda.synchronize()
     assert np.array_equal(outs["k_count"].cpu().numpy(), kc_cold)         # the count is carried over
     verify("c4 warm", "", cfg, pw, Q2, K2, V, outs, O)
+
+
+@pytest.mark.parametrize("name", ["c4", "c5"])
+def test_fullsize_dense_rows(name):
+    """The dense call that the benchmark times beside the sparse one, at the same sizes: sampled output rows
+    of the first, the middle and the last head against the fp64 softmax over all keys."""
+    cfg, Q, K, V = gen(name)
+    H, N, d = Q.shape
+    p = B.Params(H=H, N=N, d=d, dtype=B.BF16, **cfg["params"])
+    O = B.adacluster_dense_attn(p, Q, K, V)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(3)
+    scale = float(np.float32(1.0 / np.sqrt(np.float32(d))))
+    for h in sorted(set([0, H // 2, H - 1])):
+        rows = np.sort(rng.choice(N, size=24, replace=False))
+        rows[0], rows[-1] = 0, N - 1
+        k64 = K[h].float().cpu().numpy().astype(np.float64)
+        v64 = V[h].float().cpu().numpy().astype(np.float64)
+        q64 = Q[h][torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
+        ref = orc.dense_attention(q64, k64, v64, scale)
+        got = O[h][torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
+        rel = float(np.linalg.norm(got - ref) / np.linalg.norm(ref))
+        mx = float(np.abs(got - ref).max())
+        print(name, "dense head", h, "rows rel", rel, "max", mx, flush=True)
+        assert rel < 1e-2 and mx < 2e-2
 
 
 def verify(name, variant, cfg, p, Q, K, V, outs, O):
