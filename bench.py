@@ -24,7 +24,7 @@ sys.path.insert(0, ROOT)
 # reads for a plain copy of known size) + WRITE_SIZE of the two rocprofv3 --pmc passes summarised in
 # profiles/attn_pipeline_<config>.txt.  A counter cannot be read from inside this script, so the
 # figures are stored; a config without a profile reports null.
-PROFILED_ATTN_TRAFFIC_BYTES = {"c2": 963.3e6, "c3": 293.7e6, "c4": 3102.8e6, "c5": 4492.3e6}
+PROFILED_ATTN_TRAFFIC_BYTES = {"c2": 960.3e6, "c3": 293.2e6, "c4": 3100.6e6, "c5": 4493.1e6}
 
 
 def cpu_baseline(name, wl, target_s=15.0):
