@@ -62,10 +62,12 @@ __device__ __forceinline__ uint64_t order_key(double v) {
 // limit (a 16-byte broadcast read per two fused multiply-adds), with more rows the registers and the smaller
 // number of waves are.  The query values as scalar operands (scalar loads from a table prepared by another
 // kernel, no LDS) took 165 / 75 us: the scalar cache delivers far less than the LDS.
-constexpr int SCORE_QG = 13;       // query clusters per thread (65 = 5 groups)
+constexpr int SCORE_QG = 13;       // query clusters per thread (65 = 5 groups) ...
+constexpr int SCORE_QG_SMALL = 5;  // ... or 5 (13 groups) when the launch would otherwise leave SIMDs without a wave
 constexpr int SCORE_ROWS = 1;      // key clusters per thread
 constexpr int SCORE_THREADS = 128;
 
+template <int QG>
 __global__ __launch_bounds__(SCORE_THREADS) void score_kernel(SelectCfg cfg, const float* __restrict__ q_cent,
                                                               const float* __restrict__ k_cent,
                                                               const float* __restrict__ k_bmin,
@@ -74,7 +76,7 @@ __global__ __launch_bounds__(SCORE_THREADS) void score_kernel(SelectCfg cfg, con
                                                               const int32_t* __restrict__ k_count,
                                                               const int32_t* __restrict__ full_flag,
                                                               double* __restrict__ S) {
-  constexpr int QG = SCORE_QG, R = SCORE_ROWS;
+  constexpr int R = SCORE_ROWS;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   double2* qs = reinterpret_cast<double2*>(smem);            // [QG][d]
   const int h = blockIdx.z, i0 = blockIdx.y * QG, tid = threadIdx.x;
@@ -415,9 +417,17 @@ int launch_select(hipStream_t s, int H, int Cq, int cap, int d, int score_mode, 
     granted[dev].store((int)shm);
   }
   const int kb = kc_max < cap ? kc_max : cap;
-  score_kernel<<<dim3((kb + SCORE_ROWS * SCORE_THREADS - 1) / (SCORE_ROWS * SCORE_THREADS), (Cq + SCORE_QG - 1) / SCORE_QG, H),
-                 SCORE_THREADS, (size_t)SCORE_QG * d * sizeof(double2), s>>>(c, q_cent, k_cent, k_bmin, k_bmax, k_sizes, k_count,
-                                                                            full_flag, scores);
+  const int kblocks = (kb + SCORE_ROWS * SCORE_THREADS - 1) / (SCORE_ROWS * SCORE_THREADS);
+  // 1024 SIMDs: with fewer than two waves each the larger grid of the small group size is the faster one
+  const bool small_groups = (long long)kblocks * ((Cq + SCORE_QG - 1) / SCORE_QG) * H * (SCORE_THREADS / 64) < 2048;
+  if (small_groups)
+    score_kernel<SCORE_QG_SMALL><<<dim3(kblocks, (Cq + SCORE_QG_SMALL - 1) / SCORE_QG_SMALL, H), SCORE_THREADS,
+                                   (size_t)SCORE_QG_SMALL * d * sizeof(double2), s>>>(c, q_cent, k_cent, k_bmin, k_bmax, k_sizes,
+                                                                                     k_count, full_flag, scores);
+  else
+    score_kernel<SCORE_QG><<<dim3(kblocks, (Cq + SCORE_QG - 1) / SCORE_QG, H), SCORE_THREADS,
+                             (size_t)SCORE_QG * d * sizeof(double2), s>>>(c, q_cent, k_cent, k_bmin, k_bmax, k_sizes, k_count,
+                                                                         full_flag, scores);
   select_kernel<<<dim3(Cq, H), 256, shm, s>>>(c, scores, q_mean_norm, k_sizes, k_count, full_flag, sel_idx, sel_cnt);
   return hipGetLastError() == hipSuccess ? 0 : ADACLUSTER_E_INTERNAL;
 }
